@@ -1,0 +1,312 @@
+"""Pins for the CPU oracle: each test holds oracle/ to something other than itself.
+
+What fixes the expected value in each test is named in its docstring: a library
+routine (scipy softmax, torch scaled_dot_product_attention, scipy.cluster.vq.vq),
+a closed form, an invariant, or brute force written with different machinery
+(vectorised numpy gathers instead of loops).  None of them needs a GPU.
+"""
+import os
+
+import numpy as np
+import pytest
+import scipy.cluster.vq
+import scipy.special
+import torch
+
+from oracle import pq_oracle as O
+from synth import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def small(seed=0, B=2, Hq=4, Hkv=4, d=16, M=8, N=37, R=5, dtype="f32", lens=None):
+    w = W.Workload("t", B, Hq, Hkv, d, M, N, dtype, recent_cap=max(R, 0), recent_fixed=R if R > 0 else None,
+                   seed=1000 + seed, ctx_lens=lens)
+    return w, W.generate(w)
+
+
+def brute_force(data, scale, b, hq, G=1):
+    """Dense attention over explicitly decoded K/V with library softmax (scipy)."""
+    hkv = hq // G
+    N = int(data["ctx_len"][b])
+    kc = data["k_codes"][b, hkv, :N].astype(np.int64)          # [N, M]
+    vc = data["v_codes"][b, hkv, :N].astype(np.int64)
+    kcb = data["k_codebook"][hkv].astype(np.float64)           # [M, C, ds]
+    vcb = data["v_codebook"][hkv].astype(np.float64)
+    M = kc.shape[1]
+    sub = np.arange(M)[None, :]
+    K = kcb[sub, kc].reshape(N, -1)                             # gather + concatenate (Eq. 5)
+    V = vcb[sub, vc].reshape(N, -1)
+    R = int(data["recent_len"][b])
+    if R:
+        K = np.concatenate([K, data["recent_k"][b, hkv, :R].astype(np.float64)])
+        V = np.concatenate([V, data["recent_v"][b, hkv, :R].astype(np.float64)])
+    s = (K @ data["q"][b, hq].astype(np.float64)) * float(np.float32(scale))
+    return scipy.special.softmax(s) @ V
+
+
+def run_oracle(w, data, **kw):
+    return O.decode(data["q"], data["k_codes"], data["v_codes"], data["ctx_len"], data["k_codebook"],
+                    data["v_codebook"], data["recent_k"], data["recent_v"], data["recent_len"],
+                    scale=W.attention_scale(w), **kw)
+
+
+@pytest.mark.parametrize("seed,dtype,M,R", [(0, "f32", 8, 5), (1, "f16", 4, 0), (2, "f16", 16, 9), (3, "f32", 2, 1)])
+def test_decode_matches_brute_force_library_softmax(seed, dtype, M, R):
+    """Brute force on tiny inputs: numpy gather + scipy.special.softmax."""
+    w, data = small(seed, d=16, M=M, R=R, dtype=dtype, lens=(37, 11))
+    out = run_oracle(w, data)
+    for b in range(w.batch):
+        for h in range(w.n_q_heads):
+            np.testing.assert_allclose(out[b, h], brute_force(data, W.attention_scale(w), b, h), rtol=1e-12,
+                                       atol=1e-14)
+
+
+def test_decode_reduces_to_dense_attention_when_codebook_holds_the_vectors():
+    """Special case that is textbook attention: centroid t of every subspace is the
+    t-th source sub-vector and code[t, i] = t, so K^ = K and V^ = V exactly; the
+    expected value comes from torch's scaled_dot_product_attention in float64."""
+    rng = np.random.default_rng(5)
+    B, H, d, M, N = 1, 3, 32, 8, 200
+    ds = d // M
+    K = rng.standard_normal((H, N, d))
+    V = rng.standard_normal((H, N, d))
+    q = rng.standard_normal((B, H, d))
+    kcb = np.zeros((H, M, 256, ds))
+    vcb = np.zeros((H, M, 256, ds))
+    kcb[:, :, :N, :] = K.reshape(H, N, M, ds).transpose(0, 2, 1, 3)
+    vcb[:, :, :N, :] = V.reshape(H, N, M, ds).transpose(0, 2, 1, 3)
+    codes = np.broadcast_to(np.arange(N, dtype=np.uint8)[None, None, :, None], (B, H, N, M)).copy()
+    scale = np.float32(1 / np.sqrt(d))
+    out = O.decode(q, codes, codes, np.array([N], np.int32), kcb, vcb, scale=scale)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q).reshape(1, H, 1, d), torch.from_numpy(K)[None], torch.from_numpy(V)[None],
+        scale=float(scale)).reshape(H, d).numpy()
+    np.testing.assert_allclose(out[0], ref, rtol=1e-11, atol=1e-13)
+
+
+def test_hand_worked_example_from_golden_file():
+    """Closed form: softmax([0, ln 3]) = [1/4, 3/4]; derivation in the fixture."""
+    vals = {}
+    for line in open(os.path.join(GOLDEN, "hand_worked_attention.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, *v = line.split()
+        vals[k] = np.array([float(x) for x in v])
+    kcb = np.zeros((1, 2, 2, 1)); kcb[0, 0, :, 0] = [0, 1]; kcb[0, 1, :, 0] = [0, 2]
+    vcb = np.zeros((1, 2, 2, 1)); vcb[0, 0, :, 0] = [1, 5]; vcb[0, 1, :, 0] = [-2, 2]
+    kc = np.array([[[[0, 1], [1, 0]]]], np.uint8)
+    vc = np.array([[[[0, 1], [1, 0]]]], np.uint8)
+    scale = np.float32(1 / np.sqrt(2.0))
+    # q chosen so that float(scale) * q[0] * 1 == ln 3 to the last bit that matters
+    q = np.array([[[np.log(3.0) / float(scale), 0.0]]])
+    out = O.decode(q, kc, vc, np.array([2], np.int32), kcb, vcb, scale=scale)
+    np.testing.assert_allclose(out[0, 0], vals["out_no_recent"], rtol=1e-14)
+    _, wts = O.dense_attention(q[0, 0], O.dequantize(kc[0, 0], kcb[0]), O.dequantize(vc[0, 0], vcb[0]), scale)
+    np.testing.assert_allclose(wts, vals["weights_no_recent"], rtol=1e-14)
+    rk = np.array([[[[2.0, 7.0]]]]); rv = np.array([[[[-8.0, 11.0]]]])
+    out = O.decode(q, kc, vc, np.array([2], np.int32), kcb, vcb, rk, rv, np.array([1], np.int32), scale=scale)
+    np.testing.assert_allclose(out[0, 0], vals["out_with_recent"], rtol=1e-14)
+
+
+def test_softmax_weights_sum_to_one_and_output_in_convex_hull():
+    """Invariants of softmax attention: weights sum to 1; each output coordinate lies
+    between the minimum and maximum of that coordinate over the value rows."""
+    w, data = small(7, B=3, Hq=4, Hkv=4, d=32, M=16, N=300, R=12, lens=(300, 1, 77))
+    out, wsum = run_oracle(w, data, return_weight_sum=True)
+    np.testing.assert_allclose(wsum, 1.0, rtol=0, atol=1e-14)
+    for b in range(w.batch):
+        for h in range(w.n_q_heads):
+            N, R = data["ctx_len"][b], data["recent_len"][b]
+            V = np.concatenate([O.dequantize(data["v_codes"][b, h, :N], data["v_codebook"][h]),
+                                data["recent_v"][b, h, :R].astype(np.float64)])
+            assert (out[b, h] <= V.max(0) + 1e-12).all() and (out[b, h] >= V.min(0) - 1e-12).all()
+
+
+def test_adding_a_constant_to_all_scores_changes_nothing():
+    """Softmax shift invariance, exercised through the keys: adding a vector u to every
+    key adds the same q.u to every score.  Built with the codebook-holds-the-vectors case."""
+    rng = np.random.default_rng(11)
+    H, d, M, N = 1, 8, 4, 50
+    ds = d // M
+    K = rng.standard_normal((N, d)); V = rng.standard_normal((N, d)); q = rng.standard_normal((1, 1, d))
+    u = rng.standard_normal(d)
+    codes = np.broadcast_to(np.arange(N, dtype=np.uint8)[None, None, :, None], (1, 1, N, M)).copy()
+
+    def cb(X):
+        c = np.zeros((1, M, 256, ds)); c[0, :, :N, :] = X.reshape(N, M, ds).transpose(1, 0, 2); return c
+    a = O.decode(q, codes, codes, np.array([N], np.int32), cb(K), cb(V))
+    b = O.decode(q, codes, codes, np.array([N], np.int32), cb(K + u), cb(V))
+    np.testing.assert_allclose(a, b, rtol=1e-10, atol=1e-12)
+
+
+def test_zero_query_gives_mean_of_value_rows():
+    """Closed form: q = 0 makes every weight 1/n."""
+    w, data = small(3, B=1, Hq=2, Hkv=2, d=16, M=8, N=64, R=7)
+    data["q"][:] = 0
+    out = run_oracle(w, data)
+    for h in range(2):
+        V = np.concatenate([O.dequantize(data["v_codes"][0, h, :64], data["v_codebook"][h]),
+                            data["recent_v"][0, h, :7].astype(np.float64)])
+        np.testing.assert_allclose(out[0, h], V.mean(0), rtol=1e-13, atol=1e-15)
+
+
+def test_all_codes_equal_returns_that_decoded_value_row():
+    """Closed form: identical rows -> output is that row whatever the weights."""
+    w, data = small(4, B=1, Hq=1, Hkv=1, d=16, M=8, N=90, R=0)
+    data["v_codes"][:] = data["v_codes"][0, 0, 0]
+    out = run_oracle(w, data)
+    row = data["v_codebook"][0][np.arange(8), data["v_codes"][0, 0, 0].astype(int)].reshape(-1).astype(np.float64)
+    np.testing.assert_allclose(out[0, 0], row, rtol=1e-14)
+
+
+def test_single_token_returns_its_value_and_empty_sequence_returns_zeros():
+    """N = 1, R = 0 -> the decoded value row exactly; N + R = 0 -> zeros (documented reading)."""
+    w, data = small(5, B=2, Hq=1, Hkv=1, d=16, M=8, N=4, R=0, lens=(1, 0))
+    out, wsum = run_oracle(w, data, return_weight_sum=True)
+    row = data["v_codebook"][0][np.arange(8), data["v_codes"][0, 0, 0].astype(int)].reshape(-1).astype(np.float64)
+    assert (out[0, 0] == row).all()
+    assert (out[1, 0] == 0).all() and wsum[1, 0] == 0
+
+
+def test_dominant_key_selects_its_value_row():
+    """Limit: one score far above the rest -> the output tends to that value row."""
+    w, data = small(6, B=1, Hq=1, Hkv=1, d=16, M=8, N=40, R=3)
+    q = data["q"][0, 0].astype(np.float64)
+    data["recent_k"][0, 0, 1] = (q / np.linalg.norm(q) * 1e3).astype(np.float32)
+    out = run_oracle(w, data)
+    np.testing.assert_allclose(out[0, 0], data["recent_v"][0, 0, 1].astype(np.float64), rtol=1e-12, atol=1e-12)
+
+
+def test_token_permutation_invariance():
+    w, data = small(8, B=1, Hq=2, Hkv=2, d=16, M=8, N=120, R=0)
+    a = run_oracle(w, data)
+    perm = np.random.default_rng(0).permutation(120)
+    data["k_codes"] = data["k_codes"][:, :, perm]
+    data["v_codes"] = data["v_codes"][:, :, perm]
+    b = run_oracle(w, data)
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-14)
+
+
+def test_moving_a_token_from_codes_to_recent_window_changes_nothing():
+    """One softmax over the concatenation (reading of Eq. 7's two terms): a token may sit
+    in the quantized part or, with its decoded rows, in the full-precision part."""
+    w, data = small(9, B=1, Hq=2, Hkv=2, d=16, M=8, N=50, R=4, dtype="f32")
+    a = run_oracle(w, data)
+    moved = dict(data)
+    R0 = 4
+    rk = np.full((1, 2, 6, 16), np.nan, np.float64); rv = rk.copy()
+    rk[:, :, :R0] = data["recent_k"][:, :, :R0]; rv[:, :, :R0] = data["recent_v"][:, :, :R0]
+    for h in range(2):
+        rk[0, h, R0] = O.dequantize(data["k_codes"][0, h, 49:50], data["k_codebook"][h])[0]
+        rv[0, h, R0] = O.dequantize(data["v_codes"][0, h, 49:50], data["v_codebook"][h])[0]
+    moved.update(recent_k=rk, recent_v=rv, recent_len=np.array([R0 + 1], np.int32), ctx_len=np.array([49], np.int32))
+    b = run_oracle(w, moved)
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-14)
+
+
+def test_gqa_equals_mha_with_replicated_kv_heads():
+    """Query head h reads KV head h // G (contiguous groups)."""
+    G = 4
+    w = W.Workload("g", 2, 8, 2, 16, 8, 60, "f16", recent_cap=6, recent_fixed=6, seed=77)
+    data = W.generate(w)
+    a = run_oracle(w, data)
+    rep = dict(data)
+    for k in ("k_codes", "v_codes", "recent_k", "recent_v"):
+        rep[k] = np.repeat(data[k], G, axis=1)
+    for k in ("k_codebook", "v_codebook"):
+        rep[k] = np.repeat(data[k], G, axis=0)
+    b = run_oracle(w, rep)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_batch_rows_are_independent_and_pairs_subset_matches():
+    w, data = small(10, B=3, Hq=2, Hkv=2, d=16, M=8, N=33, R=2, lens=(33, 5, 20))
+    full = run_oracle(w, data)
+    part = run_oracle(w, data, pairs=[(1, 1), (2, 0)])
+    assert (part[1, 1] == full[1, 1]).all() and (part[2, 0] == full[2, 0]).all()
+    assert np.isnan(part[0, 0]).all()
+    alone = {k: (v[1:2] if (v is not None and k not in ("k_codebook", "v_codebook")) else v) for k, v in data.items()}
+    w1 = W.scaled(w, batch=1)
+    np.testing.assert_array_equal(run_oracle(w1, alone)[0], full[1])
+
+
+def test_table_sum_form_equals_dequantized_form():
+    """Eq. 7's identity: q.K^_t equals the sum over subspaces of table entries
+    LUT[i][code] with LUT[i] = q^i . (C_K^i)^T, here evaluated in double with einsum."""
+    w, data = small(12, B=1, Hq=1, Hkv=1, d=32, M=16, N=500, R=0)
+    q = data["q"][0, 0].astype(np.float64)
+    kcb = data["k_codebook"][0].astype(np.float64)
+    lut = np.einsum("ij,icj->ic", q.reshape(16, 2), kcb)
+    codes = data["k_codes"][0, 0].astype(int)
+    s_table = lut[np.arange(16)[None, :], codes].sum(1) * float(W.attention_scale(w))
+    p = scipy.special.softmax(s_table)
+    _, wts = O.dense_attention(q, O.dequantize(data["k_codes"][0, 0], kcb),
+                               O.dequantize(data["v_codes"][0, 0], data["v_codebook"][0]), W.attention_scale(w))
+    np.testing.assert_allclose(wts, p, rtol=1e-11)
+
+
+# --------------------------------------------------------------------------- encode
+
+
+def test_encode_matches_library_vector_quantizer():
+    """scipy.cluster.vq.vq is a library nearest-centroid routine (random data: no ties)."""
+    w = W.Workload("e", 2, 3, 3, 16, 4, 8, "f32", n_new=8, seed=21)
+    data = W.generate(w)
+    codes = O.encode(data["new_k"], data["k_codebook"])
+    ds = 4
+    for b in range(2):
+        for h in range(3):
+            for i in range(4):
+                obs = data["new_k"][b, h, :, i * ds:(i + 1) * ds].astype(np.float64)
+                ref, _ = scipy.cluster.vq.vq(obs, data["k_codebook"][h, i].astype(np.float64))
+                np.testing.assert_array_equal(codes[b, h, :, i], ref)
+
+
+def test_encode_matches_vectorised_argmin_fp16():
+    """Brute force with numpy broadcasting; np.argmin returns the first (lowest) index."""
+    w = W.Workload("e", 1, 2, 2, 32, 8, 20, "f16", n_new=20, seed=22)
+    data = W.generate(w)
+    codes = O.encode(data["new_v"], data["v_codebook"])
+    x = data["new_v"].astype(np.float64).reshape(1, 2, 20, 8, 1, 4)
+    cb = data["v_codebook"].astype(np.float64)[None, :, None]          # [1,H,1,M,C,ds]
+    diff = x - cb
+    dist = diff[..., 0] ** 2
+    for j in range(1, 4):
+        dist = dist + diff[..., j] ** 2
+    np.testing.assert_array_equal(codes, dist.argmin(-1).astype(np.uint8))
+
+
+def test_encode_exact_hit_duplicates_and_roundtrip():
+    """Distance 0 wins; a duplicated centroid row resolves to the lowest index;
+    encode(decode(codes)) == codes when centroids are pairwise distinct."""
+    rng = np.random.default_rng(3)
+    H, M, ds = 2, 4, 2
+    cb = rng.standard_normal((H, M, 256, ds)).astype(np.float16)
+    codes = rng.integers(0, 256, size=(1, H, 50, M), dtype=np.uint8)
+    # make centroids pairwise distinct per (head, subspace) for the round trip
+    for h in range(H):
+        for i in range(M):
+            assert len({tuple(r) for r in cb[h, i].tolist()}) == 256
+    x = np.stack([O.dequantize(codes[0, h], cb[h]) for h in range(H)])[None]
+    np.testing.assert_array_equal(O.encode(x, cb), codes)
+    # duplicate: centroid 200 becomes a copy of centroid 17, and 3 a copy of 250
+    cb2 = cb.copy()
+    cb2[:, :, 200] = cb2[:, :, 17]
+    cb2[:, :, 3] = cb2[:, :, 250]
+    c17 = np.full((1, H, 1, M), 200, np.uint8)
+    x17 = np.stack([O.dequantize(c17[0, h], cb2[h]) for h in range(H)])[None]
+    assert (O.encode(x17, cb2) == 17).all()
+    c250 = np.full((1, H, 1, M), 250, np.uint8)
+    x250 = np.stack([O.dequantize(c250[0, h], cb2[h]) for h in range(H)])[None]
+    assert (O.encode(x250, cb2) == 3).all()
+
+
+def test_encode_equidistant_tie_goes_to_lowest_index():
+    """Two different centroids at exactly the same distance: x = 0 between +a and -a."""
+    cb = np.full((1, 1, 256, 2), 100.0)
+    cb[0, 0, 9] = [0.5, -0.25]
+    cb[0, 0, 4] = [-0.5, 0.25]
+    cb[0, 0, 77] = [0.25, 0.5]     # same norm, third tie
+    x = np.zeros((1, 1, 1, 2))
+    assert O.encode(x, cb)[0, 0, 0, 0] == 4
