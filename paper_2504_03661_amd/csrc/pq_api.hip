@@ -1,0 +1,334 @@
+// C ABI of libpq_attn: argument checks, context life cycle, launch plumbing.
+// Every step of the path runs in the kernels; this file only validates and launches.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "pq_internal.h"
+
+namespace {
+
+constexpr float LOG2E = 1.44269504088896340736f;
+
+struct device_guard {
+    int prev = -1;
+    bool ok = false;
+    explicit device_guard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess)
+            return;
+        ok = (prev == dev) || (hipSetDevice(dev) == hipSuccess);
+    }
+    ~device_guard()
+    {
+        if (ok && prev >= 0)
+            (void)hipSetDevice(prev);
+    }
+};
+
+int validate(const pq_attn_config *c)
+{
+    if (c == nullptr)
+        return PQ_ERR_NULL;
+    if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->n_subspaces <= 0 ||
+        c->n_centroids <= 0 || c->max_context <= 0 || c->max_recent < 0 || c->device < 0 || c->n_splits < 0 ||
+        c->reserved != 0)
+        return PQ_ERR_SHAPE;
+    if (c->n_q_heads % c->n_kv_heads != 0 || c->head_dim % c->n_subspaces != 0)
+        return PQ_ERR_SHAPE;
+    if (c->dtype != PQ_F16 && c->dtype != PQ_F32)
+        return PQ_ERR_SHAPE;
+    if (c->n_centroids != 256 || c->head_dim != PQ_HEAD_DIM || (c->n_subspaces != 64 && c->n_subspaces != 32))
+        return PQ_ERR_UNSUPPORTED;
+    if (c->n_splits > PQ_MAX_SPLITS)
+        return PQ_ERR_UNSUPPORTED;
+    if ((int64_t)c->batch * c->n_q_heads * PQ_MAX_SPLITS > (int64_t)1 << 30)
+        return PQ_ERR_UNSUPPORTED;
+    return PQ_OK;
+}
+
+int64_t padded_capacity(const pq_attn_config *c) { return ((int64_t)c->max_context + 63) / 64 * 64; }
+
+// Splits per (sequence, query head): enough workgroups to give each of the chip's
+// compute units one (a workgroup's tables take most of a CU's LDS, so one is resident
+// at a time), but never so many that a split has less than a block per wavefront.
+int choose_splits(const pq_attn_config *c, int n_cu)
+{
+    const int64_t heads = (int64_t)c->batch * c->n_q_heads;
+    int64_t s = (n_cu + heads - 1) / heads;
+    const int64_t blocks = padded_capacity(c) / 64;
+    const int64_t max_by_work = blocks / 16 > 0 ? blocks / 16 : 1;
+    if (s > max_by_work)
+        s = max_by_work;
+    if (s > PQ_MAX_SPLITS)
+        s = PQ_MAX_SPLITS;
+    if (s < 1)
+        s = 1;
+    return (int)s;
+}
+
+int ensure_codebooks(pq_attn_ctx *ctx, const void *k, const void *v, hipStream_t s, bool force)
+{
+    if (k == nullptr && v == nullptr && !force)
+        return (ctx->reg_k && ctx->reg_v) ? PQ_OK : PQ_ERR_NULL;
+    if (k == nullptr || v == nullptr)
+        return PQ_ERR_NULL;
+    if (!force && k == ctx->reg_k && v == ctx->reg_v)
+        return PQ_OK;
+    if (pq_launch_pack_codebook(ctx, k, ctx->kcb_packed, s) != hipSuccess)
+        return PQ_ERR_HIP;
+    if (pq_launch_pack_codebook(ctx, v, ctx->vcb_packed, s) != hipSuccess)
+        return PQ_ERR_HIP;
+    ctx->reg_k = k;
+    ctx->reg_v = v;
+    return PQ_OK;
+}
+
+void free_ctx(pq_attn_ctx *ctx)
+{
+    if (ctx->kcb_packed) (void)hipFree(ctx->kcb_packed);
+    if (ctx->vcb_packed) (void)hipFree(ctx->vcb_packed);
+    if (ctx->partials) (void)hipFree(ctx->partials);
+    if (ctx->tickets) (void)hipFree(ctx->tickets);
+    if (ctx->dev_err) (void)hipFree(ctx->dev_err);
+    delete ctx;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pq_attn_validate_config(const pq_attn_config *cfg) { return validate(cfg); }
+
+int64_t pq_attn_codes_bytes(const pq_attn_config *cfg)
+{
+    const int rc = validate(cfg);
+    if (rc != PQ_OK)
+        return rc;
+    return (int64_t)cfg->batch * cfg->n_kv_heads * padded_capacity(cfg) * cfg->n_subspaces;
+}
+
+int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
+{
+    if (out == nullptr)
+        return PQ_ERR_NULL;
+    const int rc = validate(cfg);
+    if (rc != PQ_OK)
+        return rc;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || cfg->device >= n_dev) {
+        (void)hipGetLastError();
+        return PQ_ERR_HIP;
+    }
+    device_guard guard(cfg->device);
+    if (!guard.ok)
+        return PQ_ERR_HIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess)
+        return PQ_ERR_HIP;
+
+    pq_attn_ctx *ctx = new (std::nothrow) pq_attn_ctx();
+    if (ctx == nullptr)
+        return PQ_ERR_ALLOC;
+    ctx->cfg = *cfg;
+    ctx->ds = cfg->head_dim / cfg->n_subspaces;
+    ctx->group = cfg->n_q_heads / cfg->n_kv_heads;
+    ctx->cap_padded = padded_capacity(cfg);
+    ctx->elem_bytes = cfg->dtype == PQ_F16 ? 2 : 4;
+    ctx->n_splits = cfg->n_splits > 0 ? cfg->n_splits : choose_splits(cfg, prop.multiProcessorCount);
+
+    const size_t cb_bytes = (size_t)cfg->n_kv_heads * 256 * PQ_HEAD_DIM * ctx->elem_bytes;
+    const size_t n_bh = (size_t)cfg->batch * cfg->n_q_heads;
+    const size_t part_bytes = n_bh * ctx->n_splits * PQ_PART_STRIDE * sizeof(float);
+    bool ok = hipMalloc(&ctx->kcb_packed, cb_bytes) == hipSuccess;
+    ok = ok && hipMalloc(&ctx->vcb_packed, cb_bytes) == hipSuccess;
+    ok = ok && hipMalloc((void **)&ctx->partials, part_bytes) == hipSuccess;
+    ok = ok && hipMalloc((void **)&ctx->tickets, n_bh * sizeof(unsigned int)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&ctx->dev_err, sizeof(unsigned int)) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        free_ctx(ctx);
+        return PQ_ERR_ALLOC;
+    }
+    ok = hipMemset(ctx->tickets, 0, n_bh * sizeof(unsigned int)) == hipSuccess;
+    ok = ok && hipMemset(ctx->dev_err, 0, sizeof(unsigned int)) == hipSuccess;
+    ok = ok && hipMemset(ctx->partials, 0, part_bytes) == hipSuccess;
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        free_ctx(ctx);
+        return PQ_ERR_HIP;
+    }
+    *out = ctx;
+    return PQ_OK;
+}
+
+int pq_attn_destroy(pq_attn_ctx *ctx)
+{
+    if (ctx == nullptr)
+        return PQ_ERR_NULL;
+    device_guard guard(ctx->cfg.device);
+    if (!guard.ok)
+        return PQ_ERR_HIP;
+    const bool ok = hipDeviceSynchronize() == hipSuccess;
+    free_ctx(ctx);
+    return ok ? PQ_OK : PQ_ERR_HIP;
+}
+
+int pq_attn_n_splits(const pq_attn_ctx *ctx) { return ctx ? ctx->n_splits : PQ_ERR_NULL; }
+
+int pq_attn_set_codebooks(pq_attn_ctx *ctx, const void *k_codebook, const void *v_codebook, void *hip_stream)
+{
+    if (ctx == nullptr || k_codebook == nullptr || v_codebook == nullptr)
+        return PQ_ERR_NULL;
+    device_guard guard(ctx->cfg.device);
+    if (!guard.ok)
+        return PQ_ERR_HIP;
+    return ensure_codebooks(ctx, k_codebook, v_codebook, (hipStream_t)hip_stream, true);
+}
+
+int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, const uint8_t *v_codes,
+                   const int32_t *ctx_len, const void *k_codebook, const void *v_codebook, const void *recent_k,
+                   const void *recent_v, const int32_t *recent_len, float scale, float *out, void *hip_stream)
+{
+    if (ctx == nullptr || q == nullptr || k_codes == nullptr || v_codes == nullptr || ctx_len == nullptr ||
+        out == nullptr)
+        return PQ_ERR_NULL;
+    if ((recent_k == nullptr) != (recent_v == nullptr))
+        return PQ_ERR_NULL;
+    if (recent_k != nullptr && ctx->cfg.max_recent == 0)
+        return PQ_ERR_SHAPE;
+    if (!(scale == scale))
+        return PQ_ERR_SHAPE;
+    device_guard guard(ctx->cfg.device);
+    if (!guard.ok)
+        return PQ_ERR_HIP;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int rc = ensure_codebooks(ctx, k_codebook, v_codebook, s, false);
+    if (rc != PQ_OK)
+        return rc;
+
+    pq_decode_args a;
+    a.q = q;
+    a.k_codes = k_codes;
+    a.v_codes = v_codes;
+    a.ctx_len = ctx_len;
+    a.kcb_packed = ctx->kcb_packed;
+    a.vcb_packed = ctx->vcb_packed;
+    a.recent_k = recent_k;
+    a.recent_v = recent_v;
+    a.recent_len = recent_k ? recent_len : nullptr;
+    a.out = out;
+    a.partials = ctx->partials;
+    a.tickets = ctx->tickets;
+    a.scale_log2e = scale * LOG2E;
+    a.B = ctx->cfg.batch;
+    a.Hq = ctx->cfg.n_q_heads;
+    a.Hkv = ctx->cfg.n_kv_heads;
+    a.S = ctx->n_splits;
+    a.max_context = ctx->cfg.max_context;
+    a.max_recent = ctx->cfg.max_recent;
+    a.head_stride = ctx->cap_padded * ctx->cfg.n_subspaces;
+    return pq_launch_decode(ctx, a, s) == hipSuccess ? PQ_OK : PQ_ERR_HIP;
+}
+
+int pq_encode_append(pq_attn_ctx *ctx, const void *new_k, const void *new_v, int32_t n_new, const void *k_codebook,
+                     const void *v_codebook, uint8_t *k_codes, uint8_t *v_codes, int32_t *ctx_len, void *hip_stream)
+{
+    if (ctx == nullptr || new_k == nullptr || new_v == nullptr || k_codes == nullptr || v_codes == nullptr ||
+        ctx_len == nullptr)
+        return PQ_ERR_NULL;
+    if (n_new <= 0 || n_new > ctx->cfg.max_context)
+        return PQ_ERR_CAPACITY;
+    device_guard guard(ctx->cfg.device);
+    if (!guard.ok)
+        return PQ_ERR_HIP;
+    hipStream_t s = (hipStream_t)hip_stream;
+    // keeps the decode path's packed copy in step with the codebooks used to encode
+    const int rc = ensure_codebooks(ctx, k_codebook, v_codebook, s, false);
+    if (rc != PQ_OK)
+        return rc;
+
+    pq_encode_args a;
+    a.x[0] = new_k;
+    a.x[1] = new_v;
+    a.codebook[0] = ctx->reg_k;
+    a.codebook[1] = ctx->reg_v;
+    a.codes[0] = k_codes;
+    a.codes[1] = v_codes;
+    a.ctx_len = ctx_len;
+    a.B = ctx->cfg.batch;
+    a.Hkv = ctx->cfg.n_kv_heads;
+    a.n_new = n_new;
+    a.max_context = ctx->cfg.max_context;
+    a.head_stride = ctx->cap_padded * ctx->cfg.n_subspaces;
+    return pq_launch_encode(ctx, a, ctx_len, ctx->dev_err, s) == hipSuccess ? PQ_OK : PQ_ERR_HIP;
+}
+
+static int pack_common(pq_attn_ctx *ctx, int32_t kind, const uint8_t *token_major, int32_t n_tokens, uint8_t *packed,
+                       bool unpack, void *hip_stream)
+{
+    if (ctx == nullptr || token_major == nullptr || packed == nullptr)
+        return PQ_ERR_NULL;
+    if (kind != PQ_CODES_K && kind != PQ_CODES_V)
+        return PQ_ERR_SHAPE;
+    if (n_tokens < 0)
+        return PQ_ERR_SHAPE;
+    if (n_tokens > ctx->cfg.max_context)
+        return PQ_ERR_CAPACITY;
+    device_guard guard(ctx->cfg.device);
+    if (!guard.ok)
+        return PQ_ERR_HIP;
+    return pq_launch_pack_codes(ctx, kind, token_major, n_tokens, packed, unpack, (hipStream_t)hip_stream) ==
+                   hipSuccess
+               ? PQ_OK
+               : PQ_ERR_HIP;
+}
+
+int pq_pack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *token_major, int32_t n_tokens, uint8_t *packed,
+                  void *hip_stream)
+{
+    return pack_common(ctx, kind, token_major, n_tokens, packed, false, hip_stream);
+}
+
+int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32_t n_tokens, uint8_t *token_major,
+                    void *hip_stream)
+{
+    return pack_common(ctx, kind, token_major, n_tokens, const_cast<uint8_t *>(packed), true, hip_stream);
+}
+
+int pq_attn_device_error(pq_attn_ctx *ctx, uint32_t *flags)
+{
+    if (ctx == nullptr || flags == nullptr)
+        return PQ_ERR_NULL;
+    device_guard guard(ctx->cfg.device);
+    if (!guard.ok)
+        return PQ_ERR_HIP;
+    unsigned int v = 0;
+    if (hipDeviceSynchronize() != hipSuccess)
+        return PQ_ERR_HIP;
+    if (hipMemcpy(&v, ctx->dev_err, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess)
+        return PQ_ERR_HIP;
+    if (v != 0 && hipMemset(ctx->dev_err, 0, sizeof(v)) != hipSuccess)
+        return PQ_ERR_HIP;
+    *flags = v;
+    return PQ_OK;
+}
+
+const char *pq_status_string(int status)
+{
+    switch (status) {
+    case PQ_OK: return "ok";
+    case PQ_ERR_NULL: return "a required pointer is NULL";
+    case PQ_ERR_SHAPE: return "inconsistent sizes";
+    case PQ_ERR_UNSUPPORTED: return "shape not supported by this build";
+    case PQ_ERR_CAPACITY: return "capacity exceeded";
+    case PQ_ERR_HIP: return "HIP runtime error";
+    case PQ_ERR_ALLOC: return "allocation failed";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,421 @@
+// Decode attention over a product-quantized KV cache: one fused kernel per call.
+//
+// What it computes (Eq. 7, equal to Eq. 6): for every (sequence b, query head hq)
+//   s_t   = sum_i LUT[i][Delta_K[t][i]],  LUT[i][c] = scale * q^i . C_K^i[c]        (quantized tokens)
+//   s_r   = scale * q . k_r                                                        (recent rows)
+//   out   = sum_t p_t * (||_i C_V^i[Delta_V[t][i]]) + sum_r p_r * v_r,   p = softmax over all s
+// with one shared maximum and normaliser, evaluated as split partials merged by
+// online softmax (the "OlSoftmax" of Eq. 7; steps 1-4 of Section III-C).
+//
+// Mapping to gfx950.  One workgroup = one (b, hq, context split).  Its LDS holds
+// the query's table LUT[c][i] (fp32, centroid-major, 64 KiB) and the head's value
+// codebook (fp16, centroid-major, 64 KiB); both are built once in the prologue
+// from the context's re-packed codebooks.  Each wavefront then streams 64-token
+// blocks of codes on its own, with no workgroup barrier in the loop:
+//   score pass  lane = token.  At step s lane l reads table column (s + l) % 64 of
+//               row code: 64 lanes, 64 distinct columns, so the gather has no LDS
+//               bank conflict for any code values.  The K code layout stores each
+//               token's bytes pre-rotated so the lane's own 16-byte loads deliver
+//               them in that order; the LDS address of a gather is one v_perm_b32
+//               (code byte -> address bits 8..15, column byte -> bits 0..7).
+//   softmax     wave maximum by DPP, running maximum / rescale per block, the
+//               weights p_t go through a 256-byte LDS line so that the value pass
+//               can read them as a broadcast.
+//   value pass  lane = subspace (= output dims).  Lane i gathers centroid row
+//               code from column i of the value codebook image: again 64 distinct
+//               columns per gather; the fp16 pair is consumed by v_fma_mix.
+// The recent full-precision rows are spread over the splits and folded into the
+// same running softmax.  Partials of the wavefronts are merged in LDS, the
+// workgroup's partial goes to global scratch, and the workgroup that takes the
+// last ticket of its (b, hq) merges all splits and writes the output row.
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include "pq_internal.h"
+
+namespace {
+
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
+typedef __attribute__((address_space(3))) float lds_f32;
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
+
+constexpr int LUT_OFF = 0;           // float [256][64]
+constexpr int VCB_OFF = 65536;       // fp16 image [256][256 bytes]
+constexpr int PBUF_OFF = 131072;     // float [NW][64]
+constexpr int PART_OFF = 131072 + 4096;  // float [NW][PQ_PART_STRIDE]
+constexpr int FLAG_OFF = PART_OFF + 16 * PQ_PART_STRIDE * 4;  // int: "this workgroup took the last ticket"
+constexpr int SMEM_BYTES = FLAG_OFF + 16;
+constexpr float NEG_BIG = -1.0e30f;  // "no score yet": finite so that differences stay finite
+
+template <typename T> struct elem;
+template <> struct elem<__half> {
+    static __device__ float ld(const void *p, int64_t i) { return __half2float(((const __half *)p)[i]); }
+};
+template <> struct elem<float> {
+    static __device__ float ld(const void *p, int64_t i) { return ((const float *)p)[i]; }
+};
+
+template <int CTRL> __device__ inline float dpp_move(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+// maximum over the 64 lanes, same value returned to every lane (wave-uniform)
+__device__ inline float wave_max(float x)
+{
+    x = fmaxf(x, dpp_move<0xB1>(x));   // quad_perm [1,0,3,2]
+    x = fmaxf(x, dpp_move<0x4E>(x));   // quad_perm [2,3,0,1]
+    x = fmaxf(x, dpp_move<0x141>(x));  // row_half_mirror
+    x = fmaxf(x, dpp_move<0x140>(x));  // row_mirror
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+// sum over the 64 lanes in a fixed order, wave-uniform result
+__device__ inline float wave_sum(float x)
+{
+    x += dpp_move<0xB1>(x);
+    x += dpp_move<0x4E>(x);
+    x += dpp_move<0x141>(x);
+    x += dpp_move<0x140>(x);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+__device__ inline uint32_t comp(const uint4 &v, int r)
+{
+    return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w;
+}
+
+template <int M> struct code_regs {
+    uint4 k[M / 16];
+    uint4 v[M / 16];
+};
+
+template <int M>
+__device__ inline void load_block(code_regs<M> &c, const uint8_t *k_head, const uint8_t *v_head, int blk, int lane)
+{
+    const uint4 *kp = (const uint4 *)(k_head + (int64_t)blk * (64 * M)) + lane;
+    const uint4 *vp = (const uint4 *)(v_head + (int64_t)blk * (64 * M)) + lane;
+#pragma unroll
+    for (int j = 0; j < M / 16; ++j) {
+        c.k[j] = kp[j * 64];
+        c.v[j] = vp[j * 64];
+    }
+}
+
+template <int M, int DS, typename T, int NW>
+__global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args a)
+{
+    static_assert(M * DS == PQ_HEAD_DIM, "head_dim 128 only");
+    static_assert((M == 64 && DS == 2) || (M == 32 && DS == 4), "supported PQ shapes");
+    constexpr bool F16 = sizeof(T) == 2;
+
+    // The only LDS object of the kernel, so it sits at LDS address 0 and the
+    // byte-assembled gather addresses below are used as they are.
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM_BYTES];
+    lds_u8 *lbase = (lds_u8 *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // ---- which (sequence, query head, split) this workgroup owns.  Workgroups are
+    // dealt round-robin to the 8 XCDs; un-deal them so that all splits of a head (and
+    // all query heads of a KV group) sit on one XCD and share its L2 for the
+    // codebooks and, with grouped queries, the code stream itself.
+    const int grid = gridDim.x;
+    int logical = blockIdx.x;
+    if ((grid & 7) == 0)
+        logical = (blockIdx.x & 7) * (grid >> 3) + (blockIdx.x >> 3);
+    const int S = a.S;
+    const int split = logical % S;
+    const int bh = logical / S;
+    const int b = bh / a.Hq;
+    const int hq = bh - b * a.Hq;
+    const int hkv = hq / (a.Hq / a.Hkv);
+
+    int N = a.ctx_len[b];
+    N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
+    int R = 0;
+    if (a.recent_k != nullptr && a.recent_len != nullptr) {
+        R = a.recent_len[b];
+        R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
+    }
+    const int nblk = (N + 63) >> 6;
+    const int blk0 = (int)(((int64_t)nblk * split) / S);
+    const int blk1 = (int)(((int64_t)nblk * (split + 1)) / S);
+    const int r0 = (int)(((int64_t)R * split) / S);
+    const int r1 = (int)(((int64_t)R * (split + 1)) / S);
+
+    const uint8_t *k_head = a.k_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
+    const uint8_t *v_head = a.v_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
+
+    // first block's codes are requested before the tables are built
+    code_regs<M> cur, nxt;
+    int blk = blk0 + wave;
+    if (blk < blk1)
+        load_block<M>(cur, k_head, v_head, blk, lane);
+
+    // ---- this lane's query sub-vector, pre-multiplied by scale * log2(e)
+    const int sub = lane & (M - 1);
+    float qs[DS];
+#pragma unroll
+    for (int j = 0; j < DS; ++j)
+        qs[j] = elem<T>::ld(a.q, ((int64_t)b * a.Hq + hq) * PQ_HEAD_DIM + sub * DS + j) * a.scale_log2e;
+
+    // ---- prologue: LUT[c][x] for x = 0..63 (for M = 32 columns x and x+32 hold the same
+    // subspace), and the value codebook image
+    if (blk0 < blk1) {
+        const T *kcb = (const T *)a.kcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM;
+        for (int c = wave; c < 256; c += NW) {
+            float e = 0.f;
+#pragma unroll
+            for (int j = 0; j < DS; ++j)
+                e = fmaf(qs[j], elem<T>::ld(kcb, c * PQ_HEAD_DIM + sub * DS + j), e);
+            *(lds_f32 *)(lbase + LUT_OFF + c * 256 + lane * 4) = e;
+        }
+        if (F16) {
+            const u32x4 *src = (const u32x4 *)((const __half *)a.vcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM);
+            for (int x = tid; x < 4096; x += NW * 64)
+                *(lds_u32x4 *)(lbase + VCB_OFF + x * 16) = src[x];
+        }
+    }
+    __syncthreads();
+
+    // column bytes of the score pass: byte k of idx[r] = 4 * ((4r + k + lane) % 64)
+    uint32_t idx[M / 4];
+#pragma unroll
+    for (int r = 0; r < M / 4; ++r) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            v |= (uint32_t)(((4 * r + k + lane) & 63) << 2) << (8 * k);
+        idx[r] = v;
+    }
+    // value pass: byte 0 = this lane's column offset in a 256-byte codebook row,
+    // byte 1 = bits 16..23 of the codebook image's LDS address
+    const uint32_t vcol = (uint32_t)(sub * (2 * DS)) | ((VCB_OFF >> 16) << 8);
+    const int half_id = lane >> 5;  // M = 32: which of the two interleaved token streams
+
+    float m_run = NEG_BIG;  // running maximum (wave-uniform)
+    float l_lane = 0.f;     // this lane's share of the sum of weights
+    float acc[DS];
+#pragma unroll
+    for (int j = 0; j < DS; ++j)
+        acc[j] = 0.f;
+
+    const float *vcb_f32 = (const float *)a.vcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM;
+    lds_u8 *pline = lbase + PBUF_OFF + wave * 256;
+
+    for (; blk < blk1; blk += NW) {
+        const int nb = blk + NW;
+        if (nb < blk1)
+            load_block<M>(nxt, k_head, v_head, nb, lane);
+
+        // ---------------- score pass
+        float s4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < M / 4; ++r) {
+            const uint32_t w = comp(cur.k[r >> 2], r & 3);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t sel = 0x0c0c0000u | ((4 + k) << 8) | k;
+                const uint32_t addr = __builtin_amdgcn_perm(w, idx[r], sel);
+                s4[k] += *(lds_f32 *)(lbase + addr);
+            }
+        }
+        const bool valid = blk * 64 + lane < N;
+        const float s = valid ? (s4[0] + s4[1]) + (s4[2] + s4[3]) : NEG_BIG;
+
+        // ---------------- running softmax
+        const float m_new = fmaxf(m_run, wave_max(s));
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        const float p = valid ? __builtin_amdgcn_exp2f(s - m_new) : 0.f;
+        l_lane = fmaf(l_lane, alpha, p);
+#pragma unroll
+        for (int j = 0; j < DS; ++j)
+            acc[j] *= alpha;
+        m_run = m_new;
+        *(lds_f32 *)(pline + lane * 4) = p;
+        __builtin_amdgcn_wave_barrier();
+
+        // ---------------- value pass
+#pragma unroll
+        for (int n = 0; n < M / 16; ++n) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t w = comp(cur.v[n], r);
+                const int tok0 = (M == 64) ? (16 * n + 4 * r) : (32 * n + 16 * half_id + 4 * r);
+                const f32x4 p4 = *(lds_f32x4 *)(pline + tok0 * 4);
+                const float pk[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (F16) {
+                        const uint32_t sel = 0x0c010000u | ((4 + k) << 8);
+                        const uint32_t addr = __builtin_amdgcn_perm(w, vcol, sel);
+                        if (DS == 2) {
+                            const uint32_t cv = *(lds_u32 *)(lbase + addr);
+                            const __half2 h = *(const __half2 *)&cv;
+                            acc[0] = fmaf(pk[k], __low2float(h), acc[0]);
+                            acc[1] = fmaf(pk[k], __high2float(h), acc[1]);
+                        } else {
+                            const u32x2 cv = *(lds_u32x2 *)(lbase + addr);
+                            const uint32_t c0 = cv.x, c1 = cv.y;
+                            const __half2 h0 = *(const __half2 *)&c0;
+                            const __half2 h1 = *(const __half2 *)&c1;
+                            acc[0] = fmaf(pk[k], __low2float(h0), acc[0]);
+                            acc[1] = fmaf(pk[k], __high2float(h0), acc[1]);
+                            acc[DS - 2] = fmaf(pk[k], __low2float(h1), acc[DS - 2]);
+                            acc[DS - 1] = fmaf(pk[k], __high2float(h1), acc[DS - 1]);
+                        }
+                    } else {
+                        // fp32 codebooks do not fit in LDS next to the table: gather from memory
+                        const uint32_t code = (w >> (8 * k)) & 255u;
+                        const float *cv = vcb_f32 + ((int64_t)code * M + sub) * DS;
+#pragma unroll
+                        for (int j = 0; j < DS; ++j)
+                            acc[j] = fmaf(pk[k], cv[j], acc[j]);
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        cur = nxt;
+    }
+
+    // ---------------- recent full-precision rows of this split (Eq. 7, second term)
+    {
+        // M = 32: only lanes 0..31 own output dims here (lanes 32..63 carry the second
+        // token stream of the value pass and are merged below)
+        const bool owner = (M == 64) || lane < 32;
+        const int64_t rbase = ((int64_t)b * a.Hkv + hkv) * a.max_recent;
+        for (int r = r0 + wave; r < r1; r += NW) {
+            float kv[DS], vv[DS];
+            float dot = 0.f;
+#pragma unroll
+            for (int j = 0; j < DS; ++j) {
+                kv[j] = owner ? elem<T>::ld(a.recent_k, (rbase + r) * PQ_HEAD_DIM + sub * DS + j) : 0.f;
+                vv[j] = owner ? elem<T>::ld(a.recent_v, (rbase + r) * PQ_HEAD_DIM + sub * DS + j) : 0.f;
+                dot = fmaf(qs[j], kv[j], dot);
+            }
+            const float s = wave_sum(dot);
+            const float m_new = fmaxf(m_run, s);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            const float p = __builtin_amdgcn_exp2f(s - m_new);
+            l_lane = fmaf(l_lane, alpha, lane == 0 ? p : 0.f);
+#pragma unroll
+            for (int j = 0; j < DS; ++j)
+                acc[j] = fmaf(acc[j], alpha, p * vv[j]);
+            m_run = m_new;
+        }
+    }
+
+    // ---------------- merge the wavefronts of this workgroup
+    {
+        const float l_w = wave_sum(l_lane);
+        if (M == 32) {
+#pragma unroll
+            for (int j = 0; j < DS; ++j)
+                acc[j] += __shfl_xor(acc[j], 32);
+        }
+        lds_f32 *part = (lds_f32 *)(lbase + PART_OFF) + wave * PQ_PART_STRIDE;
+        if (lane == 0) {
+            part[0] = m_run;
+            part[1] = l_w;
+        }
+        if (M == 64 || lane < 32) {
+#pragma unroll
+            for (int j = 0; j < DS; ++j)
+                part[4 + sub * DS + j] = acc[j];
+        }
+    }
+    __syncthreads();
+
+    float *gpart = a.partials + ((int64_t)bh * S + split) * PQ_PART_STRIDE;
+    float *orow = a.out + (int64_t)bh * PQ_HEAD_DIM;
+    if (tid < PQ_HEAD_DIM) {
+        const lds_f32 *parts = (const lds_f32 *)(lbase + PART_OFF);
+        float mx = NEG_BIG;
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+            mx = fmaxf(mx, parts[w * PQ_PART_STRIDE]);
+        float o = 0.f, l = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float f = __builtin_amdgcn_exp2f(parts[w * PQ_PART_STRIDE] - mx);
+            o = fmaf(parts[w * PQ_PART_STRIDE + 4 + tid], f, o);
+            l = fmaf(parts[w * PQ_PART_STRIDE + 1], f, l);
+        }
+        if (S == 1) {
+            orow[tid] = l > 0.f ? o / l : 0.f;
+        } else {
+            gpart[4 + tid] = o;
+            if (tid == 0) {
+                gpart[0] = mx;
+                gpart[1] = l;
+            }
+        }
+    }
+    if (S == 1)
+        return;
+
+    // ---------------- last workgroup of this (b, hq) merges the splits (flash-decoding style)
+    typedef __attribute__((address_space(3))) int lds_i32;
+    lds_i32 *is_last = (lds_i32 *)(lbase + FLAG_OFF);
+    __threadfence();  // release: this workgroup's partial is visible device-wide
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned int t = __hip_atomic_fetch_add(a.tickets + bh, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        *is_last = (t == (unsigned int)(S - 1));
+    }
+    __syncthreads();
+    if (!*is_last)
+        return;
+    __threadfence();  // acquire: the other workgroups' partials
+    if (tid < PQ_HEAD_DIM) {
+        const float *ps = a.partials + (int64_t)bh * S * PQ_PART_STRIDE;
+        float mx = NEG_BIG;
+        for (int s2 = 0; s2 < S; ++s2)
+            mx = fmaxf(mx, ps[s2 * PQ_PART_STRIDE]);
+        float o = 0.f, l = 0.f;
+        for (int s2 = 0; s2 < S; ++s2) {
+            const float f = __builtin_amdgcn_exp2f(ps[s2 * PQ_PART_STRIDE] - mx);
+            o = fmaf(ps[s2 * PQ_PART_STRIDE + 4 + tid], f, o);
+            l = fmaf(ps[s2 * PQ_PART_STRIDE + 1], f, l);
+        }
+        orow[tid] = l > 0.f ? o / l : 0.f;
+    }
+    if (tid == 0)
+        a.tickets[bh] = 0u;  // ready for the next call on this context
+}
+
+template <int M, int DS, typename T, int NW>
+hipError_t launch(const pq_decode_args &a, hipStream_t s)
+{
+    const int grid = a.B * a.Hq * a.S;
+    hipLaunchKernelGGL((pq_decode_kernel<M, DS, T, NW>), dim3(grid), dim3(NW * 64), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t pq_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
+{
+    const bool f16 = ctx->cfg.dtype == PQ_F16;
+    if (ctx->cfg.n_subspaces == 64)
+        return f16 ? launch<64, 2, __half, 16>(a, s) : launch<64, 2, float, 16>(a, s);
+    return f16 ? launch<32, 4, __half, 16>(a, s) : launch<32, 4, float, 16>(a, s);
+}

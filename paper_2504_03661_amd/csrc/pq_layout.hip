@@ -1,0 +1,73 @@
+// Layout conversions: codebooks to the centroid-major image the decode kernel
+// streams into LDS, and code tensors between the logical token-major form
+// [B][Hkv][n][M] (Delta_K, Delta_V of Eq. 4) and the device layouts.
+#include <hip/hip_runtime.h>
+
+#include "pq_internal.h"
+
+namespace {
+
+// [Hkv][M][256][ds] -> [Hkv][256][M][ds]; one thread per (head, centroid, subspace)
+template <typename E>
+__global__ void pq_pack_codebook_kernel(const E *src, E *dst, int Hkv, int M, int ds)
+{
+    const int64_t n = (int64_t)Hkv * 256 * M;
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= n)
+        return;
+    const int i = (int)(x % M);
+    const int c = (int)((x / M) % 256);
+    const int h = (int)(x / ((int64_t)M * 256));
+    const E *s = src + (((int64_t)h * M + i) * 256 + c) * ds;
+    E *d = dst + x * ds;
+    for (int j = 0; j < ds; ++j)
+        d[j] = s[j];
+}
+
+// one thread per code byte of the token-major tensor
+__global__ void pq_pack_codes_kernel(const uint8_t *token_major, uint8_t *packed, int64_t n_heads, int n_tokens,
+                                     int M, int64_t head_stride, int kind, int unpack)
+{
+    const int64_t total = n_heads * n_tokens * M;
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= total)
+        return;
+    const int i = (int)(x % M);
+    const int64_t t = (x / M) % n_tokens;
+    const int64_t h = x / ((int64_t)M * n_tokens);
+    const int64_t off = h * head_stride + (kind == PQ_CODES_K ? pq_k_code_offset(t, i, M) : pq_v_code_offset(t, i, M));
+    if (unpack)
+        const_cast<uint8_t *>(token_major)[x] = packed[off];
+    else
+        packed[off] = token_major[x];
+}
+
+}  // namespace
+
+hipError_t pq_launch_pack_codebook(const pq_attn_ctx *ctx, const void *src, void *dst, hipStream_t s)
+{
+    const int Hkv = ctx->cfg.n_kv_heads, M = ctx->cfg.n_subspaces, ds = ctx->ds;
+    const int64_t n = (int64_t)Hkv * 256 * M;
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (ctx->cfg.dtype == PQ_F16)
+        hipLaunchKernelGGL(pq_pack_codebook_kernel<uint16_t>, grid, block, 0, s, (const uint16_t *)src,
+                           (uint16_t *)dst, Hkv, M, ds);
+    else
+        hipLaunchKernelGGL(pq_pack_codebook_kernel<uint32_t>, grid, block, 0, s, (const uint32_t *)src,
+                           (uint32_t *)dst, Hkv, M, ds);
+    return hipGetLastError();
+}
+
+hipError_t pq_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint8_t *token_major, int n_tokens,
+                                uint8_t *packed, bool unpack, hipStream_t s)
+{
+    const int64_t n_heads = (int64_t)ctx->cfg.batch * ctx->cfg.n_kv_heads;
+    const int M = ctx->cfg.n_subspaces;
+    const int64_t total = n_heads * n_tokens * M;
+    if (total == 0)
+        return hipSuccess;
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    hipLaunchKernelGGL(pq_pack_codes_kernel, grid, block, 0, s, token_major, packed, n_heads, n_tokens, M,
+                       ctx->cap_padded * M, kind, unpack ? 1 : 0);
+    return hipGetLastError();
+}

@@ -1,0 +1,85 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad configurations before touching HIP."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2504_03661_amd as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "pq_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pq_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = P.load_library()
+    names = declared_functions()
+    assert {"pq_attn_create", "pq_attn_decode", "pq_encode_append"} <= set(names)
+    for n in names:
+        assert getattr(lib, n) is not None, n
+
+
+def test_binding_has_the_same_names():
+    for n in declared_functions():
+        assert hasattr(P, n), n
+
+
+def good(**kw):
+    c = P.PQAttnConfig(batch=1, n_q_heads=32, n_kv_heads=32, max_context=32768, max_recent=128)
+    for k, v in kw.items():
+        setattr(c, k, v)
+    return c
+
+
+@pytest.mark.parametrize("changes,status", [
+    ({}, 0),
+    ({"n_subspaces": 32}, 0),
+    ({"n_q_heads": 32, "n_kv_heads": 8}, 0),
+    ({"dtype": P.PQ_F32}, 0),
+    ({"batch": 0}, -2),
+    ({"n_q_heads": 30, "n_kv_heads": 8}, -2),          # Hq % Hkv
+    ({"head_dim": 128, "n_subspaces": 48}, -2),        # d % M
+    ({"max_context": 0}, -2),
+    ({"max_recent": -1}, -2),
+    ({"dtype": 7}, -2),
+    ({"reserved": 1}, -2),
+    ({"n_centroids": 4096}, -3),                       # 12-bit codes: no kernel
+    ({"n_subspaces": 16}, -3),
+    ({"head_dim": 64, "n_subspaces": 32}, -3),
+    ({"n_splits": 1000}, -3),
+])
+def test_validate_config(changes, status):
+    assert P.pq_attn_validate_config(good(**changes)) == status
+
+
+def test_codes_bytes_rounds_capacity_to_64_token_blocks():
+    assert P.pq_attn_codes_bytes(good()) == 32 * 32768 * 64
+    assert P.pq_attn_codes_bytes(good(max_context=1000)) == 32 * 1024 * 64
+    assert P.pq_attn_codes_bytes(good(max_context=65, n_subspaces=32, batch=3)) == 3 * 32 * 128 * 32
+    with pytest.raises(P.PQAttnError):
+        P.pq_attn_codes_bytes(good(batch=-1))
+
+
+def test_null_arguments_are_rejected_without_a_gpu():
+    lib = P.load_library()
+    assert lib.pq_attn_create(None, None) == -1
+    assert lib.pq_attn_destroy(None) == -1
+    assert lib.pq_attn_decode(None, None, None, None, None, None, None, None, None, None, 1.0, None, None) == -1
+    assert lib.pq_encode_append(None, None, None, 1, None, None, None, None, None, None) == -1
+    assert lib.pq_attn_validate_config(None) == -1
+    out = ctypes.c_void_p()
+    # bad config is reported before any HIP call
+    assert lib.pq_attn_create(ctypes.byref(good(batch=0).c_struct()), ctypes.byref(out)) == -2
+    assert out.value is None
+
+
+def test_status_strings():
+    assert P.pq_status_string(0) == "ok"
+    for s in (-1, -2, -3, -4, -6, -7, -99):
+        assert P.pq_status_string(s)
