@@ -49,8 +49,7 @@ constexpr int LUT_OFF = 0;           // float [256][64]
 constexpr int VCB_OFF = 65536;       // fp16 image [256][256 bytes]
 constexpr int PBUF_OFF = 131072;     // float [NW][64]
 constexpr int PART_OFF = 131072 + 4096;  // float [NW][PQ_PART_STRIDE]
-constexpr int FLAG_OFF = PART_OFF + 16 * PQ_PART_STRIDE * 4;  // int: "this workgroup took the last ticket"
-constexpr int SMEM_BYTES = FLAG_OFF + 16;
+constexpr int SMEM_BYTES = PART_OFF + 16 * PQ_PART_STRIDE * 4;
 constexpr float NEG_BIG = -1.0e30f;  // "no score yet": finite so that differences stay finite
 
 template <typename T> struct elem;
@@ -163,11 +162,8 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const uint8_t *k_head = a.k_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
     const uint8_t *v_head = a.v_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
 
-    // first block's codes are requested before the tables are built
-    code_regs<M> cur, nxt;
+    code_regs<M> bufA, bufB;  // double buffer: one block is processed while the next one loads
     int blk = blk0 + wave;
-    if (blk < blk1)
-        load_block<M>(cur, k_head, v_head, blk, lane);
 
     // ---- this lane's query sub-vector, pre-multiplied by scale * log2(e)
     const int sub = lane & (M - 1);
@@ -177,20 +173,56 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         qs[j] = elem<T>::ld(a.q, ((int64_t)b * a.Hq + hq) * PQ_HEAD_DIM + sub * DS + j) * a.scale_log2e;
 
     // ---- prologue: LUT[c][x] for x = 0..63 (for M = 32 columns x and x+32 hold the same
-    // subspace), and the value codebook image
+    // subspace), and the value codebook image.  All global loads are issued before the
+    // first use so that the workgroup pays one memory round trip, not one per row.
     if (blk0 < blk1) {
-        const T *kcb = (const T *)a.kcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM;
-        for (int c = wave; c < 256; c += NW) {
-            float e = 0.f;
+        constexpr int ROWS_PER_PASS = NW * 4;              // 16 threads cover one 64-column row
+        constexpr int PASSES = 256 / ROWS_PER_PASS;
+        constexpr int NV = 4 * DS * (int)sizeof(T) / 16;   // 16-byte vectors per 4 columns
+        constexpr int VPT = 4096 / (NW * 64);              // codebook-image vectors per thread
+        const int g = tid & 15;                            // columns 4g .. 4g+3
+        const int row0 = tid >> 4;
+        const int e0 = ((4 * g) & (M - 1)) * DS;           // first element of those columns in a row
+        const char *kcb = (const char *)a.kcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM * sizeof(T);
+        u32x4 kraw[PASSES][NV];
 #pragma unroll
-            for (int j = 0; j < DS; ++j)
-                e = fmaf(qs[j], elem<T>::ld(kcb, c * PQ_HEAD_DIM + sub * DS + j), e);
-            *(lds_f32 *)(lbase + LUT_OFF + c * 256 + lane * 4) = e;
-        }
+        for (int k = 0; k < PASSES; ++k)
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+                kraw[k][v] = *(const u32x4 *)(kcb + ((row0 + k * ROWS_PER_PASS) * PQ_HEAD_DIM + e0) * sizeof(T) + v * 16);
+        u32x4 vraw[VPT];
         if (F16) {
             const u32x4 *src = (const u32x4 *)((const __half *)a.vcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM);
-            for (int x = tid; x < 4096; x += NW * 64)
-                *(lds_u32x4 *)(lbase + VCB_OFF + x * 16) = src[x];
+#pragma unroll
+            for (int v = 0; v < VPT; ++v)
+                vraw[v] = src[tid + v * (NW * 64)];
+        }
+        float qv[4 * DS];
+#pragma unroll
+        for (int e = 0; e < 4 * DS; ++e)
+            qv[e] = elem<T>::ld(a.q, ((int64_t)b * a.Hq + hq) * PQ_HEAD_DIM + e0 + e) * a.scale_log2e;
+        // the first block's codes are requested behind the (small) table loads, so that the
+        // tables are not queued behind a chip-wide burst of code loads, and stream in
+        // while the tables are built
+        if (blk < blk1)
+            load_block<M>(bufA, k_head, v_head, blk, lane);
+#pragma unroll
+        for (int k = 0; k < PASSES; ++k) {
+            f32x4 ent;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float e = 0.f;
+#pragma unroll
+                for (int j = 0; j < DS; ++j)
+                    e = fmaf(qv[u * DS + j], elem<T>::ld(&kraw[k][0], u * DS + j), e);
+                ent[u] = e;
+            }
+            *(lds_f32x4 *)(lbase + LUT_OFF + (row0 + k * ROWS_PER_PASS) * 256 + g * 16) = ent;
+        }
+        if (F16) {
+#pragma unroll
+            for (int v = 0; v < VPT; ++v)
+                *(lds_u32x4 *)(lbase + VCB_OFF + (tid + v * (NW * 64)) * 16) = vraw[v];
         }
     }
     __syncthreads();
@@ -220,11 +252,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const float *vcb_f32 = (const float *)a.vcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM;
     lds_u8 *pline = lbase + PBUF_OFF + wave * 256;
 
-    for (; blk < blk1; blk += NW) {
-        const int nb = blk + NW;
-        if (nb < blk1)
-            load_block<M>(nxt, k_head, v_head, nb, lane);
-
+    auto process = [&](const code_regs<M> &cur, const int blk) {
         // ---------------- score pass
         float s4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -293,7 +321,22 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
             }
         }
         __builtin_amdgcn_wave_barrier();
-        cur = nxt;
+    };
+
+    // two blocks per trip so that the buffers swap roles without register copies
+    while (blk < blk1) {
+        int nb = blk + NW;
+        if (nb < blk1)
+            load_block<M>(bufB, k_head, v_head, nb, lane);
+        process(bufA, blk);
+        blk = nb;
+        if (blk >= blk1)
+            break;
+        nb = blk + NW;
+        if (nb < blk1)
+            load_block<M>(bufA, k_head, v_head, nb, lane);
+        process(bufB, blk);
+        blk = nb;
     }
 
     // ---------------- recent full-precision rows of this split (Eq. 7, second term)
@@ -344,62 +387,70 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     }
     __syncthreads();
 
+    // From here on only wavefront 0 works: it merges the workgroup's wavefronts (lane l owns
+    // output dims 2l, 2l+1), publishes the split partial and takes a ticket.  Keeping the
+    // device-scope release/acquire fences in ONE wavefront per workgroup matters: each fence
+    // is an L2 write-back / invalidate, and sixteen of them per workgroup cost more than
+    // the whole scan.
+    if (wave != 0)
+        return;
     float *gpart = a.partials + ((int64_t)bh * S + split) * PQ_PART_STRIDE;
     float *orow = a.out + (int64_t)bh * PQ_HEAD_DIM;
-    if (tid < PQ_HEAD_DIM) {
-        const lds_f32 *parts = (const lds_f32 *)(lbase + PART_OFF);
-        float mx = NEG_BIG;
+    const lds_f32 *parts = (const lds_f32 *)(lbase + PART_OFF);
+    float mx = NEG_BIG;
 #pragma unroll
-        for (int w = 0; w < NW; ++w)
-            mx = fmaxf(mx, parts[w * PQ_PART_STRIDE]);
-        float o = 0.f, l = 0.f;
+    for (int w = 0; w < NW; ++w)
+        mx = fmaxf(mx, parts[w * PQ_PART_STRIDE]);
+    float o0 = 0.f, o1 = 0.f, l = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float f = __builtin_amdgcn_exp2f(parts[w * PQ_PART_STRIDE] - mx);
-            o = fmaf(parts[w * PQ_PART_STRIDE + 4 + tid], f, o);
-            l = fmaf(parts[w * PQ_PART_STRIDE + 1], f, l);
-        }
-        if (S == 1) {
-            orow[tid] = l > 0.f ? o / l : 0.f;
-        } else {
-            gpart[4 + tid] = o;
-            if (tid == 0) {
-                gpart[0] = mx;
-                gpart[1] = l;
-            }
-        }
+    for (int w = 0; w < NW; ++w) {
+        const float f = __builtin_amdgcn_exp2f(parts[w * PQ_PART_STRIDE] - mx);
+        o0 = fmaf(parts[w * PQ_PART_STRIDE + 4 + 2 * lane], f, o0);
+        o1 = fmaf(parts[w * PQ_PART_STRIDE + 5 + 2 * lane], f, o1);
+        l = fmaf(parts[w * PQ_PART_STRIDE + 1], f, l);
     }
-    if (S == 1)
+    if (S == 1) {
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        *(float2 *)(orow + 2 * lane) = make_float2(o0 * inv, o1 * inv);
         return;
-
-    // ---------------- last workgroup of this (b, hq) merges the splits (flash-decoding style)
-    typedef __attribute__((address_space(3))) int lds_i32;
-    lds_i32 *is_last = (lds_i32 *)(lbase + FLAG_OFF);
-    __threadfence();  // release: this workgroup's partial is visible device-wide
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned int t = __hip_atomic_fetch_add(a.tickets + bh, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        *is_last = (t == (unsigned int)(S - 1));
     }
-    __syncthreads();
-    if (!*is_last)
+    *(float2 *)(gpart + 4 + 2 * lane) = make_float2(o0, o1);
+    if (lane == 0)
+        *(float2 *)gpart = make_float2(mx, l);
+
+    // ---------------- the workgroup that takes the last ticket of this (b, hq) merges the
+    // splits (flash-decoding style) and leaves the ticket counter at zero for the next call
+    __threadfence();  // release: the partial above is visible device-wide before the ticket
+    unsigned int ticket = 0;
+    if (lane == 0)
+        ticket = __hip_atomic_fetch_add(a.tickets + bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    ticket = __builtin_amdgcn_readfirstlane(ticket);
+    if (ticket != (unsigned int)(S - 1))
         return;
     __threadfence();  // acquire: the other workgroups' partials
-    if (tid < PQ_HEAD_DIM) {
-        const float *ps = a.partials + (int64_t)bh * S * PQ_PART_STRIDE;
-        float mx = NEG_BIG;
-        for (int s2 = 0; s2 < S; ++s2)
-            mx = fmaxf(mx, ps[s2 * PQ_PART_STRIDE]);
-        float o = 0.f, l = 0.f;
-        for (int s2 = 0; s2 < S; ++s2) {
-            const float f = __builtin_amdgcn_exp2f(ps[s2 * PQ_PART_STRIDE] - mx);
-            o = fmaf(ps[s2 * PQ_PART_STRIDE + 4 + tid], f, o);
-            l = fmaf(ps[s2 * PQ_PART_STRIDE + 1], f, l);
+    const float *ps = a.partials + (int64_t)bh * S * PQ_PART_STRIDE;
+    // lane s holds (maximum, weight sum) of split s; all loads of a round are issued together
+    const float2 ml = lane < S ? *(const float2 *)(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
+    mx = wave_max(ml.x);
+    const float f_lane = __builtin_amdgcn_exp2f(ml.x - mx);
+    l = wave_sum(ml.y * f_lane);
+    o0 = o1 = 0.f;
+    for (int s0 = 0; s0 < S; s0 += 8) {
+        float2 o[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            o[u] = s0 + u < S ? *(const float2 *)(ps + (s0 + u) * PQ_PART_STRIDE + 4 + 2 * lane) : make_float2(0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), (s0 + u) & 63));
+            o0 = fmaf(o[u].x, f, o0);
+            o1 = fmaf(o[u].y, f, o1);
         }
-        orow[tid] = l > 0.f ? o / l : 0.f;
     }
-    if (tid == 0)
-        a.tickets[bh] = 0u;  // ready for the next call on this context
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    *(float2 *)(orow + 2 * lane) = make_float2(o0 * inv, o1 * inv);
+    if (lane == 0)
+        a.tickets[bh] = 0u;
 }
 
 template <int M, int DS, typename T, int NW>
