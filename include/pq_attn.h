@@ -54,8 +54,9 @@ typedef struct {
     int32_t head_dim;     /* d; supported: 128                                              */
     int32_t n_subspaces;  /* M; supported: 64 (ds = 2, 4 bits/dim) and 32 (ds = 4, 2 bits/dim) */
     int32_t n_centroids;  /* C; supported: 256 (nbits = 8)                                  */
-    int32_t max_context;  /* token capacity of the code tensors per (sequence, KV head)     */
-    int32_t max_recent;   /* row capacity of the recent window tensors (0: no window)       */
+    int32_t max_context;  /* token capacity of the code tensors per (sequence, KV head),    */
+                          /* 1 .. 2^24                                                      */
+    int32_t max_recent;   /* row capacity of the recent window tensors (0: no window), <= 2^24 */
     int32_t dtype;        /* pq_dtype of q, codebooks, recent K/V and new K/V               */
     int32_t device;       /* HIP device ordinal                                             */
     int32_t n_splits;     /* context splits per (sequence, query head); 0 = choose          */

@@ -42,7 +42,7 @@ int validate(const pq_attn_config *c)
         return PQ_ERR_SHAPE;
     if (c->n_centroids != 256 || c->head_dim != PQ_HEAD_DIM || (c->n_subspaces != 64 && c->n_subspaces != 32))
         return PQ_ERR_UNSUPPORTED;
-    if (c->n_splits > PQ_MAX_SPLITS)
+    if (c->n_splits > PQ_MAX_SPLITS || c->max_context > PQ_MAX_TOKENS || c->max_recent > PQ_MAX_TOKENS)
         return PQ_ERR_UNSUPPORTED;
     if ((int64_t)c->batch * c->n_q_heads * PQ_MAX_SPLITS > (int64_t)1 << 30)
         return PQ_ERR_UNSUPPORTED;
@@ -227,6 +227,7 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
     a.B = ctx->cfg.batch;
     a.Hq = ctx->cfg.n_q_heads;
     a.Hkv = ctx->cfg.n_kv_heads;
+    a.G = ctx->group;
     a.S = ctx->n_splits;
     a.max_context = ctx->cfg.max_context;
     a.max_recent = ctx->cfg.max_recent;

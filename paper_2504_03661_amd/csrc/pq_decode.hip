@@ -135,35 +135,79 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     // dealt round-robin to the 8 XCDs; un-deal them so that all splits of a head (and
     // all query heads of a KV group) sit on one XCD and share its L2 for the
     // codebooks and, with grouped queries, the code stream itself.
-    const int grid = gridDim.x;
-    int logical = blockIdx.x;
-    if ((grid & 7) == 0)
-        logical = (blockIdx.x & 7) * (grid >> 3) + (blockIdx.x >> 3);
+    const uint32_t grid = gridDim.x;
+    uint32_t logical = blockIdx.x;
+    if ((grid & 7u) == 0)
+        logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
     const int S = a.S;
-    const int split = logical % S;
-    const int bh = logical / S;
-    const int b = bh / a.Hq;
+    const int bh = (int)(logical / (uint32_t)S);
+    const int split = (int)(logical - (uint32_t)bh * (uint32_t)S);
+    const int b = (int)((uint32_t)bh / (uint32_t)a.Hq);
     const int hq = bh - b * a.Hq;
-    const int hkv = hq / (a.Hq / a.Hkv);
+    const int hkv = (int)((uint32_t)hq / (uint32_t)a.G);
 
+    // the lengths are requested first: by the time the table loads below have been issued
+    // they are here, and the first code loads can follow the tables without a further wait
     int N = a.ctx_len[b];
-    N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
-    int R = 0;
-    if (a.recent_k != nullptr && a.recent_len != nullptr) {
-        R = a.recent_len[b];
-        R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
+    int R = (a.recent_k != nullptr && a.recent_len != nullptr) ? a.recent_len[b] : 0;
+
+    // ---- prologue: LUT[c][x] for x = 0..63 (for M = 32 columns x and x+32 hold the same
+    // subspace), and the value codebook image.  Order matters at this time scale:
+    //  1. every wavefront issues its table loads (they need nothing but the head index);
+    //  2. a bare barrier, so that ALL table requests of the workgroup are queued in the
+    //     compute unit's memory pipeline before ANY code request (the pipeline serves in
+    //     order: a table request behind other wavefronts' code loads would arrive last);
+    //  3. the sequence length is read, the split is cut, the first code block is requested;
+    //  4. the tables are built while the codes stream in.
+    constexpr int ROWS_PER_PASS = NW * 4;              // 16 threads cover one 64-column row
+    constexpr int PASSES = 256 / ROWS_PER_PASS;
+    constexpr int NV = 4 * DS * (int)sizeof(T) / 16;   // 16-byte vectors per 4 columns
+    constexpr int VPT = 4096 / (NW * 64);              // codebook-image vectors per thread
+    const int g = tid & 15;                            // columns 4g .. 4g+3
+    const int row0 = tid >> 4;
+    const int e0 = ((4 * g) & (M - 1)) * DS;           // first element of those columns in a row
+    const char *kcb = (const char *)a.kcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM * sizeof(T);
+    u32x4 kraw[PASSES][NV];
+#pragma unroll
+    for (int k = 0; k < PASSES; ++k)
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+            kraw[k][v] = *(const u32x4 *)(kcb + ((row0 + k * ROWS_PER_PASS) * PQ_HEAD_DIM + e0) * sizeof(T) + v * 16);
+    u32x4 vraw[VPT];
+    if (F16) {
+        const u32x4 *src = (const u32x4 *)((const __half *)a.vcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM);
+#pragma unroll
+        for (int v = 0; v < VPT; ++v)
+            vraw[v] = src[tid + v * (NW * 64)];
     }
-    const int nblk = (N + 63) >> 6;
-    const int blk0 = (int)(((int64_t)nblk * split) / S);
-    const int blk1 = (int)(((int64_t)nblk * (split + 1)) / S);
-    const int r0 = (int)(((int64_t)R * split) / S);
-    const int r1 = (int)(((int64_t)R * (split + 1)) / S);
+    u32x4 qraw[NV];  // the query elements of columns 4g .. 4g+3 (converted after the barrier)
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+        qraw[v] = *(const u32x4 *)((const char *)a.q + (((int64_t)b * a.Hq + hq) * PQ_HEAD_DIM + e0) * sizeof(T) + v * 16);
+    __builtin_amdgcn_s_barrier();
+
+    N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
+    R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
+    // 32-bit unsigned arithmetic: the capacities are limited to 2^24 tokens and S to 64, and a
+    // 64-bit division costs more instructions than the whole table build
+    const uint32_t nblk = (uint32_t)(N + 63) >> 6;
+    const int blk0 = (int)(nblk * (uint32_t)split / (uint32_t)S);
+    const int blk1 = (int)(nblk * (uint32_t)(split + 1) / (uint32_t)S);
+    const int r0 = (int)((uint32_t)R * (uint32_t)split / (uint32_t)S);
+    const int r1 = (int)((uint32_t)R * (uint32_t)(split + 1) / (uint32_t)S);
 
     const uint8_t *k_head = a.k_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
     const uint8_t *v_head = a.v_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
 
-    code_regs<M> bufA, bufB;  // double buffer: one block is processed while the next one loads
-    int blk = blk0 + wave;
+    // Two code buffers per wavefront: one block is processed while the next one is in flight.
+    // (Deeper queues were measured to be slower: HBM saturates with a few KiB in flight per
+    // wavefront, more only lengthens the queue and with it the start-up and the drain.)
+    // Every code load is unconditional (a wavefront that has run out of blocks re-reads the
+    // block it holds, an L2 hit), so the compiler knows exactly how many loads are in flight
+    // at each use and a wait for one buffer never also drains the loads of the other.
+    code_regs<M> buf[2];
+    int blk = blk0 + wave;  // wavefront w owns blocks blk0 + w, + NW, + 2 NW, ... of the split
+    load_block<M>(buf[0], k_head, v_head, blk < blk1 ? blk : 0, lane);
 
     // ---- this lane's query sub-vector, pre-multiplied by scale * log2(e)
     const int sub = lane & (M - 1);
@@ -172,40 +216,11 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     for (int j = 0; j < DS; ++j)
         qs[j] = elem<T>::ld(a.q, ((int64_t)b * a.Hq + hq) * PQ_HEAD_DIM + sub * DS + j) * a.scale_log2e;
 
-    // ---- prologue: LUT[c][x] for x = 0..63 (for M = 32 columns x and x+32 hold the same
-    // subspace), and the value codebook image.  All global loads are issued before the
-    // first use so that the workgroup pays one memory round trip, not one per row.
-    if (blk0 < blk1) {
-        constexpr int ROWS_PER_PASS = NW * 4;              // 16 threads cover one 64-column row
-        constexpr int PASSES = 256 / ROWS_PER_PASS;
-        constexpr int NV = 4 * DS * (int)sizeof(T) / 16;   // 16-byte vectors per 4 columns
-        constexpr int VPT = 4096 / (NW * 64);              // codebook-image vectors per thread
-        const int g = tid & 15;                            // columns 4g .. 4g+3
-        const int row0 = tid >> 4;
-        const int e0 = ((4 * g) & (M - 1)) * DS;           // first element of those columns in a row
-        const char *kcb = (const char *)a.kcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM * sizeof(T);
-        u32x4 kraw[PASSES][NV];
-#pragma unroll
-        for (int k = 0; k < PASSES; ++k)
-#pragma unroll
-            for (int v = 0; v < NV; ++v)
-                kraw[k][v] = *(const u32x4 *)(kcb + ((row0 + k * ROWS_PER_PASS) * PQ_HEAD_DIM + e0) * sizeof(T) + v * 16);
-        u32x4 vraw[VPT];
-        if (F16) {
-            const u32x4 *src = (const u32x4 *)((const __half *)a.vcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM);
-#pragma unroll
-            for (int v = 0; v < VPT; ++v)
-                vraw[v] = src[tid + v * (NW * 64)];
-        }
+    {
         float qv[4 * DS];
 #pragma unroll
         for (int e = 0; e < 4 * DS; ++e)
-            qv[e] = elem<T>::ld(a.q, ((int64_t)b * a.Hq + hq) * PQ_HEAD_DIM + e0 + e) * a.scale_log2e;
-        // the first block's codes are requested behind the (small) table loads, so that the
-        // tables are not queued behind a chip-wide burst of code loads, and stream in
-        // while the tables are built
-        if (blk < blk1)
-            load_block<M>(bufA, k_head, v_head, blk, lane);
+            qv[e] = elem<T>::ld(&qraw[0], e) * a.scale_log2e;
 #pragma unroll
         for (int k = 0; k < PASSES; ++k) {
             f32x4 ent;
@@ -324,19 +339,20 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     };
 
     // two blocks per trip so that the buffers swap roles without register copies
-    while (blk < blk1) {
-        int nb = blk + NW;
-        if (nb < blk1)
-            load_block<M>(bufB, k_head, v_head, nb, lane);
-        process(bufA, blk);
-        blk = nb;
-        if (blk >= blk1)
-            break;
-        nb = blk + NW;
-        if (nb < blk1)
-            load_block<M>(bufA, k_head, v_head, nb, lane);
-        process(bufB, blk);
-        blk = nb;
+    if (blk < blk1) {
+        bool more = true;
+        while (more) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                if (more) {
+                    const int nb = blk + NW;
+                    load_block<M>(buf[j ^ 1], k_head, v_head, nb < blk1 ? nb : blk, lane);
+                    process(buf[j], blk);
+                    blk = nb;
+                    more = nb < blk1;
+                }
+            }
+        }
     }
 
     // ---------------- recent full-precision rows of this split (Eq. 7, second term)
@@ -420,14 +436,14 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
 
     // ---------------- the workgroup that takes the last ticket of this (b, hq) merges the
     // splits (flash-decoding style) and leaves the ticket counter at zero for the next call
-    __threadfence();  // release: the partial above is visible device-wide before the ticket
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // the partial above is visible device-wide before the ticket
     unsigned int ticket = 0;
     if (lane == 0)
         ticket = __hip_atomic_fetch_add(a.tickets + bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if (ticket != (unsigned int)(S - 1))
         return;
-    __threadfence();  // acquire: the other workgroups' partials
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the other workgroups' partials
     const float *ps = a.partials + (int64_t)bh * S * PQ_PART_STRIDE;
     // lane s holds (maximum, weight sum) of split s; all loads of a round are issued together
     const float2 ml = lane < S ? *(const float2 *)(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
@@ -467,6 +483,6 @@ hipError_t pq_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hip
 {
     const bool f16 = ctx->cfg.dtype == PQ_F16;
     if (ctx->cfg.n_subspaces == 64)
-        return f16 ? launch<64, 2, __half, 16>(a, s) : launch<64, 2, float, 16>(a, s);
-    return f16 ? launch<32, 4, __half, 16>(a, s) : launch<32, 4, float, 16>(a, s);
+        return f16 ? launch<64, 2, __half, 8>(a, s) : launch<64, 2, float, 8>(a, s);
+    return f16 ? launch<32, 4, __half, 8>(a, s) : launch<32, 4, float, 8>(a, s);
 }

@@ -39,6 +39,7 @@ __host__ __device__ inline int64_t pq_v_code_offset(int64_t t, int i, int M)
 // [2..3] unused, [4..4+d) unnormalised output.
 #define PQ_PART_STRIDE 132
 #define PQ_MAX_SPLITS 64
+#define PQ_MAX_TOKENS (1 << 24)  // capacity limit that keeps the kernels' index arithmetic in 32 bits
 #define PQ_HEAD_DIM 128
 #define PQ_ERRFLAG_APPEND_OVERFLOW 1u
 
@@ -69,7 +70,7 @@ struct pq_decode_args {
     float *partials;
     unsigned int *tickets;
     float scale_log2e;
-    int B, Hq, Hkv, S;
+    int B, Hq, Hkv, G, S;  // G = Hq / Hkv
     int max_context, max_recent;
     int64_t head_stride;  // bytes of one (sequence, KV head) in a code tensor
 };

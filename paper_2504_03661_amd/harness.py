@@ -77,6 +77,43 @@ class PQSession:
                          self.recent_k, self.recent_v, self.recent_len, float(scale), o)
         return o
 
+    def prepared_decode(self, scale: float, copy: int = 0):
+        """A zero-argument callable that launches decode on the CURRENT stream with the argument
+        marshalling done once (the benchmark's inner loop must not be bound by Python)."""
+        lib = B.load_library()
+        import ctypes
+        vp = ctypes.c_void_p
+        stream = int(torch.cuda.current_stream().cuda_stream) or None
+        args = (vp(self.ctx), vp(self.q.data_ptr()), vp(self.k_codes[copy].data_ptr()),
+                vp(self.v_codes[copy].data_ptr()), vp(self.ctx_len.data_ptr()), None, None,
+                vp(self.recent_k.data_ptr()) if self.recent_k is not None else None,
+                vp(self.recent_v.data_ptr()) if self.recent_v is not None else None,
+                vp(self.recent_len.data_ptr()) if self.recent_len is not None else None,
+                ctypes.c_float(float(scale)), vp(self.out.data_ptr()), vp(stream) if stream else None)
+        fn = lib.pq_attn_decode
+
+        def call():
+            rc = fn(*args)
+            if rc != 0:
+                raise B.PQAttnError(rc, "pq_attn_decode")
+        return call
+
+    def prepared_append(self, new_k: torch.Tensor, new_v: torch.Tensor, copy: int = 0):
+        lib = B.load_library()
+        import ctypes
+        vp = ctypes.c_void_p
+        stream = int(torch.cuda.current_stream().cuda_stream) or None
+        args = (vp(self.ctx), vp(new_k.data_ptr()), vp(new_v.data_ptr()), ctypes.c_int32(new_k.shape[2]), None, None,
+                vp(self.k_codes[copy].data_ptr()), vp(self.v_codes[copy].data_ptr()), vp(self.ctx_len.data_ptr()),
+                vp(stream) if stream else None)
+        fn = lib.pq_encode_append
+
+        def call():
+            rc = fn(*args)
+            if rc != 0:
+                raise B.PQAttnError(rc, "pq_encode_append")
+        return call
+
     def append(self, new_k: torch.Tensor, new_v: torch.Tensor, copy: int = 0, pass_codebooks: bool = False):
         n_new = new_k.shape[2]
         B.pq_encode_append(self.ctx, new_k, new_v, n_new,
