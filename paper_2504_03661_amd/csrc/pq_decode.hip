@@ -49,7 +49,8 @@ constexpr int LUT_OFF = 0;           // float [256][64]
 constexpr int VCB_OFF = 65536;       // fp16 image [256][256 bytes]
 constexpr int PBUF_OFF = 131072;     // float [NW][64]
 constexpr int PART_OFF = 131072 + 4096;  // float [NW][PQ_PART_STRIDE]
-constexpr int SMEM_BYTES = PART_OFF + 16 * PQ_PART_STRIDE * 4;
+constexpr int CTR_OFF = PART_OFF + 16 * PQ_PART_STRIDE * 4;  // uint32: next unowned block of the split
+constexpr int SMEM_BYTES = CTR_OFF + 16;
 constexpr float NEG_BIG = -1.0e30f;  // "no score yet": finite so that differences stay finite
 
 template <typename T> struct elem;
@@ -96,6 +97,17 @@ __device__ inline float wave_sum(float x)
 __device__ inline uint32_t comp(const uint4 &v, int r)
 {
     return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w;
+}
+
+// Takes the next unowned block of the workgroup's split from a counter in LDS.  Every lane
+// executes the atomic, lane 0 adds 1 and the others add 0, so no branch appears in the scan
+// loop (the compiler's wait-count analysis turns conservative at control-flow joins); inline
+// assembly keeps the compiler from rewriting it into a branchy single-lane form.
+__device__ inline int lds_grab(uint32_t lds_addr, uint32_t inc)
+{
+    uint32_t r;
+    asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(lds_addr), "v"(inc) : "memory");
+    return __builtin_amdgcn_readfirstlane((int)r);
 }
 
 template <int M> struct code_regs {
@@ -206,7 +218,14 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     // block it holds, an L2 hit), so the compiler knows exactly how many loads are in flight
     // at each use and a wait for one buffer never also drains the loads of the other.
     code_regs<M> buf[2];
-    int blk = blk0 + wave;  // wavefront w owns blocks blk0 + w, + NW, + 2 NW, ... of the split
+    // Wavefront w starts with block blk0 + w; every later block of the split goes to whichever
+    // wavefront asks next, so wavefronts that the memory system or the SIMD arbiter serve
+    // faster scan more and all of them reach the merge together.  (Which wavefront sums which
+    // block varies from run to run: outputs agree to fp32 rounding, not bit for bit.)
+    int blk = blk0 + wave;
+    *(lds_u32 *)(lbase + CTR_OFF) = (uint32_t)(blk0 + NW);  // same value from every thread: no branch
+    const uint32_t ctr_addr = (uint32_t)(uintptr_t)(lbase + CTR_OFF);
+    const uint32_t grab_inc = lane == 0 ? 1u : 0u;
     load_block<M>(buf[0], k_head, v_head, blk < blk1 ? blk : 0, lane);
 
     // ---- this lane's query sub-vector, pre-multiplied by scale * log2(e)
@@ -345,7 +364,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 if (more) {
-                    const int nb = blk + NW;
+                    const int nb = lds_grab(ctr_addr, grab_inc);
                     load_block<M>(buf[j ^ 1], k_head, v_head, nb < blk1 ? nb : blk, lane);
                     process(buf[j], blk);
                     blk = nb;
