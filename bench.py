@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--copies", type=int, default=0, help="distinct code-tensor copies to rotate (0 = 1 GiB worth)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no sharding, no collectives); run with --gpus 1",
@@ -74,6 +76,17 @@ def main():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        # known traffic: every launch reads 1 GiB and writes 1 GiB
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"bytes_read_per_launch": 1 << 30, "bytes_written_per_launch": 1 << 30,
+                                             "launches": 10}}))
+        return
 
     w = W.config(args.config)
     data = W.generate(w)
