@@ -149,7 +149,7 @@ def main():
 
     achieved = bytes_alg["total"] / (kernel_ms * 1e-3) / 1e9
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.txt")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
     roofline = {"bound": "hbm", "kernel": "pq_decode_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
