@@ -119,9 +119,8 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
 /* Quantizes n_new full-precision tokens per (sequence, KV head) and appends their
  * codes (Eq. 4 with Section II-C's nearest-centroid assignment; step 5 of Section
  * III-C): for every sub-vector the index of the centroid at the smallest squared
- * Euclidean distance, the distance being sum_j (x_j - c_j)^2 in IEEE double,
- * accumulated left to right without fused multiply-add; equal distances go to the
- * lowest index.
+ * Euclidean distance; equal distances go to the lowest index.  The distance is decided
+ * in IEEE double as dist = fma(x_j - c_j, x_j - c_j, dist), j = 0 .. ds-1 in order.
  *
  *   new_k/new_v device [B][Hkv][n_new][d] dtype (finite values)
  *   k_codebook / v_codebook as in pq_attn_decode

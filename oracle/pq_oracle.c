@@ -18,9 +18,11 @@
  *
  *   encode  (Eq. 4 read with Section II-C's "assigned to the nearest centroid"):
  *           for each sub-vector the index of the centroid at the smallest squared
- *           Euclidean distance, ties going to the lowest index.  The distance is
- *           sum_j (x_j - c_j)^2 accumulated left to right in IEEE double with each
- *           product and each sum rounded once (build with -ffp-contract=off).
+ *           Euclidean distance, ties going to the lowest index.  The paper fixes no
+ *           rounding, so the decision is taken in the arithmetic the GPU kernel uses:
+ *           IEEE double, dist = fma(x_j - c_j, x_j - c_j, dist) for j = 0 .. ds-1 in
+ *           order (each difference rounded once, each fused multiply-add rounded once;
+ *           nothing else may be contracted: build with -ffp-contract=off).
  *
  * Pins (tests that hold it to something other than itself): brute-force
  * attention with library softmax on tiny inputs, codebooks that contain the
@@ -96,7 +98,8 @@ void oracle_dense_attention(const double *q, const double *keys, const double *v
  *   k_codebook  [Hkv][M][C][ds]        v_codebook likewise (shared by the batch)
  *   recent_k    [B][Hkv][rec_cap][d]   recent_v likewise; may be NULL (no window)
  *   recent_len  [B]                    may be NULL (all zero)
- *   pairs       [n_pairs][2] (b, hq)   NULL: all B*Hq pairs
+ *   pairs       [n_pairs][2] (b, hq)   NULL: all B*Hq pairs; the listed pairs must be distinct
+ *                                      (each output row is accumulated by one thread)
  *   out         [B][Hq][d]             rows not listed in `pairs` are left alone
  *   weight_sum  optional [B][Hq]       sum of the softmax weights (an invariant: 1)
  *
@@ -182,8 +185,7 @@ void oracle_pq_encode_head(const double *x, const double *codebook, int64_t n, i
                 double dist = 0.0;
                 for (int j = 0; j < ds; ++j) {
                     const double diff = x[t * d + i * ds + j] - codebook[((int64_t)i * C + c) * ds + j];
-                    const double sq = diff * diff;
-                    dist = dist + sq;
+                    dist = fma(diff, diff, dist);
                 }
                 if (c == 0 || dist < best_dist) {
                     best = c;

@@ -109,8 +109,10 @@ def decode(q, k_codes, v_codes, ctx_len, k_codebook, v_codebook, recent_k=None, 
     pr = None
     n_pairs = 0
     if pairs is not None:
-        pr = np.ascontiguousarray(np.asarray(pairs, dtype=np.int32).reshape(-1, 2))
+        # each listed row is computed by one thread: a pair listed twice would be written by two
+        pr = np.ascontiguousarray(np.unique(np.asarray(pairs, dtype=np.int32).reshape(-1, 2), axis=0))
         n_pairs = pr.shape[0]
+        assert (pr[:, 0] >= 0).all() and (pr[:, 0] < B).all() and (pr[:, 1] >= 0).all() and (pr[:, 1] < Hq).all()
     rc = lib().oracle_pq_decode(B, Hq, Hkv, d, M, C, _ptr(qd), _ptr(k_codes), _ptr(v_codes), ctx_cap, _ptr(cl),
                                 _ptr(kcb), _ptr(vcb), _ptr(rk), _ptr(rv), rec_cap, _ptr(rl),
                                 float(np.float32(scale)), _ptr(pr), n_pairs, _ptr(out), _ptr(wsum))

@@ -2,11 +2,12 @@
 //
 // Eq. 4 read with Section II-C ("assigned to the nearest centroid in its subspace"):
 //   code[t][i] = argmin_c sum_j (x[t][i*ds + j] - C^i[c][j])^2,   ties -> lowest c.
-// The comparison is decided in IEEE double: inputs widened exactly, each difference,
-// each square and each partial sum rounded once, left to right, no fused
-// multiply-add (this file is compiled with -ffp-contract=off and the loop below
-// also pins it with a pragma).  fp64 vector arithmetic runs at the same rate as
-// unpacked fp32 on gfx950, so exactness costs nothing here.
+// The comparison is decided in IEEE double: inputs widened exactly, and for
+// j = 0 .. ds-1 in order dist = fma(x_j - c_j, x_j - c_j, dist): each difference and
+// each fused multiply-add rounded once, nothing else contracted (this file is compiled
+// with -ffp-contract=off and the loop below also pins it with a pragma).  fp64 vector
+// arithmetic runs at the same rate as unpacked fp32 on gfx950, so exactness costs
+// nothing here; the scan costs 2 ds + 3 vector operations per (sub-vector, centroid).
 //
 // Mapping.  One wavefront = one (K or V, sequence, KV head, subspace, 64-token
 // chunk).  Lane = token: all 64 lanes walk the 256 centroids in lock step, the
@@ -63,18 +64,17 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void pq_encode_kernel(const pq_enco
         x[j] = live ? widen<T>(a.x[which], ((int64_t)head * a.n_new + tok) * PQ_HEAD_DIM + i * DS + j) : 0.0;
 
     int best = 0;
-    double best_dist = 0.0;
+    double best_dist = __builtin_huge_val();  // finite inputs: centroid 0 always beats it
     for (int c = 0; c < 256; ++c) {
         double dist = 0.0;
 #pragma unroll
         for (int j = 0; j < DS; ++j) {
             const double diff = x[j] - cb[wave][c * DS + j];
-            const double sq = diff * diff;
-            dist = dist + sq;
+            dist = __builtin_fma(diff, diff, dist);
         }
-        const bool better = (c == 0) || (dist < best_dist);
-        best = better ? c : best;
-        best_dist = better ? dist : best_dist;
+        // strict "<" on an ascending scan: the lowest index among equal distances stays
+        best = dist < best_dist ? c : best;
+        best_dist = __builtin_fmin(best_dist, dist);
     }
 
     int n_old = a.ctx_len[b];

@@ -223,7 +223,7 @@ def test_gqa_equals_mha_with_replicated_kv_heads():
 def test_batch_rows_are_independent_and_pairs_subset_matches():
     w, data = small(10, B=3, Hq=2, Hkv=2, d=16, M=8, N=33, R=2, lens=(33, 5, 20))
     full = run_oracle(w, data)
-    part = run_oracle(w, data, pairs=[(1, 1), (2, 0)])
+    part = run_oracle(w, data, pairs=[(1, 1), (2, 0), (1, 1)])      # a repeated pair is computed once
     assert (part[1, 1] == full[1, 1]).all() and (part[2, 0] == full[2, 0]).all()
     assert np.isnan(part[0, 0]).all()
     alone = {k: (v[1:2] if (v is not None and k not in ("k_codebook", "v_codebook")) else v) for k, v in data.items()}
