@@ -7,8 +7,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpq_attn.so")
-SOURCES = ["pq_api.hip", "pq_decode.hip", "pq_encode.hip", "pq_layout.hip"]
-HEADERS = [os.path.join(CSRC, "pq_internal.h"), os.path.join(ROOT, "include", "pq_attn.h")]
+SOURCES = ["pq_api.hip", "pq_decode.hip", "pq_decode_grouped.hip", "pq_encode.hip", "pq_layout.hip"]
+HEADERS = [os.path.join(CSRC, "pq_internal.h"), os.path.join(CSRC, "pq_device_utils.h"),
+           os.path.join(ROOT, "include", "pq_attn.h")]
 
 # packed-fp32 instructions are switched off for all device code; -ffp-contract=off keeps
 # the encode distances as separately rounded IEEE operations.

@@ -56,7 +56,8 @@ int64_t padded_capacity(const pq_attn_config *c) { return ((int64_t)c->max_conte
 // at a time), but never so many that a split has less than a block per wavefront.
 int choose_splits(const pq_attn_config *c, int n_cu)
 {
-    const int64_t heads = (int64_t)c->batch * c->n_q_heads;
+    // the grouped-query kernel runs one workgroup per (sequence, KV head, split)
+    const int64_t heads = (int64_t)c->batch * (pq_config_uses_grouped_kernel(c) ? c->n_kv_heads : c->n_q_heads);
     int64_t s = (n_cu + heads - 1) / heads;
     const int64_t blocks = padded_capacity(c) / 64;
     const int64_t max_by_work = blocks / 16 > 0 ? blocks / 16 : 1;
@@ -137,6 +138,7 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     ctx->group = cfg->n_q_heads / cfg->n_kv_heads;
     ctx->cap_padded = padded_capacity(cfg);
     ctx->elem_bytes = cfg->dtype == PQ_F16 ? 2 : 4;
+    ctx->k_skew = pq_config_uses_grouped_kernel(cfg) ? PQ_K_SKEW_QUAD : PQ_K_SKEW_LANE;
     ctx->n_splits = cfg->n_splits > 0 ? cfg->n_splits : choose_splits(cfg, prop.multiProcessorCount);
 
     const size_t cb_bytes = (size_t)cfg->n_kv_heads * 256 * PQ_HEAD_DIM * ctx->elem_bytes;
@@ -232,7 +234,8 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
     a.max_context = ctx->cfg.max_context;
     a.max_recent = ctx->cfg.max_recent;
     a.head_stride = ctx->cap_padded * ctx->cfg.n_subspaces;
-    return pq_launch_decode(ctx, a, s) == hipSuccess ? PQ_OK : PQ_ERR_HIP;
+    const hipError_t e = ctx->k_skew == PQ_K_SKEW_QUAD ? pq_launch_decode_grouped(ctx, a, s) : pq_launch_decode(ctx, a, s);
+    return e == hipSuccess ? PQ_OK : PQ_ERR_HIP;
 }
 
 int pq_encode_append(pq_attn_ctx *ctx, const void *new_k, const void *new_v, int32_t n_new, const void *k_codebook,
@@ -264,6 +267,7 @@ int pq_encode_append(pq_attn_ctx *ctx, const void *new_k, const void *new_v, int
     a.Hkv = ctx->cfg.n_kv_heads;
     a.n_new = n_new;
     a.max_context = ctx->cfg.max_context;
+    a.k_skew = ctx->k_skew;
     a.head_stride = ctx->cap_padded * ctx->cfg.n_subspaces;
     return pq_launch_encode(ctx, a, ctx_len, ctx->dev_err, s) == hipSuccess ? PQ_OK : PQ_ERR_HIP;
 }

@@ -32,18 +32,9 @@
 #include <hip/hip_runtime.h>
 
 #include "pq_internal.h"
+#include "pq_device_utils.h"
 
 namespace {
-
-typedef __attribute__((address_space(3))) unsigned char lds_u8;
-typedef __attribute__((address_space(3))) float lds_f32;
-typedef __attribute__((address_space(3))) uint32_t lds_u32;
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
-typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
-typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
 
 constexpr int LUT_OFF = 0;           // float [256][64]
 constexpr int VCB_OFF = 65536;       // fp16 image [256][256 bytes]
@@ -51,82 +42,6 @@ constexpr int PBUF_OFF = 131072;     // float [NW][64]
 constexpr int PART_OFF = 131072 + 4096;  // float [NW][PQ_PART_STRIDE]
 constexpr int CTR_OFF = PART_OFF + 16 * PQ_PART_STRIDE * 4;  // uint32: next unowned block of the split
 constexpr int SMEM_BYTES = CTR_OFF + 16;
-constexpr float NEG_BIG = -1.0e30f;  // "no score yet": finite so that differences stay finite
-
-template <typename T> struct elem;
-template <> struct elem<__half> {
-    static __device__ float ld(const void *p, int64_t i) { return __half2float(((const __half *)p)[i]); }
-};
-template <> struct elem<float> {
-    static __device__ float ld(const void *p, int64_t i) { return ((const float *)p)[i]; }
-};
-
-template <int CTRL> __device__ inline float dpp_move(float x)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
-}
-
-// maximum over the 64 lanes, same value returned to every lane (wave-uniform)
-__device__ inline float wave_max(float x)
-{
-    x = fmaxf(x, dpp_move<0xB1>(x));   // quad_perm [1,0,3,2]
-    x = fmaxf(x, dpp_move<0x4E>(x));   // quad_perm [2,3,0,1]
-    x = fmaxf(x, dpp_move<0x141>(x));  // row_half_mirror
-    x = fmaxf(x, dpp_move<0x140>(x));  // row_mirror
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
-    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
-    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
-    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
-}
-
-// sum over the 64 lanes in a fixed order, wave-uniform result
-__device__ inline float wave_sum(float x)
-{
-    x += dpp_move<0xB1>(x);
-    x += dpp_move<0x4E>(x);
-    x += dpp_move<0x141>(x);
-    x += dpp_move<0x140>(x);
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
-    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
-    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
-    return (r0 + r1) + (r2 + r3);
-}
-
-__device__ inline uint32_t comp(const uint4 &v, int r)
-{
-    return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w;
-}
-
-// Takes the next unowned block of the workgroup's split from a counter in LDS.  Every lane
-// executes the atomic, lane 0 adds 1 and the others add 0, so no branch appears in the scan
-// loop (the compiler's wait-count analysis turns conservative at control-flow joins); inline
-// assembly keeps the compiler from rewriting it into a branchy single-lane form.
-__device__ inline int lds_grab(uint32_t lds_addr, uint32_t inc)
-{
-    uint32_t r;
-    asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(lds_addr), "v"(inc) : "memory");
-    return __builtin_amdgcn_readfirstlane((int)r);
-}
-
-template <int M> struct code_regs {
-    uint4 k[M / 16];
-    uint4 v[M / 16];
-};
-
-template <int M>
-__device__ inline void load_block(code_regs<M> &c, const uint8_t *k_head, const uint8_t *v_head, int blk, int lane)
-{
-    const uint4 *kp = (const uint4 *)(k_head + (int64_t)blk * (64 * M)) + lane;
-    const uint4 *vp = (const uint4 *)(v_head + (int64_t)blk * (64 * M)) + lane;
-#pragma unroll
-    for (int j = 0; j < M / 16; ++j) {
-        c.k[j] = kp[j * 64];
-        c.v[j] = vp[j * 64];
-    }
-}
-
 template <int M, int DS, typename T, int NW>
 __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args a)
 {

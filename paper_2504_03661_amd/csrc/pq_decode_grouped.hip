@@ -1,0 +1,370 @@
+// Decode attention over a product-quantized KV cache for grouped queries (2..4 query heads
+// per KV head, fp16, M = 64 subspaces of 2 dims): one fused kernel per call.
+//
+// Same result as the per-head table kernel (Eq. 7 = Eq. 6), different evaluation.  With G
+// query heads reading one KV head, per-head score tables cost G x 64 KiB of LDS and G times
+// the gather and add work per code byte: the scan turns ALU/LDS bound at a fraction of the HBM
+// rate.  Here the codes of a KV head are gathered ONCE and the contraction over the query
+// heads — a genuine small dense product — goes to the matrix cores:
+//
+//   score pass  lane = token.  The K CODEBOOK image (not a per-query table) sits in LDS; a
+//               lane gathers the two centroids of a 4-dim slice of its token (2 x ds_read_b32)
+//               and v_mfma_f32_4x4x4_16B_f16 multiplies, per quad of lanes, the 4 heads' query
+//               slice (A, 4 heads x 4 dims, from LDS) with the quad's 4 tokens (B, 4 dims x 4
+//               tokens): 32 instructions give all G scores of 64 tokens.  fp16 x fp16 products
+//               are exact in the fp32 accumulator.  The instruction needs the 4 lanes of a quad
+//               on the same dims, so the K code layout rotates by quad (PQ_K_SKEW_QUAD): the 16
+//               quads of a gather touch 16 different table columns, 4 lanes each (a 4-way LDS
+//               bank conflict, measured at 8 cycles per gather instead of 2).
+//   softmax     per head: wave maximum, running maximum / rescale; the weights are split into
+//               an fp16 high and low part (p = hi + lo to 2^-22) and staged in LDS.
+//   value pass  lane = subspace, as in the per-head kernel: one gather per code byte from the V
+//               codebook image.  Four tokens' centroid pairs are re-packed (4 x v_perm) into
+//               the B operands of the same 4x4x4 instruction, whose A operand holds the 4 heads'
+//               weights of those 4 tokens: 4 instructions (x / y dims, hi / lo weights) per 4
+//               tokens accumulate all G output rows; lane l ends up with dims 2l, 2l+1 of every
+//               head.
+// Vector-ALU work per code byte no longer grows with G; the per-head kernel remains the
+// choice for G = 1 (its gathers are conflict-free) and serves every other shape.
+//
+// One workgroup = one (sequence, KV head, context split).  Schedule, block hand-out, recent
+// rows, split merge and ticket protocol follow the per-head kernel.
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include "pq_internal.h"
+#include "pq_device_utils.h"
+
+namespace {
+
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
+
+constexpr int GNW = 8;                       // wavefronts per workgroup
+constexpr int GMAX = 4;                      // rows of the 4x4x4 instruction = query heads per KV head
+constexpr int KIMG_OFF = 0;                  // fp16 K codebook image [256][256 bytes]
+constexpr int VIMG_OFF = 65536;              // fp16 V codebook image [256][256 bytes]
+constexpr int Q_OFF = 131072;                // fp16 q [4][128]
+constexpr int PST_OFF = Q_OFF + 1024;        // per wavefront: hi [4][64] fp16, lo [4][64] fp16
+constexpr int GPART_OFF = PST_OFF + GNW * 1024;              // float [GNW][4][PQ_PART_STRIDE]
+constexpr int GCTR_OFF = GPART_OFF + GNW * GMAX * PQ_PART_STRIDE * 4;
+constexpr int GSMEM_BYTES = GCTR_OFF + 16;
+static_assert(GSMEM_BYTES <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+
+__device__ inline f16x4 as_f16x4(uint32_t lo, uint32_t hi)
+{
+    u32x2 v = {lo, hi};
+    return __builtin_bit_cast(f16x4, v);
+}
+
+__global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_decode_args a)
+{
+    constexpr int M = 64;
+    constexpr int NW = GNW;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[GSMEM_BYTES];
+    lds_u8 *lbase = (lds_u8 *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int G = a.G;
+
+    const uint32_t grid = gridDim.x;
+    uint32_t logical = blockIdx.x;
+    if ((grid & 7u) == 0)
+        logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
+    const int S = a.S;
+    const int bkv = (int)(logical / (uint32_t)S);  // b * Hkv + hkv
+    const int split = (int)(logical - (uint32_t)bkv * (uint32_t)S);
+    const int b = (int)((uint32_t)bkv / (uint32_t)a.Hkv);
+    const int hkv = bkv - b * a.Hkv;
+    const int bh0 = b * a.Hq + hkv * G;            // first query head of the group
+
+    int N = a.ctx_len[b];
+    int R = (a.recent_k != nullptr && a.recent_len != nullptr) ? a.recent_len[b] : 0;
+
+    // ---- prologue: both codebook images and the group's queries; table loads first, bare
+    // barrier, then the first code block (see the per-head kernel for why)
+    constexpr int VPT = 8192 / (NW * 64);  // 16-byte vectors per thread for the two images
+    u32x4 raw[VPT];
+    {
+        const u32x4 *ksrc = (const u32x4 *)((const __half *)a.kcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM);
+        const u32x4 *vsrc = (const u32x4 *)((const __half *)a.vcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM);
+#pragma unroll
+        for (int v = 0; v < VPT / 2; ++v) {
+            raw[v] = ksrc[tid + v * (NW * 64)];
+            raw[VPT / 2 + v] = vsrc[tid + v * (NW * 64)];
+        }
+    }
+    // q of the group: G x 128 fp16 = G x 16 vectors; heads beyond G are zero rows
+    u32x4 qraw = {0u, 0u, 0u, 0u};
+    if (tid < 16 * G)
+        qraw = *((const u32x4 *)((const __half *)a.q + (int64_t)bh0 * PQ_HEAD_DIM) + tid);
+    __builtin_amdgcn_s_barrier();
+
+    N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
+    R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
+    const uint32_t nblk = (uint32_t)(N + 63) >> 6;
+    const int blk0 = (int)(nblk * (uint32_t)split / (uint32_t)S);
+    const int blk1 = (int)(nblk * (uint32_t)(split + 1) / (uint32_t)S);
+    const int r0 = (int)((uint32_t)R * (uint32_t)split / (uint32_t)S);
+    const int r1 = (int)((uint32_t)R * (uint32_t)(split + 1) / (uint32_t)S);
+    const uint8_t *k_head = a.k_codes + (int64_t)bkv * a.head_stride;
+    const uint8_t *v_head = a.v_codes + (int64_t)bkv * a.head_stride;
+
+    code_regs<M> buf[2];
+    int blk = blk0 + wave;
+    *(lds_u32 *)(lbase + GCTR_OFF) = (uint32_t)(blk0 + NW);
+    const uint32_t ctr_addr = (uint32_t)(uintptr_t)(lbase + GCTR_OFF);
+    const uint32_t grab_inc = lane == 0 ? 1u : 0u;
+    load_block<M>(buf[0], k_head, v_head, blk < blk1 ? blk : 0, lane);
+
+#pragma unroll
+    for (int v = 0; v < VPT / 2; ++v) {
+        *(lds_u32x4 *)(lbase + KIMG_OFF + (tid + v * (NW * 64)) * 16) = raw[v];
+        *(lds_u32x4 *)(lbase + VIMG_OFF + (tid + v * (NW * 64)) * 16) = raw[VPT / 2 + v];
+    }
+    if (tid < 64)
+        *(lds_u32x4 *)(lbase + Q_OFF + tid * 16) = qraw;
+    __syncthreads();
+
+    // this lane's own output dims (2 lane, 2 lane + 1) of every head's query, as scaled fp32, for the recent rows
+    float qf[GMAX][2];
+#pragma unroll
+    for (int g = 0; g < GMAX; ++g) {
+        const uint32_t w = *(lds_u32 *)(lbase + Q_OFF + g * 256 + lane * 4);
+        const __half2 h = *(const __half2 *)&w;
+        qf[g][0] = __low2float(h) * a.scale_log2e;
+        qf[g][1] = __high2float(h) * a.scale_log2e;
+    }
+
+    const int quad = lane >> 2;  // the 4x4x4 block of this lane
+    const int row = lane & 3;    // its row: query head as an A operand, token / dim as a B operand
+    // score pass: column bytes, byte k of idx[r] = 4 * ((4r + k + 4 quad) % 64)
+    uint32_t idx[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            v |= (uint32_t)(((4 * r + k + 4 * quad) & 63) << 2) << (8 * k);
+        idx[r] = v;
+    }
+    const uint32_t vcol = (uint32_t)(lane * 4) | ((VIMG_OFF >> 16) << 8);
+    // A operand of the score pass at step u: q[row][4 sigma .. 4 sigma + 3], sigma = (u + 2 quad) % 32
+    const uint32_t qa_base = (uint32_t)(Q_OFF + row * 256);
+
+    float m_run[GMAX], l_lane[GMAX];
+    f32x4 accx = {0.f, 0.f, 0.f, 0.f}, accy = {0.f, 0.f, 0.f, 0.f};  // element g: head g, dims 2 lane / 2 lane + 1
+#pragma unroll
+    for (int g = 0; g < GMAX; ++g) {
+        m_run[g] = NEG_BIG;
+        l_lane[g] = 0.f;
+    }
+    lds_u8 *pst = lbase + PST_OFF + wave * 1024;  // hi at [g][token] * 2, lo at 512 + the same
+
+    auto process = [&](const code_regs<M> &cur, const int blk_id) {
+        // ---------------- score pass: sc[g] = q_g . K^_token for this lane's token
+        f32x4 sc0 = {0.f, 0.f, 0.f, 0.f}, sc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 32; ++u) {
+            const uint32_t w = comp(cur.k[u >> 3], (u >> 1) & 3);
+            const int e = 2 * (u & 1);
+            const uint32_t a0 = __builtin_amdgcn_perm(w, idx[u >> 1], 0x0c0c0000u | ((4 + e) << 8) | e);
+            const uint32_t a1 = __builtin_amdgcn_perm(w, idx[u >> 1], 0x0c0c0000u | ((5 + e) << 8) | (e + 1));
+            const uint32_t c0 = *(lds_u32 *)(lbase + a0);
+            const uint32_t c1 = *(lds_u32 *)(lbase + a1);
+            const uint32_t sigma = (uint32_t)(u + 2 * quad) & 31u;
+            const u32x2 qa = *(lds_u32x2 *)(lbase + qa_base + sigma * 8);
+            const f16x4 A = __builtin_bit_cast(f16x4, qa);
+            const f16x4 B = as_f16x4(c0, c1);
+            if (u & 1)
+                sc1 = __builtin_amdgcn_mfma_f32_4x4x4f16(A, B, sc1, 0, 0, 0);
+            else
+                sc0 = __builtin_amdgcn_mfma_f32_4x4x4f16(A, B, sc0, 0, 0, 0);
+        }
+        const bool valid = blk_id * 64 + lane < N;
+
+        // ---------------- running softmax, one per head; weights staged as fp16 hi + lo
+#pragma unroll
+        for (int g = 0; g < GMAX; ++g) {
+            const float s = valid ? (sc0[g] + sc1[g]) * a.scale_log2e : NEG_BIG;
+            const float m_new = fmaxf(m_run[g], wave_max(s));
+            const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_new);
+            const float p = valid ? __builtin_amdgcn_exp2f(s - m_new) : 0.f;
+            l_lane[g] = fmaf(l_lane[g], alpha, p);
+            accx[g] *= alpha;
+            accy[g] *= alpha;
+            m_run[g] = m_new;
+            const _Float16 hi = (_Float16)p;
+            const _Float16 lo = (_Float16)(p - (float)hi);
+            *(lds_u16 *)(pst + g * 128 + lane * 2) = __builtin_bit_cast(uint16_t, hi);
+            *(lds_u16 *)(pst + 512 + g * 128 + lane * 2) = __builtin_bit_cast(uint16_t, lo);
+        }
+        __builtin_amdgcn_wave_barrier();
+
+        // ---------------- value pass: 4 tokens per step
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t w = comp(cur.v[n], r);
+                const int tok0 = 16 * n + 4 * r;
+                uint32_t c[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t addr = __builtin_amdgcn_perm(w, vcol, 0x0c010000u | ((4 + k) << 8));
+                    c[k] = *(lds_u32 *)(lbase + addr);
+                }
+                // B operands: this lane's x (then y) coordinate of the 4 tokens
+                const f16x4 Bx = as_f16x4(__builtin_amdgcn_perm(c[1], c[0], 0x05040100u),
+                                          __builtin_amdgcn_perm(c[3], c[2], 0x05040100u));
+                const f16x4 By = as_f16x4(__builtin_amdgcn_perm(c[1], c[0], 0x07060302u),
+                                          __builtin_amdgcn_perm(c[3], c[2], 0x07060302u));
+                // A operands: weights of head `row` for the 4 tokens
+                const f16x4 Ahi = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(pst + row * 128 + tok0 * 2));
+                const f16x4 Alo = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(pst + 512 + row * 128 + tok0 * 2));
+                accx = __builtin_amdgcn_mfma_f32_4x4x4f16(Ahi, Bx, accx, 0, 0, 0);
+                accy = __builtin_amdgcn_mfma_f32_4x4x4f16(Ahi, By, accy, 0, 0, 0);
+                accx = __builtin_amdgcn_mfma_f32_4x4x4f16(Alo, Bx, accx, 0, 0, 0);
+                accy = __builtin_amdgcn_mfma_f32_4x4x4f16(Alo, By, accy, 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    if (blk < blk1) {
+        bool more = true;
+        while (more) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                if (more) {
+                    const int nb = lds_grab(ctr_addr, grab_inc);
+                    load_block<M>(buf[j ^ 1], k_head, v_head, nb < blk1 ? nb : blk, lane);
+                    process(buf[j], blk);
+                    blk = nb;
+                    more = nb < blk1;
+                }
+            }
+        }
+    }
+
+    // ---------------- recent full-precision rows of this split, all heads of the group
+    {
+        const int64_t rbase = (int64_t)bkv * a.max_recent;
+        for (int r = r0 + wave; r < r1; r += NW) {
+            const uint32_t kw = *((const uint32_t *)((const __half *)a.recent_k + (rbase + r) * PQ_HEAD_DIM) + lane);
+            const uint32_t vw = *((const uint32_t *)((const __half *)a.recent_v + (rbase + r) * PQ_HEAD_DIM) + lane);
+            const __half2 kh = *(const __half2 *)&kw, vh = *(const __half2 *)&vw;
+            const float k0 = __low2float(kh), k1 = __high2float(kh), v0 = __low2float(vh), v1 = __high2float(vh);
+#pragma unroll
+            for (int g = 0; g < GMAX; ++g) {
+                const float s = wave_sum(fmaf(qf[g][0], k0, qf[g][1] * k1));
+                const float m_new = fmaxf(m_run[g], s);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_new);
+                const float p = __builtin_amdgcn_exp2f(s - m_new);
+                l_lane[g] = fmaf(l_lane[g], alpha, lane == 0 ? p : 0.f);
+                accx[g] = fmaf(accx[g], alpha, p * v0);
+                accy[g] = fmaf(accy[g], alpha, p * v1);
+                m_run[g] = m_new;
+            }
+        }
+    }
+
+    // ---------------- merge the wavefronts of this workgroup
+    {
+        lds_f32 *part = (lds_f32 *)(lbase + GPART_OFF) + wave * GMAX * PQ_PART_STRIDE;
+#pragma unroll
+        for (int g = 0; g < GMAX; ++g) {
+            const float l_w = wave_sum(l_lane[g]);
+            if (lane == 0) {
+                part[g * PQ_PART_STRIDE] = m_run[g];
+                part[g * PQ_PART_STRIDE + 1] = l_w;
+            }
+            part[g * PQ_PART_STRIDE + 4 + 2 * lane] = accx[g];
+            part[g * PQ_PART_STRIDE + 5 + 2 * lane] = accy[g];
+        }
+    }
+    __syncthreads();
+    if (wave != 0)
+        return;
+
+    // wavefront 0: merge per head, publish the split partials, one ticket per (sequence, KV head)
+    const lds_f32 *parts = (const lds_f32 *)(lbase + GPART_OFF);
+    for (int g = 0; g < G; ++g) {
+        float mx = NEG_BIG;
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+            mx = fmaxf(mx, parts[(w * GMAX + g) * PQ_PART_STRIDE]);
+        float o0 = 0.f, o1 = 0.f, l = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const lds_f32 *pw = parts + (w * GMAX + g) * PQ_PART_STRIDE;
+            const float f = __builtin_amdgcn_exp2f(pw[0] - mx);
+            o0 = fmaf(pw[4 + 2 * lane], f, o0);
+            o1 = fmaf(pw[5 + 2 * lane], f, o1);
+            l = fmaf(pw[1], f, l);
+        }
+        if (S == 1) {
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            *(float2 *)(a.out + (int64_t)(bh0 + g) * PQ_HEAD_DIM + 2 * lane) = make_float2(o0 * inv, o1 * inv);
+        } else {
+            float *gpart = a.partials + ((int64_t)(bh0 + g) * S + split) * PQ_PART_STRIDE;
+            *(float2 *)(gpart + 4 + 2 * lane) = make_float2(o0, o1);
+            if (lane == 0)
+                *(float2 *)gpart = make_float2(mx, l);
+        }
+    }
+    if (S == 1)
+        return;
+
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // the partials above are visible device-wide before the ticket
+    unsigned int ticket = 0;
+    if (lane == 0)
+        ticket = __hip_atomic_fetch_add(a.tickets + bh0, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    ticket = __builtin_amdgcn_readfirstlane(ticket);
+    if (ticket != (unsigned int)(S - 1))
+        return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the other workgroups' partials
+    for (int g = 0; g < G; ++g) {
+        const float *ps = a.partials + (int64_t)(bh0 + g) * S * PQ_PART_STRIDE;
+        const float2 ml = lane < S ? *(const float2 *)(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
+        const float mx = wave_max(ml.x);
+        const float f_lane = __builtin_amdgcn_exp2f(ml.x - mx);
+        const float l = wave_sum(ml.y * f_lane);
+        float o0 = 0.f, o1 = 0.f;
+        for (int s0 = 0; s0 < S; s0 += 8) {
+            float2 o[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                o[u] = s0 + u < S ? *(const float2 *)(ps + (s0 + u) * PQ_PART_STRIDE + 4 + 2 * lane)
+                                  : make_float2(0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), (s0 + u) & 63));
+                o0 = fmaf(o[u].x, f, o0);
+                o1 = fmaf(o[u].y, f, o1);
+            }
+        }
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        *(float2 *)(a.out + (int64_t)(bh0 + g) * PQ_HEAD_DIM + 2 * lane) = make_float2(o0 * inv, o1 * inv);
+    }
+    if (lane == 0)
+        a.tickets[bh0] = 0u;
+}
+
+}  // namespace
+
+bool pq_config_uses_grouped_kernel(const pq_attn_config *cfg)
+{
+    const int g = cfg->n_kv_heads > 0 ? cfg->n_q_heads / cfg->n_kv_heads : 0;
+    return cfg->dtype == PQ_F16 && cfg->n_subspaces == 64 && cfg->head_dim == PQ_HEAD_DIM && g >= 2 && g <= GMAX;
+}
+
+hipError_t pq_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
+{
+    (void)ctx;
+    const int grid = a.B * a.Hkv * a.S;
+    hipLaunchKernelGGL(pq_decode_grouped_kernel, dim3(grid), dim3(GNW * 64), 0, s, a);
+    return hipGetLastError();
+}

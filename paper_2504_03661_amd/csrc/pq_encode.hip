@@ -82,7 +82,7 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void pq_encode_kernel(const pq_enco
     const int64_t pos = (int64_t)n_old + tok;
     if (live && pos < a.max_context) {
         uint8_t *dst = a.codes[which] + (int64_t)head * a.head_stride;
-        const int64_t off = which == 0 ? pq_k_code_offset(pos, i, M) : pq_v_code_offset(pos, i, M);
+        const int64_t off = which == 0 ? pq_k_code_offset(pos, i, M, a.k_skew) : pq_v_code_offset(pos, i, M);
         dst[off] = (uint8_t)best;
     }
 }

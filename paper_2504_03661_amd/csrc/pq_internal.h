@@ -16,17 +16,24 @@
 // whatever the code values are.  A block holds 64 tokens, M bytes each, as M/16
 // chunks of 1 KiB; chunk k holds, for lane l = t % 64, the 16 bytes that lane
 // consumes at steps s = 16k .. 16k+15, and the byte at step s is the code of
-// subspace (s + l) % M.  One wavefront load of a chunk is 1 KiB contiguous.
+// subspace (s + rot) % M.  One wavefront load of a chunk is 1 KiB contiguous.
+// rot = l for the per-head table kernel (every lane on its own column); rot = l rounded down to
+// a multiple of 4 for the grouped-query kernel, whose 4x4x4 matrix instruction makes the four
+// tokens of a lane quad walk the same dimensions together (PQ_K_SKEW_LANE / PQ_K_SKEW_QUAD).
 //
 // V codes ("16-token tiles, subspace-major"): the value pass gives every lane one
 // subspace (lane = output dims) and walks tokens; a tile is 16 tokens x M
 // subspaces with the 16 tokens of one subspace contiguous, so a lane's 16-byte
 // load is its subspace's next 16 tokens and a wavefront load is 1 KiB contiguous.
 // ---------------------------------------------------------------------------------
-__host__ __device__ inline int64_t pq_k_code_offset(int64_t t, int i, int M)
+#define PQ_K_SKEW_LANE 0
+#define PQ_K_SKEW_QUAD 1
+
+__host__ __device__ inline int64_t pq_k_code_offset(int64_t t, int i, int M, int skew)
 {
     const int l = (int)(t & 63);
-    const int s = (i - l) & (M - 1);  // M is a power of two
+    const int rot = skew == PQ_K_SKEW_QUAD ? (l & ~3) : l;
+    const int s = (i - rot) & (M - 1);  // M is a power of two
     return (t >> 6) * (64 * (int64_t)M) + (int64_t)(s >> 4) * 1024 + l * 16 + (s & 15);
 }
 
@@ -48,6 +55,7 @@ struct pq_attn_ctx {
     int ds;               // sub-vector width
     int group;            // Hq / Hkv
     int n_splits;
+    int k_skew;           // PQ_K_SKEW_*: which decode kernel this context runs, hence its K code layout
     int64_t cap_padded;   // max_context rounded up to 64 tokens
     size_t elem_bytes;    // 2 or 4
     void *kcb_packed;     // [Hkv][256][M][ds] dtype   (centroid-major)
@@ -81,11 +89,15 @@ struct pq_encode_args {
     uint8_t *codes[2];
     const int32_t *ctx_len;
     int B, Hkv, n_new, max_context;
+    int k_skew;
     int64_t head_stride;
 };
 
 // launchers (each returns hipGetLastError() after its launches)
 hipError_t pq_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
+hipError_t pq_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
+// true when the grouped-query kernel serves this configuration (fp16, M = 64, 2..4 query heads per KV head)
+bool pq_config_uses_grouped_kernel(const pq_attn_config *cfg);
 hipError_t pq_launch_encode(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len, unsigned int *dev_err,
                             hipStream_t s);
 hipError_t pq_launch_pack_codebook(const pq_attn_ctx *ctx, const void *src, void *dst, hipStream_t s);

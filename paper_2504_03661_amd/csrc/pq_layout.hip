@@ -26,7 +26,7 @@ __global__ void pq_pack_codebook_kernel(const E *src, E *dst, int Hkv, int M, in
 
 // one thread per code byte of the token-major tensor
 __global__ void pq_pack_codes_kernel(const uint8_t *token_major, uint8_t *packed, int64_t n_heads, int n_tokens,
-                                     int M, int64_t head_stride, int kind, int unpack)
+                                     int M, int64_t head_stride, int kind, int unpack, int k_skew)
 {
     const int64_t total = n_heads * n_tokens * M;
     const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -35,7 +35,7 @@ __global__ void pq_pack_codes_kernel(const uint8_t *token_major, uint8_t *packed
     const int i = (int)(x % M);
     const int64_t t = (x / M) % n_tokens;
     const int64_t h = x / ((int64_t)M * n_tokens);
-    const int64_t off = h * head_stride + (kind == PQ_CODES_K ? pq_k_code_offset(t, i, M) : pq_v_code_offset(t, i, M));
+    const int64_t off = h * head_stride + (kind == PQ_CODES_K ? pq_k_code_offset(t, i, M, k_skew) : pq_v_code_offset(t, i, M));
     if (unpack)
         const_cast<uint8_t *>(token_major)[x] = packed[off];
     else
@@ -68,6 +68,6 @@ hipError_t pq_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint8_t 
         return hipSuccess;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     hipLaunchKernelGGL(pq_pack_codes_kernel, grid, block, 0, s, token_major, packed, n_heads, n_tokens, M,
-                       ctx->cap_padded * M, kind, unpack ? 1 : 0);
+                       ctx->cap_padded * M, kind, unpack ? 1 : 0, ctx->k_skew);
     return hipGetLastError();
 }

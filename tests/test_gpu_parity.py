@@ -45,9 +45,10 @@ def gpu_decode(w, data, n_splits=0, max_context=None, pass_codebooks=False):
 # ------------------------------------------------------------------ layouts
 
 
-def k_offset(t, i, M):
+def k_offset(t, i, M, quad_skew=False):
     lane = t % 64
-    s = (i - lane) % M
+    rot = (lane // 4) * 4 if quad_skew else lane
+    s = (i - rot) % M
     return (t // 64) * 64 * M + (s // 16) * 1024 + lane * 16 + s % 16
 
 
@@ -55,13 +56,17 @@ def v_offset(t, i, M):
     return (t // 16) * 16 * M + i * 16 + t % 16
 
 
-@pytest.mark.parametrize("M", [64, 32])
-def test_pack_layouts_and_unpack_roundtrip(M):
-    w = W.Workload("p", 2, 2, 2, 128, M, 200, "f16", seed=5)
+@pytest.mark.parametrize("M,Hq", [(64, 2), (32, 2), (64, 8), (32, 8)])
+def test_pack_layouts_and_unpack_roundtrip(M, Hq):
+    """Hq = 8 over 2 KV heads with M = 64 is served by the grouped-query kernel, whose K layout
+    rotates by lane quad instead of by lane."""
+    w = W.Workload("p", 2, Hq, 2, 128, M, 200, "f16", seed=5)
     data = W.generate(w)
-    with PQSession(data, 2, "f16") as s:
+    quad = (M == 64 and Hq == 8)
+    with PQSession(data, Hq, "f16") as s:
         cap = 256
-        for kind, off, src in ((PQ_CODES_K, k_offset, data["k_codes"]), (PQ_CODES_V, v_offset, data["v_codes"])):
+        koff = lambda t, i, M: k_offset(t, i, M, quad)
+        for kind, off, src in ((PQ_CODES_K, koff, data["k_codes"]), (PQ_CODES_V, v_offset, data["v_codes"])):
             packed = (s.k_codes if kind == PQ_CODES_K else s.v_codes)[0].cpu().numpy().reshape(2, 2, cap * M)
             t = np.arange(200)[:, None]
             i = np.arange(M)[None, :]
@@ -87,6 +92,12 @@ CASES = [
     ("mha_m64_f16_s1", 3, 4, 4, 64, "f16", (1000, 64, 2085), 40, 1),
     ("mha_m64_f16_s7", 2, 2, 2, 64, "f16", (5000, 129), 17, 7),
     ("gqa_m64_f16", 2, 8, 2, 64, "f16", (3001, 640), 33, 3),
+    ("gqa4_m64_f16_s1", 2, 8, 2, 64, "f16", (3001, 640), 33, 1),
+    ("gqa2_m64_f16", 3, 4, 2, 64, "f16", (1000, 64, 2085), 40, 0),
+    ("gqa3_m64_f16", 1, 6, 2, 64, "f16", (4097,), 7, 5),
+    ("gqa8_m64_f16_per_head", 1, 8, 1, 64, "f16", (1500,), 7, 2),
+    ("gqa4_m64_f32_per_head", 1, 4, 1, 64, "f32", (700,), 7, 2),
+    ("gqa_edges", 6, 8, 2, 64, "f16", (0, 1, 63, 64, 65, 0), 8, 4),
     ("mha_m32_f16", 2, 4, 4, 32, "f16", (777, 4096), 20, 0),
     ("gqa_m32_f16_s5", 2, 8, 4, 32, "f16", (1500, 63), 9, 5),
     ("mha_m64_f32", 2, 2, 2, 64, "f32", (900, 65), 12, 2),
@@ -102,15 +113,18 @@ def test_decode_small(case):
     w = W.Workload(name, B, Hq, Hkv, 128, M, cap, dtype, recent_cap=rcap, recent_uniform=True, seed=zlib.crc32(name.encode()) % 10000,
                    ctx_lens=lens)
     data = W.generate(w)
-    if name == "edges":
+    if name.endswith("edges"):
         data["recent_len"][:] = [0, 0, 3, 0, 7, 5]     # sequence 0: nothing at all; sequence 5: window only
+        fill = np.random.default_rng(7)                # the generator poisoned rows beyond ITS lengths: redraw all
+        data["recent_k"][:] = fill.standard_normal(data["recent_k"].shape).astype(data["recent_k"].dtype)
+        data["recent_v"][:] = fill.standard_normal(data["recent_v"].shape).astype(data["recent_v"].dtype)
         for b in range(B):
             data["recent_k"][b, :, data["recent_len"][b]:] = np.nan
             data["recent_v"][b, :, data["recent_len"][b]:] = np.nan
     got = gpu_decode(w, data, n_splits=splits)
     ref = oracle_out(w, data)
     check(got, ref, name)
-    if name == "edges":
+    if name.endswith("edges"):
         assert (got[0] == 0).all()                      # empty sequence -> zeros row
 
 
@@ -141,17 +155,17 @@ def test_repeated_calls_reuse_tickets_and_scratch():
 # ------------------------------------------------------------------ encode / append
 
 
-@pytest.mark.parametrize("M,dtype,n_new,n_old", [(32, "f16", 64, 100), (64, "f16", 70, 0), (32, "f32", 5, 60),
-                                                 (64, "f32", 129, 3)])
-def test_encode_append_bit_exact_then_decode(M, dtype, n_new, n_old):
+@pytest.mark.parametrize("M,dtype,n_new,n_old,Hq", [(32, "f16", 64, 100, 4), (64, "f16", 70, 0, 4), (32, "f32", 5, 60, 4),
+                                                    (64, "f32", 129, 3, 4), (64, "f16", 77, 150, 16)])
+def test_encode_append_bit_exact_then_decode(M, dtype, n_new, n_old, Hq):
     ctx = n_old + n_new
-    w = W.Workload("enc", 2, 4, 4, 128, M, ctx, dtype, n_new=n_new, seed=100 + M + n_new)
+    w = W.Workload("enc", 2, Hq, 4, 128, M, ctx, dtype, n_new=n_new, seed=100 + M + n_new)
     data = W.generate(w, ctx_cap=ctx + 10)
     # plant exact ties: duplicated centroid rows in some subspaces
     for cb in (data["k_codebook"], data["v_codebook"]):
         cb[:, 0, 200] = cb[:, 0, 17]
         cb[:, 3, 5] = cb[:, 3, 250]
-    with PQSession(data, 4, dtype, max_context=ctx + 10) as s:
+    with PQSession(data, Hq, dtype, max_context=ctx + 10) as s:
         s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())
         torch.cuda.synchronize()
         assert s.ctx_len.cpu().tolist() == [ctx, ctx]
