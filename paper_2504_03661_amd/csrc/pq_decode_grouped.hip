@@ -40,15 +40,23 @@ namespace {
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) uint16_t lds_u16;
 
-constexpr int GNW = 8;                       // wavefronts per workgroup
+constexpr int GNW = 16;                      // wavefronts per workgroup (4 per SIMD: this kernel is bound by LDS and
+                                             // instruction latency, not by HBM queues)
 constexpr int GMAX = 4;                      // rows of the 4x4x4 instruction = query heads per KV head
 constexpr int KIMG_OFF = 0;                  // fp16 K codebook image [256][256 bytes]
 constexpr int VIMG_OFF = 65536;              // fp16 V codebook image [256][256 bytes]
-constexpr int Q_OFF = 131072;                // fp16 q [4][128]
-constexpr int PST_OFF = Q_OFF + 1024;        // per wavefront: hi [4][64] fp16, lo [4][64] fp16
-constexpr int GPART_OFF = PST_OFF + GNW * 1024;              // float [GNW][4][PQ_PART_STRIDE]
-constexpr int GCTR_OFF = GPART_OFF + GNW * GMAX * PQ_PART_STRIDE * 4;
+// Rows of the two A-operand tables are padded by 8 bytes: the 4 lanes of a quad read the same
+// offset of 4 different rows, and an unpadded row stride is a multiple of the bank count.
+constexpr int Q_ROW = 256 + 8;               // bytes per head of q
+constexpr int Q_OFF = 131072;                // fp16 q [4][128 (+4)]
+constexpr int P_ROW = 128 + 8;               // bytes per head of staged weights
+constexpr int PST_WAVE = 2 * GMAX * P_ROW;   // per wavefront: hi [4][64 (+4)] fp16, then lo likewise
+constexpr int PST_OFF = Q_OFF + 1088;
+constexpr int GCTR_OFF = PST_OFF + GNW * PST_WAVE;  // uint32 block counter, uint32 "last ticket" flag
 constexpr int GSMEM_BYTES = GCTR_OFF + 16;
+// wavefront partials float [GNW][4][PQ_PART_STRIDE] reuse the K image once every wavefront has left the scan
+constexpr int GPART_OFF = KIMG_OFF;
+static_assert(GNW * GMAX * PQ_PART_STRIDE * 4 <= 65536, "partials fit in the K image");
 static_assert(GSMEM_BYTES <= 160 * 1024, "LDS budget of a gfx950 compute unit");
 
 __device__ inline f16x4 as_f16x4(uint32_t lo, uint32_t hi)
@@ -112,31 +120,39 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const uint8_t *k_head = a.k_codes + (int64_t)bkv * a.head_stride;
     const uint8_t *v_head = a.v_codes + (int64_t)bkv * a.head_stride;
 
-    code_regs<M> buf[2];
+    // One K and one V buffer per wavefront, each refilled as soon as its pass is over: the V codes
+    // of a block are requested when its score pass starts, the K codes of the next block when
+    // that score pass ends.  With 4 wavefronts per SIMD that is enough to keep the loads ahead.
+    uint4 kbuf[4], vbuf[4];
+    auto load_k = [&](uint4 (&dst)[4], int blk_id) {
+        const uint4 *kp = (const uint4 *)(k_head + (int64_t)blk_id * (64 * M)) + lane;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            dst[j] = kp[j * 64];
+    };
+    auto load_v = [&](int blk_id) {
+        const uint4 *vp = (const uint4 *)(v_head + (int64_t)blk_id * (64 * M)) + lane;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            vbuf[j] = vp[j * 64];
+    };
     int blk = blk0 + wave;
     *(lds_u32 *)(lbase + GCTR_OFF) = (uint32_t)(blk0 + NW);
     const uint32_t ctr_addr = (uint32_t)(uintptr_t)(lbase + GCTR_OFF);
     const uint32_t grab_inc = lane == 0 ? 1u : 0u;
-    load_block<M>(buf[0], k_head, v_head, blk < blk1 ? blk : 0, lane);
+    load_k(kbuf, blk < blk1 ? blk : 0);
 
 #pragma unroll
     for (int v = 0; v < VPT / 2; ++v) {
         *(lds_u32x4 *)(lbase + KIMG_OFF + (tid + v * (NW * 64)) * 16) = raw[v];
         *(lds_u32x4 *)(lbase + VIMG_OFF + (tid + v * (NW * 64)) * 16) = raw[VPT / 2 + v];
     }
-    if (tid < 64)
-        *(lds_u32x4 *)(lbase + Q_OFF + tid * 16) = qraw;
-    __syncthreads();
-
-    // this lane's own output dims (2 lane, 2 lane + 1) of every head's query, as scaled fp32, for the recent rows
-    float qf[GMAX][2];
-#pragma unroll
-    for (int g = 0; g < GMAX; ++g) {
-        const uint32_t w = *(lds_u32 *)(lbase + Q_OFF + g * 256 + lane * 4);
-        const __half2 h = *(const __half2 *)&w;
-        qf[g][0] = __low2float(h) * a.scale_log2e;
-        qf[g][1] = __high2float(h) * a.scale_log2e;
+    if (tid < 64) {  // padded rows are 8-byte, not 16-byte, aligned: two 8-byte stores
+        const u32x2 qlo = {qraw.x, qraw.y}, qhi = {qraw.z, qraw.w};
+        *(lds_u32x2 *)(lbase + Q_OFF + (tid >> 4) * Q_ROW + (tid & 15) * 16) = qlo;
+        *(lds_u32x2 *)(lbase + Q_OFF + (tid >> 4) * Q_ROW + (tid & 15) * 16 + 8) = qhi;
     }
+    __syncthreads();
 
     const int quad = lane >> 2;  // the 4x4x4 block of this lane
     const int row = lane & 3;    // its row: query head as an A operand, token / dim as a B operand
@@ -152,7 +168,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     }
     const uint32_t vcol = (uint32_t)(lane * 4) | ((VIMG_OFF >> 16) << 8);
     // A operand of the score pass at step u: q[row][4 sigma .. 4 sigma + 3], sigma = (u + 2 quad) % 32
-    const uint32_t qa_base = (uint32_t)(Q_OFF + row * 256);
+    const uint32_t qa_base = (uint32_t)(Q_OFF + row * Q_ROW);
 
     float m_run[GMAX], l_lane[GMAX];
     f32x4 accx = {0.f, 0.f, 0.f, 0.f}, accy = {0.f, 0.f, 0.f, 0.f};  // element g: head g, dims 2 lane / 2 lane + 1
@@ -161,14 +177,14 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         m_run[g] = NEG_BIG;
         l_lane[g] = 0.f;
     }
-    lds_u8 *pst = lbase + PST_OFF + wave * 1024;  // hi at [g][token] * 2, lo at 512 + the same
+    lds_u8 *pst = lbase + PST_OFF + wave * PST_WAVE;  // hi at g * P_ROW + token * 2, lo at GMAX * P_ROW + the same
 
-    auto process = [&](const code_regs<M> &cur, const int blk_id) {
+    auto process = [&](const int blk_id, const int next_id) {
         // ---------------- score pass: sc[g] = q_g . K^_token for this lane's token
         f32x4 sc0 = {0.f, 0.f, 0.f, 0.f}, sc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = 0; u < 32; ++u) {
-            const uint32_t w = comp(cur.k[u >> 3], (u >> 1) & 3);
+            const uint32_t w = comp(kbuf[u >> 3], (u >> 1) & 3);
             const int e = 2 * (u & 1);
             const uint32_t a0 = __builtin_amdgcn_perm(w, idx[u >> 1], 0x0c0c0000u | ((4 + e) << 8) | e);
             const uint32_t a1 = __builtin_amdgcn_perm(w, idx[u >> 1], 0x0c0c0000u | ((5 + e) << 8) | (e + 1));
@@ -183,6 +199,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
             else
                 sc0 = __builtin_amdgcn_mfma_f32_4x4x4f16(A, B, sc0, 0, 0, 0);
         }
+        load_k(kbuf, next_id);  // the score pass is done with the K codes of this block
         const bool valid = blk_id * 64 + lane < N;
 
         // ---------------- running softmax, one per head; weights staged as fp16 hi + lo
@@ -198,8 +215,8 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
             m_run[g] = m_new;
             const _Float16 hi = (_Float16)p;
             const _Float16 lo = (_Float16)(p - (float)hi);
-            *(lds_u16 *)(pst + g * 128 + lane * 2) = __builtin_bit_cast(uint16_t, hi);
-            *(lds_u16 *)(pst + 512 + g * 128 + lane * 2) = __builtin_bit_cast(uint16_t, lo);
+            *(lds_u16 *)(pst + g * P_ROW + lane * 2) = __builtin_bit_cast(uint16_t, hi);
+            *(lds_u16 *)(pst + (GMAX + g) * P_ROW + lane * 2) = __builtin_bit_cast(uint16_t, lo);
         }
         __builtin_amdgcn_wave_barrier();
 
@@ -208,7 +225,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         for (int n = 0; n < 4; ++n) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const uint32_t w = comp(cur.v[n], r);
+                const uint32_t w = comp(vbuf[n], r);
                 const int tok0 = 16 * n + 4 * r;
                 uint32_t c[4];
 #pragma unroll
@@ -222,8 +239,8 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
                 const f16x4 By = as_f16x4(__builtin_amdgcn_perm(c[1], c[0], 0x07060302u),
                                           __builtin_amdgcn_perm(c[3], c[2], 0x07060302u));
                 // A operands: weights of head `row` for the 4 tokens
-                const f16x4 Ahi = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(pst + row * 128 + tok0 * 2));
-                const f16x4 Alo = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(pst + 512 + row * 128 + tok0 * 2));
+                const f16x4 Ahi = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(pst + row * P_ROW + tok0 * 2));
+                const f16x4 Alo = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(pst + (GMAX + row) * P_ROW + tok0 * 2));
                 accx = __builtin_amdgcn_mfma_f32_4x4x4f16(Ahi, Bx, accx, 0, 0, 0);
                 accy = __builtin_amdgcn_mfma_f32_4x4x4f16(Ahi, By, accy, 0, 0, 0);
                 accx = __builtin_amdgcn_mfma_f32_4x4x4f16(Alo, Bx, accx, 0, 0, 0);
@@ -233,20 +250,11 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         __builtin_amdgcn_wave_barrier();
     };
 
-    if (blk < blk1) {
-        bool more = true;
-        while (more) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                if (more) {
-                    const int nb = lds_grab(ctr_addr, grab_inc);
-                    load_block<M>(buf[j ^ 1], k_head, v_head, nb < blk1 ? nb : blk, lane);
-                    process(buf[j], blk);
-                    blk = nb;
-                    more = nb < blk1;
-                }
-            }
-        }
+    while (blk < blk1) {
+        const int nb = lds_grab(ctr_addr, grab_inc);
+        load_v(blk);
+        process(blk, nb < blk1 ? nb : blk);
+        blk = nb;
     }
 
     // ---------------- recent full-precision rows of this split, all heads of the group
@@ -259,7 +267,10 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
             const float k0 = __low2float(kh), k1 = __high2float(kh), v0 = __low2float(vh), v1 = __high2float(vh);
 #pragma unroll
             for (int g = 0; g < GMAX; ++g) {
-                const float s = wave_sum(fmaf(qf[g][0], k0, qf[g][1] * k1));
+                // this lane's dims (2 lane, 2 lane + 1) of head g's query
+                const uint32_t qw = *(lds_u32 *)(lbase + Q_OFF + g * Q_ROW + lane * 4);
+                const __half2 qh = *(const __half2 *)&qw;
+                const float s = wave_sum(fmaf(__low2float(qh), k0, __high2float(qh) * k1)) * a.scale_log2e;
                 const float m_new = fmaxf(m_run[g], s);
                 const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_new);
                 const float p = __builtin_amdgcn_exp2f(s - m_new);
@@ -271,7 +282,9 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         }
     }
 
-    // ---------------- merge the wavefronts of this workgroup
+    // ---------------- merge the wavefronts of this workgroup (their partials overwrite the K image:
+    // wait until nobody scans any more)
+    __syncthreads();
     {
         lds_f32 *part = (lds_f32 *)(lbase + GPART_OFF) + wave * GMAX * PQ_PART_STRIDE;
 #pragma unroll
@@ -286,12 +299,16 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         }
     }
     __syncthreads();
-    if (wave != 0)
-        return;
 
-    // wavefront 0: merge per head, publish the split partials, one ticket per (sequence, KV head)
-    const lds_f32 *parts = (const lds_f32 *)(lbase + GPART_OFF);
-    for (int g = 0; g < G; ++g) {
+    // Wavefront g (< G) finishes head g: merges the workgroup's wavefronts, publishes the split
+    // partial, and — in the workgroup that takes the last ticket of this (sequence, KV head) —
+    // merges all splits and writes the output row.  One release fence and one ticket per
+    // workgroup (wavefront 0), between two barriers.
+    typedef __attribute__((address_space(3))) int lds_i32;
+    lds_i32 *last_flag = (lds_i32 *)(lbase + GCTR_OFF + 4);
+    const int g = wave;
+    if (g < G) {
+        const lds_f32 *parts = (const lds_f32 *)(lbase + GPART_OFF);
         float mx = NEG_BIG;
 #pragma unroll
         for (int w = 0; w < NW; ++w)
@@ -317,30 +334,35 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     }
     if (S == 1)
         return;
-
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // the partials above are visible device-wide before the ticket
-    unsigned int ticket = 0;
-    if (lane == 0)
-        ticket = __hip_atomic_fetch_add(a.tickets + bh0, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    ticket = __builtin_amdgcn_readfirstlane(ticket);
-    if (ticket != (unsigned int)(S - 1))
+    __syncthreads();  // all G partials of this workgroup are written (and complete: the barrier's release)
+    if (wave == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // visible device-wide before the ticket
+        unsigned int ticket = 0;
+        if (lane == 0)
+            ticket = __hip_atomic_fetch_add(a.tickets + bh0, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ticket = __builtin_amdgcn_readfirstlane(ticket);
+        if (lane == 0)
+            *last_flag = ticket == (unsigned int)(S - 1);
+    }
+    __syncthreads();
+    if (!*last_flag || g >= G)
         return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the other workgroups' partials
-    for (int g = 0; g < G; ++g) {
+    {
         const float *ps = a.partials + (int64_t)(bh0 + g) * S * PQ_PART_STRIDE;
         const float2 ml = lane < S ? *(const float2 *)(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
         const float mx = wave_max(ml.x);
         const float f_lane = __builtin_amdgcn_exp2f(ml.x - mx);
         const float l = wave_sum(ml.y * f_lane);
         float o0 = 0.f, o1 = 0.f;
-        for (int s0 = 0; s0 < S; s0 += 8) {
-            float2 o[8];
+        for (int s0 = 0; s0 < S; s0 += 16) {
+            float2 o[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 16; ++u)
                 o[u] = s0 + u < S ? *(const float2 *)(ps + (s0 + u) * PQ_PART_STRIDE + 4 + 2 * lane)
                                   : make_float2(0.f, 0.f);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), (s0 + u) & 63));
                 o0 = fmaf(o[u].x, f, o0);
                 o1 = fmaf(o[u].y, f, o1);
@@ -349,7 +371,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         const float inv = l > 0.f ? 1.f / l : 0.f;
         *(float2 *)(a.out + (int64_t)(bh0 + g) * PQ_HEAD_DIM + 2 * lane) = make_float2(o0 * inv, o1 * inv);
     }
-    if (lane == 0)
+    if (wave == 0 && lane == 0)
         a.tickets[bh0] = 0u;
 }
 
