@@ -127,6 +127,10 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
  *   k_codes / v_codes       written at token positions ctx_len[b] .. ctx_len[b]+n_new-1
  *   ctx_len     device [B] int32, incremented by n_new on the stream
  *
+ * The call may run on another stream concurrently with pq_attn_decode on the same context if the
+ * two are given different length arrays and the decode does not attend over the positions being
+ * written (asynchronous quantization, Section III-B); the caller publishes the new lengths afterwards.
+ *
  * 0 < n_new <= max_context, else PQ_ERR_CAPACITY.  Tokens that would land beyond
  * max_context for some sequence are dropped, that sequence's length saturates, and
  * bit 0 of the device error word is set (see pq_attn_device_error). */

@@ -1,0 +1,126 @@
+#!/usr/bin/env python3
+"""Measurements beyond the headline benchmark (one MI355X):
+
+    python -m paper_2504_03661_amd.bench_extra prefill   # bulk encode of a 32K-token prompt, all heads, K and V
+    python -m paper_2504_03661_amd.bench_extra async     # encode on a second stream while decode runs
+
+prefill: the nearest-centroid encode at prompt shape (Section III-A, "Online Prefill with KV Cache
+Quantization"): vectors per second against the fp64 vector-ALU roofline (2 ds + 3 operations per
+(sub-vector, centroid); 256 CUs x 64 lanes x 2.4 GHz = 39.3 T operations/s).
+
+async: Section III-B's asynchronous quantization with what this pool allows — two streams of DEFAULT
+priority.  Decode reads the visible lengths, encode appends behind them using a second length array, so the
+two kernels touch disjoint data; the caller publishes the new lengths between steps.
+Each mode prints one JSON line.
+"""
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+ALU_LANE_OPS_PER_S = 256 * 64 * 2.4e9
+
+
+def _span_ms(fn, steps, warmup=3):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def prefill():
+    import numpy as np
+    import torch
+    from paper_2504_03661_amd.harness import PQSession
+    from synth import workloads as W
+
+    n_new = 32768
+    w = W.Workload("prefill_encode_32k", 1, 32, 32, 128, 64, n_new, "f16", n_new=n_new, seed=W.BASE_SEED + 11)
+    data = W.generate(w)
+    with PQSession(data, w.n_q_heads, w.dtype) as s:
+        nk = torch.from_numpy(data["new_k"]).cuda()
+        nv = torch.from_numpy(data["new_v"]).cuda()
+        app = s.prepared_append(nk, nv)
+
+        def step():
+            s.ctx_len.zero_()
+            app()
+        ms = _span_ms(step, 5)
+    vectors = 2 * w.batch * w.n_kv_heads * n_new
+    ops = vectors * w.n_subspaces * 256 * (2 * w.sub_dim + 3)
+    achieved = ops / (ms * 1e-3)
+    print(json.dumps({"mode": "prefill_encode", "workload": w.name, "ms": round(ms, 3),
+                      "vectors_per_s": round(vectors / (ms * 1e-3)), "tokens_per_s": round(n_new / (ms * 1e-3)),
+                      "roofline": {"bound": "alu", "unit": "lane-op/s", "achieved": achieved,
+                                   "peak": ALU_LANE_OPS_PER_S, "frac": round(achieved / ALU_LANE_OPS_PER_S, 4),
+                                   "ops_per_subvector_centroid": 2 * w.sub_dim + 3}}))
+
+
+def async_encode():
+    import numpy as np
+    import torch
+    from paper_2504_03661_amd import binding as B
+    from paper_2504_03661_amd.harness import PQSession
+    from synth import workloads as W
+
+    w = W.config(4)
+    data = W.generate(w)
+    scale = W.attention_scale(w)
+    with PQSession(data, w.n_q_heads, w.dtype) as s:
+        nk = torch.from_numpy(data["new_k"]).cuda()
+        nv = torch.from_numpy(data["new_v"]).cuda()
+        visible = s.ctx_len                                  # decode reads these lengths
+        pending = visible.clone()                            # encode appends behind them
+        side = torch.cuda.Stream()                           # default priority
+        main = torch.cuda.current_stream()
+
+        def decode_only():
+            B.pq_attn_decode(s.ctx, s.q, s.k_codes[0], s.v_codes[0], visible, None, None, None, None, None, scale,
+                             s.out, main)
+
+        def encode_only():
+            pending.copy_(visible)
+            B.pq_encode_append(s.ctx, nk, nv, w.n_new, None, None, s.k_codes[0], s.v_codes[0], pending, main)
+
+        def overlapped():
+            # decode is submitted first: its workgroups take most of every CU's LDS, the encode
+            # workgroups (one wavefront, a few KiB of LDS) then fit beside them
+            side.wait_stream(main)
+            decode_only()
+            with torch.cuda.stream(side):
+                pending.copy_(visible)
+                B.pq_encode_append(s.ctx, nk, nv, w.n_new, None, None, s.k_codes[0], s.v_codes[0], pending, side)
+            main.wait_stream(side)
+
+        steps = 50
+        t_dec = _span_ms(decode_only, steps)
+        t_enc = _span_ms(encode_only, steps)
+        t_both = _span_ms(overlapped, steps)
+    print(json.dumps({"mode": "async_encode", "workload": w.name, "decode_ms": round(t_dec, 4),
+                      "encode_ms": round(t_enc, 4), "serial_ms": round(t_dec + t_enc, 4),
+                      "overlapped_ms": round(t_both, 4),
+                      "hidden_fraction_of_encode": round((t_dec + t_enc - t_both) / t_enc, 3),
+                      "streams": "two streams of default priority"}))
+
+
+if __name__ == "__main__":
+    mode = sys.argv[1] if len(sys.argv) > 1 else ""
+    if mode == "prefill":
+        prefill()
+    elif mode == "async":
+        async_encode()
+    else:
+        print(__doc__)
+        sys.exit(2)

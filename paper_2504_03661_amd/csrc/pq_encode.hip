@@ -22,7 +22,10 @@
 
 namespace {
 
-constexpr int ENC_WAVES = 4;
+// One wavefront per workgroup: its LDS footprint (the widened codebook of one subspace, 4-8 KiB)
+// fits beside a resident decode workgroup, so an encode issued on another stream can share the
+// compute units with a running decode (asynchronous quantization, Section III-B).
+constexpr int ENC_WAVES = 1;
 
 template <typename T> __device__ inline double widen(const void *p, int64_t i);
 template <> __device__ inline double widen<__half>(const void *p, int64_t i)

@@ -204,6 +204,44 @@ def test_encode_round_trip_of_exact_centroids_and_ragged_lengths():
     np.testing.assert_array_equal(got[0, :, :13], data["k_codes"][0, :, :13])   # older tokens untouched
 
 
+def test_bulk_encode_at_prefill_shape_is_bit_exact():
+    """The prompt-sized encode (many 64-token chunks per head), both layouts, both dtypes of width."""
+    for M, Hq in ((64, 4), (32, 4), (64, 8)):
+        w = W.Workload("pre", 1, Hq, 2, 128, M, 3000, "f16", n_new=3000, seed=300 + M + Hq)
+        data = W.generate(w)
+        with PQSession(data, Hq, "f16") as s:
+            s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())
+            torch.cuda.synchronize()
+            assert s.ctx_len.cpu().tolist() == [3000]
+            np.testing.assert_array_equal(s.unpack(PQ_CODES_K, 3000), O.encode(data["new_k"], data["k_codebook"]))
+            np.testing.assert_array_equal(s.unpack(PQ_CODES_V, 3000), O.encode(data["new_v"], data["v_codebook"]))
+
+
+def test_encode_on_a_second_stream_while_decode_runs():
+    """Asynchronous quantization (Section III-B) with two default-priority streams: decode attends over the
+    visible lengths while encode appends behind them through a second length array."""
+    w = W.Workload("async", 2, 4, 4, 128, 64, 6000, "f16", recent_cap=64, recent_fixed=64, n_new=64, seed=55)
+    data = W.generate(w, ctx_cap=6100)
+    n_old = w.context - w.n_new
+    with PQSession(data, 4, "f16", max_context=6100) as s:
+        nk, nv = torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda()
+        pending = s.ctx_len.clone()
+        side = torch.cuda.Stream()
+        main = torch.cuda.current_stream()
+        for _ in range(3):
+            pending.copy_(s.ctx_len)
+            side.wait_stream(main)
+            binding.pq_encode_append(s.ctx, nk, nv, w.n_new, None, None, s.k_codes[0], s.v_codes[0], pending, side)
+            out = s.decode(W.attention_scale(w))
+            main.wait_stream(side)
+            torch.cuda.synchronize()
+            check(out.cpu().numpy(), oracle_out(w, data), "decode during encode")
+            assert pending.cpu().tolist() == [w.context] * 2 and s.ctx_len.cpu().tolist() == [n_old] * 2
+        got = s.unpack(PQ_CODES_K, w.context)
+    np.testing.assert_array_equal(got[:, :, n_old:], O.encode(data["new_k"], data["k_codebook"]))
+    np.testing.assert_array_equal(got[:, :, :n_old], data["k_codes"][:, :, :n_old])
+
+
 def test_append_overflow_saturates_and_flags():
     w = W.Workload("ov", 2, 2, 2, 128, 64, 100, "f16", n_new=30, seed=4, ctx_lens=(60, 90))
     data = W.generate(w, ctx_cap=100)
