@@ -140,7 +140,6 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     int blk = blk0 + wave;
     *(lds_u32 *)(lbase + CTR_OFF) = (uint32_t)(blk0 + NW);  // same value from every thread: no branch
     const uint32_t ctr_addr = (uint32_t)(uintptr_t)(lbase + CTR_OFF);
-    const uint32_t grab_inc = lane == 0 ? 1u : 0u;
     load_block<M>(buf[0], k_head, v_head, blk < blk1 ? blk : 0, lane);
 
     // ---- this lane's query sub-vector, pre-multiplied by scale * log2(e)
@@ -279,7 +278,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 if (more) {
-                    const int nb = lds_grab(ctr_addr, grab_inc);
+                    const int nb = lds_grab(ctr_addr);
                     load_block<M>(buf[j ^ 1], k_head, v_head, nb < blk1 ? nb : blk, lane);
                     process(buf[j], blk);
                     blk = nb;

@@ -139,7 +139,6 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     int blk = blk0 + wave;
     *(lds_u32 *)(lbase + GCTR_OFF) = (uint32_t)(blk0 + NW);
     const uint32_t ctr_addr = (uint32_t)(uintptr_t)(lbase + GCTR_OFF);
-    const uint32_t grab_inc = lane == 0 ? 1u : 0u;
     load_k(kbuf, blk < blk1 ? blk : 0);
 
 #pragma unroll
@@ -251,7 +250,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     };
 
     while (blk < blk1) {
-        const int nb = lds_grab(ctr_addr, grab_inc);
+        const int nb = lds_grab(ctr_addr);
         load_v(blk);
         process(blk, nb < blk1 ? nb : blk);
         blk = nb;

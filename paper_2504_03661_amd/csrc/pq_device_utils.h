@@ -66,14 +66,23 @@ __device__ inline uint32_t comp(const uint4 &v, int r)
     return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w;
 }
 
-// Takes the next unowned block of the workgroup's split from a counter in LDS.  Every lane
-// executes the atomic, lane 0 adds 1 and the others add 0, so no branch appears in the scan
-// loop (the compiler's wait-count analysis turns conservative at control-flow joins); inline
-// assembly keeps the compiler from rewriting it into a branchy single-lane form.
-__device__ inline int lds_grab(uint32_t lds_addr, uint32_t inc)
+// Takes the next unowned block of the workgroup's split from a counter in LDS.  One lane adds
+// 1; the execution mask is narrowed to that lane inside the assembly block, so no branch
+// appears in the scan loop (the compiler's wait-count analysis turns conservative at
+// control-flow joins) and the atomic unit serves one lane, not sixty-four on one address.
+__device__ inline int lds_grab(uint32_t lds_addr)
 {
     uint32_t r;
-    asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(lds_addr), "v"(inc) : "memory");
+    uint64_t saved_exec;
+    const uint32_t one = 1;
+    asm volatile("s_mov_b64 %1, exec\n\t"
+                 "s_mov_b64 exec, 1\n\t"
+                 "ds_add_rtn_u32 %0, %2, %3\n\t"
+                 "s_mov_b64 exec, %1\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(r), "=&s"(saved_exec)
+                 : "v"(lds_addr), "v"(one)
+                 : "memory");
     return __builtin_amdgcn_readfirstlane((int)r);
 }
 
