@@ -126,13 +126,31 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const uint8_t *k_head = a.k_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
     const uint8_t *v_head = a.v_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
 
-    // Two code buffers per wavefront: one block is processed while the next one is in flight.
-    // (Deeper queues were measured to be slower: HBM saturates with a few KiB in flight per
-    // wavefront, more only lengthens the queue and with it the start-up and the drain.)
-    // Every code load is unconditional (a wavefront that has run out of blocks re-reads the
-    // block it holds, an L2 hit), so the compiler knows exactly how many loads are in flight
-    // at each use and a wait for one buffer never also drains the loads of the other.
-    code_regs<M> buf[2];
+    // Code buffers of a wavefront.  Every code load is unconditional (a wavefront that has run
+    // out of blocks re-reads the block it holds, an L2 hit), so the compiler knows exactly how
+    // many loads are in flight at each use and a wait for one buffer never drains another's loads.
+    //  M = 64 (8 KiB per block): one K and one V buffer, each refilled as soon as its pass is over
+    //          — the V codes of a block are requested when its score pass starts, the K codes of
+    //          the next block when that score pass ends.
+    //  M = 32 (4 KiB per block): two K+V buffers, the whole next block loads during this one;
+    //          the staggered scheme keeps too few bytes in flight for the smaller blocks
+    //          (measured 417 us against 394 us at 16 x 32 heads x 64K).
+    // Deeper queues than these were measured to be slower: HBM saturates with a few KiB in
+    // flight per wavefront, more only lengthens the queue and with it the start-up and the drain.
+    constexpr int NBUF = M == 64 ? 1 : 2;
+    uint4 kbuf[NBUF][M / 16], vbuf[NBUF][M / 16];
+    auto load_k = [&](uint4 (&dst)[M / 16], int blk_id) {
+        const uint4 *kp = (const uint4 *)(k_head + (int64_t)blk_id * (64 * M)) + lane;
+#pragma unroll
+        for (int j = 0; j < M / 16; ++j)
+            dst[j] = kp[j * 64];
+    };
+    auto load_v = [&](uint4 (&dst)[M / 16], int blk_id) {
+        const uint4 *vp = (const uint4 *)(v_head + (int64_t)blk_id * (64 * M)) + lane;
+#pragma unroll
+        for (int j = 0; j < M / 16; ++j)
+            dst[j] = vp[j * 64];
+    };
     // Wavefront w starts with block blk0 + w; every later block of the split goes to whichever
     // wavefront asks next, so wavefronts that the memory system or the SIMD arbiter serve
     // faster scan more and all of them reach the merge together.  (Which wavefront sums which
@@ -140,7 +158,9 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     int blk = blk0 + wave;
     *(lds_u32 *)(lbase + CTR_OFF) = (uint32_t)(blk0 + NW);  // same value from every thread: no branch
     const uint32_t ctr_addr = (uint32_t)(uintptr_t)(lbase + CTR_OFF);
-    load_block<M>(buf[0], k_head, v_head, blk < blk1 ? blk : 0, lane);
+    load_k(kbuf[0], blk < blk1 ? blk : 0);
+    if (NBUF == 2)
+        load_v(vbuf[0], blk < blk1 ? blk : 0);
 
     // ---- this lane's query sub-vector, pre-multiplied by scale * log2(e)
     const int sub = lane & (M - 1);
@@ -200,12 +220,12 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const float *vcb_f32 = (const float *)a.vcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM;
     lds_u8 *pline = lbase + PBUF_OFF + wave * 256;
 
-    auto process = [&](const code_regs<M> &cur, const int blk) {
+    auto process = [&](const uint4 (&kb)[M / 16], const uint4 (&vb)[M / 16], const int blk, auto &&after_score) {
         // ---------------- score pass
         float s4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int r = 0; r < M / 4; ++r) {
-            const uint32_t w = comp(cur.k[r >> 2], r & 3);
+            const uint32_t w = comp(kb[r >> 2], r & 3);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const uint32_t sel = 0x0c0c0000u | ((4 + k) << 8) | k;
@@ -213,6 +233,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
                 s4[k] += *(lds_f32 *)(lbase + addr);
             }
         }
+        after_score();  // the score pass is done with this block's K codes
         const bool valid = blk * 64 + lane < N;
         const float s = valid ? (s4[0] + s4[1]) + (s4[2] + s4[3]) : NEG_BIG;
 
@@ -233,7 +254,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         for (int n = 0; n < M / 16; ++n) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const uint32_t w = comp(cur.v[n], r);
+                const uint32_t w = comp(vb[n], r);
                 const int tok0 = (M == 64) ? (16 * n + 4 * r) : (32 * n + 16 * half_id + 4 * r);
                 const f32x4 p4 = *(lds_f32x4 *)(pline + tok0 * 4);
                 const float pk[4] = {p4.x, p4.y, p4.z, p4.w};
@@ -271,16 +292,25 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         __builtin_amdgcn_wave_barrier();
     };
 
-    // two blocks per trip so that the buffers swap roles without register copies
-    if (blk < blk1) {
-        bool more = true;
+    if constexpr (NBUF == 1) {
+        while (blk < blk1) {
+            const int nb = lds_grab(ctr_addr);
+            const int next_blk = nb < blk1 ? nb : blk;
+            load_v(vbuf[0], blk);
+            process(kbuf[0], vbuf[0], blk, [&]() { load_k(kbuf[0], next_blk); });
+            blk = nb;
+        }
+    } else {
+        // two blocks per trip so that the buffers swap roles without register copies
+        bool more = blk < blk1;
         while (more) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 if (more) {
                     const int nb = lds_grab(ctr_addr);
-                    load_block<M>(buf[j ^ 1], k_head, v_head, nb < blk1 ? nb : blk, lane);
-                    process(buf[j], blk);
+                    load_k(kbuf[j ^ 1], nb < blk1 ? nb : blk);
+                    load_v(vbuf[j ^ 1], nb < blk1 ? nb : blk);
+                    process(kbuf[j], vbuf[j], blk, []() {});
                     blk = nb;
                     more = nb < blk1;
                 }
