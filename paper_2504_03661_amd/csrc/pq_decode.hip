@@ -367,10 +367,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     __syncthreads();
 
     // From here on only wavefront 0 works: it merges the workgroup's wavefronts (lane l owns
-    // output dims 2l, 2l+1), publishes the split partial and takes a ticket.  Keeping the
-    // device-scope release/acquire fences in ONE wavefront per workgroup matters: each fence
-    // is an L2 write-back / invalidate, and sixteen of them per workgroup cost more than
-    // the whole scan.
+    // output dims 2l, 2l+1), publishes the split partial and takes a ticket.
     if (wave != 0)
         return;
     float *gpart = a.partials + ((int64_t)bh * S + split) * PQ_PART_STRIDE;
@@ -393,38 +390,48 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         *(float2 *)(orow + 2 * lane) = make_float2(o0 * inv, o1 * inv);
         return;
     }
-    *(float2 *)(gpart + 4 + 2 * lane) = make_float2(o0, o1);
+    // The partial is published with device-scope stores (they are performed at the memory all
+    // XCDs share, not left dirty in this XCD's L2), so the only thing the ticket has to wait for
+    // is their completion; a release fence would add a whole-L2 write-back (about 1.8 us).
+    publish(gpart + 4 + 2 * lane, o0, o1);
     if (lane == 0)
-        *(float2 *)gpart = make_float2(mx, l);
+        publish(gpart, mx, l);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---------------- the workgroup that takes the last ticket of this (b, hq) merges the
     // splits (flash-decoding style) and leaves the ticket counter at zero for the next call
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // the partial above is visible device-wide before the ticket
     unsigned int ticket = 0;
     if (lane == 0)
         ticket = __hip_atomic_fetch_add(a.tickets + bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if (ticket != (unsigned int)(S - 1))
         return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the other workgroups' partials
+    // the other splits' partials: device-scope loads, issued after the ticket has returned
     const float *ps = a.partials + (int64_t)bh * S * PQ_PART_STRIDE;
-    // lane s holds (maximum, weight sum) of split s; all loads of a round are issued together
-    const float2 ml = lane < S ? *(const float2 *)(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
+    // Lane s holds (maximum, weight sum) of split s.  The first eight splits' output loads are issued
+    // together with that load, so the merge costs one memory round trip for up to eight splits.
+    float2 o[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        o[u] = u < S ? fetch(ps + u * PQ_PART_STRIDE + 4 + 2 * lane) : make_float2(0.f, 0.f);
+    const float2 ml = lane < S ? fetch(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
     mx = wave_max(ml.x);
     const float f_lane = __builtin_amdgcn_exp2f(ml.x - mx);
     l = wave_sum(ml.y * f_lane);
     o0 = o1 = 0.f;
-    for (int s0 = 0; s0 < S; s0 += 8) {
-        float2 o[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-            o[u] = s0 + u < S ? *(const float2 *)(ps + (s0 + u) * PQ_PART_STRIDE + 4 + 2 * lane) : make_float2(0.f, 0.f);
+    for (int s0 = 0;;) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), (s0 + u) & 63));
             o0 = fmaf(o[u].x, f, o0);
             o1 = fmaf(o[u].y, f, o1);
         }
+        s0 += 8;
+        if (s0 >= S)
+            break;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            o[u] = s0 + u < S ? fetch(ps + (s0 + u) * PQ_PART_STRIDE + 4 + 2 * lane) : make_float2(0.f, 0.f);
     }
     const float inv = l > 0.f ? 1.f / l : 0.f;
     *(float2 *)(orow + 2 * lane) = make_float2(o0 * inv, o1 * inv);

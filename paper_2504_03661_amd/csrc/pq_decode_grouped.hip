@@ -301,8 +301,8 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
 
     // Wavefront g (< G) finishes head g: merges the workgroup's wavefronts, publishes the split
     // partial, and — in the workgroup that takes the last ticket of this (sequence, KV head) —
-    // merges all splits and writes the output row.  One release fence and one ticket per
-    // workgroup (wavefront 0), between two barriers.
+    // merges all splits and writes the output row.  One ticket per workgroup (wavefront 0),
+    // between two barriers.
     typedef __attribute__((address_space(3))) int lds_i32;
     lds_i32 *last_flag = (lds_i32 *)(lbase + GCTR_OFF + 4);
     const int g = wave;
@@ -326,16 +326,17 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
             *(float2 *)(a.out + (int64_t)(bh0 + g) * PQ_HEAD_DIM + 2 * lane) = make_float2(o0 * inv, o1 * inv);
         } else {
             float *gpart = a.partials + ((int64_t)(bh0 + g) * S + split) * PQ_PART_STRIDE;
-            *(float2 *)(gpart + 4 + 2 * lane) = make_float2(o0, o1);
+            // device-scope stores, complete (performed where every XCD sees them) before the barrier
+            publish(gpart + 4 + 2 * lane, o0, o1);
             if (lane == 0)
-                *(float2 *)gpart = make_float2(mx, l);
+                publish(gpart, mx, l);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
     }
     if (S == 1)
         return;
-    __syncthreads();  // all G partials of this workgroup are written (and complete: the barrier's release)
+    __syncthreads();  // all G partials of this workgroup are published
     if (wave == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // visible device-wide before the ticket
         unsigned int ticket = 0;
         if (lane == 0)
             ticket = __hip_atomic_fetch_add(a.tickets + bh0, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -346,10 +347,10 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     __syncthreads();
     if (!*last_flag || g >= G)
         return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the other workgroups' partials
     {
+        // the other workgroups' partials, by device-scope loads issued after the ticket has returned
         const float *ps = a.partials + (int64_t)(bh0 + g) * S * PQ_PART_STRIDE;
-        const float2 ml = lane < S ? *(const float2 *)(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
+        const float2 ml = lane < S ? fetch(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
         const float mx = wave_max(ml.x);
         const float f_lane = __builtin_amdgcn_exp2f(ml.x - mx);
         const float l = wave_sum(ml.y * f_lane);
@@ -358,8 +359,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
             float2 o[16];
 #pragma unroll
             for (int u = 0; u < 16; ++u)
-                o[u] = s0 + u < S ? *(const float2 *)(ps + (s0 + u) * PQ_PART_STRIDE + 4 + 2 * lane)
-                                  : make_float2(0.f, 0.f);
+                o[u] = s0 + u < S ? fetch(ps + (s0 + u) * PQ_PART_STRIDE + 4 + 2 * lane) : make_float2(0.f, 0.f);
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
                 const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), (s0 + u) & 63));

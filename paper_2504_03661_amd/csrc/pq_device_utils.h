@@ -61,6 +61,22 @@ __device__ inline float wave_sum(float x)
     return (r0 + r1) + (r2 + r3);
 }
 
+// A pair of floats stored / loaded at device scope (8-byte aligned): the store is performed at the
+// level of the memory hierarchy all XCDs share instead of staying dirty in the local L2, the load
+// does not take a stale line from the local L2.  Workgroups on different XCDs exchange split
+// partials through these without a whole-L2 write-back or invalidate.
+__device__ inline void publish(float *p, float x, float y)
+{
+    const uint64_t bits = (uint64_t)__float_as_uint(x) | ((uint64_t)__float_as_uint(y) << 32);
+    __hip_atomic_store((uint64_t *)p, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ inline float2 fetch(const float *p)
+{
+    const uint64_t bits = __hip_atomic_load((const uint64_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((uint32_t)bits), __uint_as_float((uint32_t)(bits >> 32)));
+}
+
 __device__ inline uint32_t comp(const uint4 &v, int r)
 {
     return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w;

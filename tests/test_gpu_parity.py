@@ -152,6 +152,42 @@ def test_repeated_calls_reuse_tickets_and_scratch():
             s.out.zero_()
 
 
+@pytest.mark.parametrize("Hq,Hkv,S", [(5, 5, 9), (3, 3, 8), (8, 4, 5), (32, 32, 8)],
+                         ids=["per_head_grid45", "per_head_grid24", "grouped_grid20", "metric_shape"])
+def test_split_exchange_is_never_stale_over_many_launches(Hq, Hkv, S):
+    """The splits of a head run on workgroups of different XCDs (grids that are no multiple of 8 deal
+    consecutive workgroups round-robin) and exchange partials through memory.  Alternating between two
+    queries makes every launch overwrite the previous launch's partials with different values, so a launch
+    that merged a stale partial is off by about 1/S of the output (1e-2), far above the 1e-6 by which
+    launches differ through the order in which wavefronts pick up blocks."""
+    N = 32768 if Hq == 32 else 20000
+    w = W.Workload("xcd", 1, Hq, Hkv, 128, 64, N, "f16", recent_cap=8, recent_fixed=8, seed=77)
+    data = W.generate(w)
+    scale = W.attention_scale(w)
+    with PQSession(data, Hq, "f16", n_splits=S) as s:
+        assert s.n_splits == S
+        qa = s.q.clone()
+        qb = torch.flip(s.q, dims=[1]).contiguous() * 0.5
+        refs = []
+        for qx in (qa, qb):
+            s.q.copy_(qx)
+            refs.append(s.decode(scale).clone())
+            torch.cuda.synchronize()
+        check(refs[0].cpu().numpy(), oracle_out(w, data), "first launch")
+        assert not torch.equal(refs[0], refs[1])
+        n = 400
+        outs = torch.empty((n,) + tuple(s.out.shape), dtype=torch.float32, device=s.out.device)
+        dec = s.prepared_decode(scale)
+        for i in range(n):
+            s.q.copy_(qa if i % 2 == 0 else qb)
+            dec()
+            outs[i].copy_(s.out)
+        torch.cuda.synchronize()
+        assert (refs[0] - refs[1]).abs().max().item() > 1e-2
+        dev = (outs - torch.stack(refs).repeat(n // 2, 1, 1, 1)).abs().amax(dim=(1, 2, 3)).cpu().numpy()
+        assert dev.max() <= 2e-6, f"launch {int(dev.argmax())} is off by {dev.max():.3e} from the first launch of its query"
+
+
 # ------------------------------------------------------------------ encode / append
 
 
