@@ -73,10 +73,14 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const int hq = bh - b * a.Hq;
     const int hkv = (int)((uint32_t)hq / (uint32_t)a.G);
 
-    // the lengths are requested first: by the time the table loads below have been issued
-    // they are here, and the first code loads can follow the tables without a further wait
-    int N = a.ctx_len[b];
-    int R = (a.recent_k != nullptr && a.recent_len != nullptr) ? a.recent_len[b] : 0;
+    // The lengths are requested first and taken out of their registers only after the table loads
+    // below have been issued.  The loads go through lane_zero(), which the compiler cannot see
+    // through: a load from a wave-uniform address is otherwise made scalar on the spot, with a full
+    // wait for each of the two — two serial memory round trips before the first table load.
+    const int zero = lane_zero();
+    const bool has_recent = a.recent_k != nullptr && a.recent_len != nullptr;
+    const int n_vec = a.ctx_len[b + zero];
+    const int r_vec = (has_recent ? a.recent_len : a.ctx_len)[b + zero];
 
     // ---- prologue: LUT[c][x] for x = 0..63 (for M = 32 columns x and x+32 hold the same
     // subspace), and the value codebook image.  Order matters at this time scale:
@@ -113,6 +117,8 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         qraw[v] = *(const u32x4 *)((const char *)a.q + (((int64_t)b * a.Hq + hq) * PQ_HEAD_DIM + e0) * sizeof(T) + v * 16);
     __builtin_amdgcn_s_barrier();
 
+    int N = __builtin_amdgcn_readfirstlane(n_vec);
+    int R = has_recent ? __builtin_amdgcn_readfirstlane(r_vec) : 0;
     N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
     R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
     // 32-bit unsigned arithmetic: the capacities are limited to 2^24 tokens and S to 64, and a

@@ -87,9 +87,14 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const int b = (int)((uint32_t)bkv / (uint32_t)a.Hkv);
     const int hkv = bkv - b * a.Hkv;
     const int bh0 = b * a.Hq + hkv * G;            // first query head of the group
-
-    int N = a.ctx_len[b];
-    int R = (a.recent_k != nullptr && a.recent_len != nullptr) ? a.recent_len[b] : 0;
+    // The lengths are requested first and taken out of their registers only after the table loads
+    // below have been issued.  The loads go through lane_zero(), which the compiler cannot see
+    // through: a load from a wave-uniform address is otherwise made scalar on the spot, with a full
+    // wait for each of the two — two serial memory round trips before the first table load.
+    const int zero = lane_zero();
+    const bool has_recent = a.recent_k != nullptr && a.recent_len != nullptr;
+    const int n_vec = a.ctx_len[b + zero];
+    const int r_vec = (has_recent ? a.recent_len : a.ctx_len)[b + zero];
 
     // ---- prologue: both codebook images and the group's queries; table loads first, bare
     // barrier, then the first code block (see the per-head kernel for why)
@@ -110,6 +115,8 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         qraw = *((const u32x4 *)((const __half *)a.q + (int64_t)bh0 * PQ_HEAD_DIM) + tid);
     __builtin_amdgcn_s_barrier();
 
+    int N = __builtin_amdgcn_readfirstlane(n_vec);
+    int R = has_recent ? __builtin_amdgcn_readfirstlane(r_vec) : 0;
     N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
     R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
     const uint32_t nblk = (uint32_t)(N + 63) >> 6;

@@ -61,6 +61,16 @@ __device__ inline float wave_sum(float x)
     return (r0 + r1) + (r2 + r3);
 }
 
+// Zero in a vector register, opaque to the compiler: added to a wave-uniform index it keeps a
+// load a vector load that can stay in flight, where the compiler would otherwise issue a scalar
+// read and wait for it at once.
+__device__ inline int lane_zero()
+{
+    int z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
+
 // A pair of floats stored / loaded at device scope (8-byte aligned): the store is performed at the
 // level of the memory hierarchy all XCDs share instead of staying dirty in the local L2, the load
 // does not take a stale line from the local L2.  Workgroups on different XCDs exchange split
