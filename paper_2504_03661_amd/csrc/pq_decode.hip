@@ -143,19 +143,24 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     //          (measured 417 us against 394 us at 16 x 32 heads x 64K).
     // Deeper queues than these were measured to be slower: HBM saturates with a few KiB in
     // flight per wavefront, more only lengthens the queue and with it the start-up and the drain.
+    // The 8-wavefront instantiation serves one query head per KV head: every code byte is read by
+    // exactly one workgroup, once, and is loaded with the non-temporal hint (see load_codes).  The
+    // 16-wavefront instantiation serves grouped queries, where the G workgroups of a group share
+    // the code stream through their XCD's L2, and loads normally.
+    constexpr bool READ_ONCE = NW == 8;
     constexpr int NBUF = M == 64 ? 1 : 2;
     uint4 kbuf[NBUF][M / 16], vbuf[NBUF][M / 16];
     auto load_k = [&](uint4 (&dst)[M / 16], int blk_id) {
-        const uint4 *kp = (const uint4 *)(k_head + (int64_t)blk_id * (64 * M)) + lane;
+        const u32x4 *kp = (const u32x4 *)(k_head + (int64_t)blk_id * (64 * M)) + lane;
 #pragma unroll
         for (int j = 0; j < M / 16; ++j)
-            dst[j] = kp[j * 64];
+            dst[j] = load_codes<READ_ONCE>(kp + j * 64);
     };
     auto load_v = [&](uint4 (&dst)[M / 16], int blk_id) {
-        const uint4 *vp = (const uint4 *)(v_head + (int64_t)blk_id * (64 * M)) + lane;
+        const u32x4 *vp = (const u32x4 *)(v_head + (int64_t)blk_id * (64 * M)) + lane;
 #pragma unroll
         for (int j = 0; j < M / 16; ++j)
-            dst[j] = vp[j * 64];
+            dst[j] = load_codes<READ_ONCE>(vp + j * 64);
     };
     // Wavefront w starts with block blk0 + w; every later block of the split goes to whichever
     // wavefront asks next, so wavefronts that the memory system or the SIMD arbiter serve

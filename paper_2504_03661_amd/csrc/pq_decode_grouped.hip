@@ -132,16 +132,16 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     // that score pass ends.  With 4 wavefronts per SIMD that is enough to keep the loads ahead.
     uint4 kbuf[4], vbuf[4];
     auto load_k = [&](uint4 (&dst)[4], int blk_id) {
-        const uint4 *kp = (const uint4 *)(k_head + (int64_t)blk_id * (64 * M)) + lane;
+        const u32x4 *kp = (const u32x4 *)(k_head + (int64_t)blk_id * (64 * M)) + lane;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            dst[j] = kp[j * 64];
+            dst[j] = load_codes<true>(kp + j * 64);
     };
     auto load_v = [&](int blk_id) {
-        const uint4 *vp = (const uint4 *)(v_head + (int64_t)blk_id * (64 * M)) + lane;
+        const u32x4 *vp = (const u32x4 *)(v_head + (int64_t)blk_id * (64 * M)) + lane;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            vbuf[j] = vp[j * 64];
+            vbuf[j] = load_codes<true>(vp + j * 64);
     };
     int blk = blk0 + wave;
     *(lds_u32 *)(lbase + GCTR_OFF) = (uint32_t)(blk0 + NW);

@@ -112,21 +112,14 @@ __device__ inline int lds_grab(uint32_t lds_addr)
     return __builtin_amdgcn_readfirstlane((int)r);
 }
 
-template <int M> struct code_regs {
-    uint4 k[M / 16];
-    uint4 v[M / 16];
-};
-
-template <int M>
-__device__ inline void load_block(code_regs<M> &c, const uint8_t *k_head, const uint8_t *v_head, int blk, int lane)
+// 16 code bytes of one lane.  Codes that are read once per launch are loaded with the
+// non-temporal hint: the stream then does not displace the tables and each other's lines in L2
+// and the memory-side cache, and HBM delivers markedly more (measured on the 8 x 32 heads x 32K
+// workload: 192 us with plain loads, 164 us with the hint; a kernel that only reads shows the same).
+template <bool READ_ONCE> __device__ inline uint4 load_codes(const u32x4 *p)
 {
-    const uint4 *kp = (const uint4 *)(k_head + (int64_t)blk * (64 * M)) + lane;
-    const uint4 *vp = (const uint4 *)(v_head + (int64_t)blk * (64 * M)) + lane;
-#pragma unroll
-    for (int j = 0; j < M / 16; ++j) {
-        c.k[j] = kp[j * 64];
-        c.v[j] = vp[j * 64];
-    }
+    const u32x4 t = READ_ONCE ? __builtin_nontemporal_load(p) : *p;
+    return make_uint4(t.x, t.y, t.z, t.w);
 }
 
 }  // namespace
