@@ -42,7 +42,7 @@ constexpr int PBUF_OFF = 131072;     // float [NW][64]
 constexpr int PART_OFF = 131072 + 4096;  // float [NW][PQ_PART_STRIDE]
 constexpr int CTR_OFF = PART_OFF + 16 * PQ_PART_STRIDE * 4;  // uint32: next unowned block of the split
 constexpr int SMEM_BYTES = CTR_OFF + 16;
-template <int M, int DS, typename T, int NW>
+template <int M, int DS, typename T, int NW, bool READ_ONCE>
 __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args a)
 {
     static_assert(M * DS == PQ_HEAD_DIM, "head_dim 128 only");
@@ -143,11 +143,9 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     //          (measured 417 us against 394 us at 16 x 32 heads x 64K).
     // Deeper queues than these were measured to be slower: HBM saturates with a few KiB in
     // flight per wavefront, more only lengthens the queue and with it the start-up and the drain.
-    // The 8-wavefront instantiation serves one query head per KV head: every code byte is read by
-    // exactly one workgroup, once, and is loaded with the non-temporal hint (see load_codes).  The
-    // 16-wavefront instantiation serves grouped queries, where the G workgroups of a group share
-    // the code stream through their XCD's L2, and loads normally.
-    constexpr bool READ_ONCE = NW == 8;
+    // READ_ONCE: one query head per KV head, so every code byte is read by exactly one workgroup,
+    // once, and is loaded with the non-temporal hint (see load_codes).  With grouped queries the G
+    // workgroups of a group share the code stream through their XCD's L2 and load normally.
     constexpr int NBUF = M == 64 ? 1 : 2;
     uint4 kbuf[NBUF][M / 16], vbuf[NBUF][M / 16];
     auto load_k = [&](uint4 (&dst)[M / 16], int blk_id) {
@@ -450,11 +448,11 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         a.tickets[bh] = 0u;
 }
 
-template <int M, int DS, typename T, int NW>
+template <int M, int DS, typename T, int NW, bool READ_ONCE>
 hipError_t launch(const pq_decode_args &a, hipStream_t s)
 {
     const int grid = a.B * a.Hq * a.S;
-    hipLaunchKernelGGL((pq_decode_kernel<M, DS, T, NW>), dim3(grid), dim3(NW * 64), 0, s, a);
+    hipLaunchKernelGGL((pq_decode_kernel<M, DS, T, NW, READ_ONCE>), dim3(grid), dim3(NW * 64), 0, s, a);
     return hipGetLastError();
 }
 
@@ -463,18 +461,19 @@ hipError_t launch(const pq_decode_args &a, hipStream_t s)
 hipError_t pq_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
 {
     const bool f16 = ctx->cfg.dtype == PQ_F16;
-    // Wavefronts per workgroup.  With one query head per KV head the scan is bound by HBM and
-    // 8 wavefronts (less data in flight, shorter queues) measured fastest.  With grouped queries
-    // every code byte is scored by G workgroups out of one XCD's L2, the scan is bound by the
-    // vector ALU and LDS, and 16 wavefronts (4 per SIMD) hide their latencies better (measured
-    // 79 us against 86 us at 32 query heads over 8 KV heads, 128K context).
-    const bool wide = ctx->group > 1;
+    // Wavefronts per workgroup.  With one query head per KV head the scan is bound by HBM; at
+    // M = 64 (8 KiB per block) 8 wavefronts — less data in flight, shorter queues — measured
+    // fastest, at M = 32 (4 KiB per block) 16 do (16 x 32 heads x 64K: 355 us against 381 us).
+    // With grouped queries every code byte is scored by G workgroups out of one XCD's L2, the scan
+    // is bound by the vector ALU and LDS, and 16 wavefronts (4 per SIMD) hide their latencies
+    // better (79 us against 86 us at 32 query heads over 8 KV heads, 128K context).
+    const bool shared = ctx->group > 1;
     if (ctx->cfg.n_subspaces == 64) {
-        if (wide)
-            return f16 ? launch<64, 2, __half, 16>(a, s) : launch<64, 2, float, 16>(a, s);
-        return f16 ? launch<64, 2, __half, 8>(a, s) : launch<64, 2, float, 8>(a, s);
+        if (shared)
+            return f16 ? launch<64, 2, __half, 16, false>(a, s) : launch<64, 2, float, 16, false>(a, s);
+        return f16 ? launch<64, 2, __half, 8, true>(a, s) : launch<64, 2, float, 8, true>(a, s);
     }
-    if (wide)
-        return f16 ? launch<32, 4, __half, 16>(a, s) : launch<32, 4, float, 16>(a, s);
-    return f16 ? launch<32, 4, __half, 8>(a, s) : launch<32, 4, float, 8>(a, s);
+    if (shared)
+        return f16 ? launch<32, 4, __half, 16, false>(a, s) : launch<32, 4, float, 16, false>(a, s);
+    return f16 ? launch<32, 4, __half, 16, true>(a, s) : launch<32, 4, float, 16, true>(a, s);
 }
