@@ -146,6 +146,12 @@ int pq_pack_codes(pq_attn_ctx *ctx, int32_t kind /* pq_code_kind */, const uint8
 int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32_t n_tokens, uint8_t *token_major,
                     void *hip_stream);
 
+/* Measurement aid, not part of the method: one kernel that only reads `bytes` bytes (a multiple of
+ * 16, 16-byte aligned, device memory) with the load instruction the decode kernels use for codes.
+ * The benchmark times it to report what HBM delivers to a pure read on the box it runs on, beside
+ * the nominal peak.  Asynchronous on the stream. */
+int pq_stream_read_probe(pq_attn_ctx *ctx, const void *src /* device */, int64_t bytes, void *hip_stream);
+
 /* Synchronises the device, returns the sticky device error word in *flags and
  * clears it.  Bit 0: an append overflowed max_context. */
 int pq_attn_device_error(pq_attn_ctx *ctx, uint32_t *flags /* host */);

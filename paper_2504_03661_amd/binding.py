@@ -87,6 +87,8 @@ def load_library():
     L.pq_pack_codes.argtypes = [vp, i32, vp, i32, vp, vp]
     L.pq_unpack_codes.restype = ctypes.c_int
     L.pq_unpack_codes.argtypes = [vp, i32, vp, i32, vp, vp]
+    L.pq_stream_read_probe.restype = ctypes.c_int
+    L.pq_stream_read_probe.argtypes = [vp, vp, ctypes.c_int64, vp]
     L.pq_attn_device_error.restype = ctypes.c_int
     L.pq_attn_device_error.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
     L.pq_status_string.restype = ctypes.c_char_p
@@ -174,6 +176,10 @@ def pq_pack_codes(ctx, kind, token_major, n_tokens, packed, stream=None) -> None
 def pq_unpack_codes(ctx, kind, packed, n_tokens, token_major, stream=None) -> None:
     _check(load_library().pq_unpack_codes(ctx, int(kind), _addr(packed), int(n_tokens), _addr(token_major),
                                           _stream(stream)), "pq_unpack_codes")
+
+
+def pq_stream_read_probe(ctx, src, n_bytes, stream=None) -> None:
+    _check(load_library().pq_stream_read_probe(ctx, _addr(src), int(n_bytes), _stream(stream)), "pq_stream_read_probe")
 
 
 def pq_attn_device_error(ctx) -> int:

@@ -151,14 +151,14 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     ok = ok && hipMalloc(&ctx->vcb_packed, cb_bytes) == hipSuccess;
     ok = ok && hipMalloc((void **)&ctx->partials, part_bytes) == hipSuccess;
     ok = ok && hipMalloc((void **)&ctx->tickets, n_bh * sizeof(unsigned int)) == hipSuccess;
-    ok = ok && hipMalloc((void **)&ctx->dev_err, sizeof(unsigned int)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&ctx->dev_err, 2 * sizeof(unsigned int)) == hipSuccess;  // [1]: probe sink
     if (!ok) {
         (void)hipGetLastError();
         free_ctx(ctx);
         return PQ_ERR_ALLOC;
     }
     ok = hipMemset(ctx->tickets, 0, n_bh * sizeof(unsigned int)) == hipSuccess;
-    ok = ok && hipMemset(ctx->dev_err, 0, sizeof(unsigned int)) == hipSuccess;
+    ok = ok && hipMemset(ctx->dev_err, 0, 2 * sizeof(unsigned int)) == hipSuccess;
     ok = ok && hipMemset(ctx->partials, 0, part_bytes) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
@@ -305,6 +305,18 @@ int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32
                     void *hip_stream)
 {
     return pack_common(ctx, kind, token_major, n_tokens, const_cast<uint8_t *>(packed), true, hip_stream);
+}
+
+int pq_stream_read_probe(pq_attn_ctx *ctx, const void *src, int64_t bytes, void *hip_stream)
+{
+    if (ctx == nullptr || src == nullptr)
+        return PQ_ERR_NULL;
+    if (bytes < 16 || (bytes & 15) != 0 || ((uintptr_t)src & 15) != 0)
+        return PQ_ERR_SHAPE;
+    device_guard guard(ctx->cfg.device);
+    if (!guard.ok)
+        return PQ_ERR_HIP;
+    return pq_launch_stream_read(src, bytes, ctx->dev_err + 1, (hipStream_t)hip_stream) == hipSuccess ? PQ_OK : PQ_ERR_HIP;
 }
 
 int pq_attn_device_error(pq_attn_ctx *ctx, uint32_t *flags)

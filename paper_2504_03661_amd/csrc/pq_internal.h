@@ -103,3 +103,4 @@ hipError_t pq_launch_encode(const pq_attn_ctx *ctx, const pq_encode_args &a, int
 hipError_t pq_launch_pack_codebook(const pq_attn_ctx *ctx, const void *src, void *dst, hipStream_t s);
 hipError_t pq_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint8_t *token_major, int n_tokens,
                                 uint8_t *packed, bool unpack, hipStream_t s);
+hipError_t pq_launch_stream_read(const void *src, int64_t bytes, uint32_t *sink, hipStream_t s);

@@ -3,6 +3,7 @@
 // [B][Hkv][n][M] (Delta_K, Delta_V of Eq. 4) and the device layouts.
 #include <hip/hip_runtime.h>
 
+#include "pq_device_utils.h"
 #include "pq_internal.h"
 
 namespace {
@@ -42,6 +43,21 @@ __global__ void pq_pack_codes_kernel(const uint8_t *token_major, uint8_t *packed
         packed[off] = token_major[x];
 }
 
+// Reads n 16-byte vectors with the code-stream load and folds them into one word per lane; the
+// store (into a scratch word nobody reads) happens for one value in 2^32 and keeps the loads alive.
+__global__ __launch_bounds__(1024) void pq_stream_read_kernel(const u32x4 *p, int64_t n, uint32_t *sink)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    uint32_t acc = 0;
+    for (; i < n; i += stride) {
+        const uint4 v = load_codes<true>(p + i);
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x9e3779b9u)
+        *sink = acc;
+}
+
 }  // namespace
 
 hipError_t pq_launch_pack_codebook(const pq_attn_ctx *ctx, const void *src, void *dst, hipStream_t s)
@@ -69,5 +85,11 @@ hipError_t pq_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint8_t 
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     hipLaunchKernelGGL(pq_pack_codes_kernel, grid, block, 0, s, token_major, packed, n_heads, n_tokens, M,
                        ctx->cap_padded * M, kind, unpack ? 1 : 0, ctx->k_skew);
+    return hipGetLastError();
+}
+
+hipError_t pq_launch_stream_read(const void *src, int64_t bytes, uint32_t *sink, hipStream_t s)
+{
+    hipLaunchKernelGGL(pq_stream_read_kernel, dim3(2048), dim3(1024), 0, s, (const u32x4 *)src, bytes / 16, sink);
     return hipGetLastError();
 }
