@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of PQ decode attention on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--copies C] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--copies C] [--no-cpu-baseline] [--warm]
 
 A step is one pass of the hot path over one batch: pq_attn_decode (table build,
 score pass, softmax, value pass, recent rows, split merge — one fused kernel) on
@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--copies", type=int, default=0, help="distinct code-tensor copies to rotate (0 = 1 GiB worth)")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--warm", action="store_true", help="also time the same-buffer (cache-warm) case")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -143,15 +144,18 @@ def main():
         torch.cuda.synchronize()
         kernel_ms = ev0.elapsed_time(ev1) / args.steps
 
-    # Same-buffer ("warm") figure: every step reads copy 0, which the 256 MB memory-side cache can hold
-    # for the 128 MiB workloads.  Reported for reference only; never used for `value`.
-    torch.cuda.synchronize()
-    ev0.record()
-    for i in range(args.steps):
-        dec[0]()
-    ev1.record()
-    torch.cuda.synchronize()
-    warm_ms = ev0.elapsed_time(ev1) / args.steps
+    # Same-buffer ("warm") figure, on request: every step reads copy 0, which the 256 MB memory-side
+    # cache can hold for the 128 MiB workloads.  For reference only; never used for `value`.  Off by
+    # default so that a kernel trace of the default run holds warm-up and timed launches only.
+    warm_ms = None
+    if args.warm:
+        torch.cuda.synchronize()
+        ev0.record()
+        for i in range(args.steps):
+            dec[0]()
+        ev1.record()
+        torch.cuda.synchronize()
+        warm_ms = ev0.elapsed_time(ev1) / args.steps
 
     # What HBM delivers to a kernel that only reads, on this machine: the library's read probe (same load
     # instruction as the code stream) over a 1 GiB buffer, five passes.
@@ -182,7 +186,7 @@ def main():
                 "kernel_ms": round(kernel_ms, 5), "event_span_ms_per_step": round(span_ms, 5),
                 "measured_stream_read_gbps": round(stream_gbps, 1),
                 "frac_of_measured_stream_read": round(achieved / stream_gbps, 4),
-                "warm_same_buffer_kernel_ms": round(warm_ms, 5),
+                "warm_same_buffer_kernel_ms": None if warm_ms is None else round(warm_ms, 5),
                 "algorithmic_bytes": bytes_alg,
                 "code_read_gbps": round(bytes_alg["codes"] / (kernel_ms * 1e-3) / 1e9, 1),
                 "code_read_frac_of_peak": round(bytes_alg["codes"] / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}

@@ -132,9 +132,10 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const uint8_t *k_head = a.k_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
     const uint8_t *v_head = a.v_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
 
-    // Code buffers of a wavefront.  Every code load is unconditional (a wavefront that has run
-    // out of blocks re-reads the block it holds, an L2 hit), so the compiler knows exactly how
-    // many loads are in flight at each use and a wait for one buffer never drains another's loads.
+    // Code buffers of a wavefront.  Every code load is unconditional, so the compiler knows exactly
+    // how many loads are in flight at each use and a wait for one buffer never drains another's
+    // loads.  A wavefront that has run out of blocks issues a dead load instead (`live` false): all
+    // lanes read the first 16 bytes of a block it has already read, one line instead of 4 KiB.
     //  M = 64 (8 KiB per block): one K and one V buffer, each refilled as soon as its pass is over
     //          — the V codes of a block are requested when its score pass starts, the K codes of
     //          the next block when that score pass ends.
@@ -148,17 +149,19 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     // workgroups of a group share the code stream through their XCD's L2 and load normally.
     constexpr int NBUF = M == 64 ? 1 : 2;
     uint4 kbuf[NBUF][M / 16], vbuf[NBUF][M / 16];
-    auto load_k = [&](uint4 (&dst)[M / 16], int blk_id) {
-        const u32x4 *kp = (const u32x4 *)(k_head + (int64_t)blk_id * (64 * M)) + lane;
+    auto load_k = [&](uint4 (&dst)[M / 16], int blk_id, bool live) {
+        const u32x4 *kp = (const u32x4 *)(k_head + (int64_t)blk_id * (64 * M)) + (live ? lane : 0);
+        const int step = live ? 64 : 0;
 #pragma unroll
         for (int j = 0; j < M / 16; ++j)
-            dst[j] = load_codes<READ_ONCE>(kp + j * 64);
+            dst[j] = load_codes<READ_ONCE>(kp + j * step);
     };
-    auto load_v = [&](uint4 (&dst)[M / 16], int blk_id) {
-        const u32x4 *vp = (const u32x4 *)(v_head + (int64_t)blk_id * (64 * M)) + lane;
+    auto load_v = [&](uint4 (&dst)[M / 16], int blk_id, bool live) {
+        const u32x4 *vp = (const u32x4 *)(v_head + (int64_t)blk_id * (64 * M)) + (live ? lane : 0);
+        const int step = live ? 64 : 0;
 #pragma unroll
         for (int j = 0; j < M / 16; ++j)
-            dst[j] = load_codes<READ_ONCE>(vp + j * 64);
+            dst[j] = load_codes<READ_ONCE>(vp + j * step);
     };
     // Wavefront w starts with block blk0 + w; every later block of the split goes to whichever
     // wavefront asks next, so wavefronts that the memory system or the SIMD arbiter serve
@@ -167,9 +170,9 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     int blk = blk0 + wave;
     *(lds_u32 *)(lbase + CTR_OFF) = (uint32_t)(blk0 + NW);  // same value from every thread: no branch
     const uint32_t ctr_addr = (uint32_t)(uintptr_t)(lbase + CTR_OFF);
-    load_k(kbuf[0], blk < blk1 ? blk : 0);
+    load_k(kbuf[0], blk < blk1 ? blk : 0, blk < blk1);
     if (NBUF == 2)
-        load_v(vbuf[0], blk < blk1 ? blk : 0);
+        load_v(vbuf[0], blk < blk1 ? blk : 0, blk < blk1);
 
     // ---- this lane's query sub-vector, pre-multiplied by scale * log2(e)
     const int sub = lane & (M - 1);
@@ -305,8 +308,8 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         while (blk < blk1) {
             const int nb = lds_grab(ctr_addr);
             const int next_blk = nb < blk1 ? nb : blk;
-            load_v(vbuf[0], blk);
-            process(kbuf[0], vbuf[0], blk, [&]() { load_k(kbuf[0], next_blk); });
+            load_v(vbuf[0], blk, true);
+            process(kbuf[0], vbuf[0], blk, [&]() { load_k(kbuf[0], next_blk, nb < blk1); });
             blk = nb;
         }
     } else {
@@ -317,8 +320,8 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
             for (int j = 0; j < 2; ++j) {
                 if (more) {
                     const int nb = lds_grab(ctr_addr);
-                    load_k(kbuf[j ^ 1], nb < blk1 ? nb : blk);
-                    load_v(vbuf[j ^ 1], nb < blk1 ? nb : blk);
+                    load_k(kbuf[j ^ 1], nb < blk1 ? nb : blk, nb < blk1);
+                    load_v(vbuf[j ^ 1], nb < blk1 ? nb : blk, nb < blk1);
                     process(kbuf[j], vbuf[j], blk, []() {});
                     blk = nb;
                     more = nb < blk1;

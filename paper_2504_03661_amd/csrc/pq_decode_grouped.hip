@@ -131,11 +131,14 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     // of a block are requested when its score pass starts, the K codes of the next block when
     // that score pass ends.  With 4 wavefronts per SIMD that is enough to keep the loads ahead.
     uint4 kbuf[4], vbuf[4];
-    auto load_k = [&](uint4 (&dst)[4], int blk_id) {
-        const u32x4 *kp = (const u32x4 *)(k_head + (int64_t)blk_id * (64 * M)) + lane;
+    // `live` false: a dead load by a wavefront that has run out of blocks (loads stay unconditional
+    // so that the wait counts stay exact); all lanes then read the same 16 bytes, not 4 KiB.
+    auto load_k = [&](uint4 (&dst)[4], int blk_id, bool live) {
+        const u32x4 *kp = (const u32x4 *)(k_head + (int64_t)blk_id * (64 * M)) + (live ? lane : 0);
+        const int step = live ? 64 : 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            dst[j] = load_codes<true>(kp + j * 64);
+            dst[j] = load_codes<true>(kp + j * step);
     };
     auto load_v = [&](int blk_id) {
         const u32x4 *vp = (const u32x4 *)(v_head + (int64_t)blk_id * (64 * M)) + lane;
@@ -146,7 +149,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     int blk = blk0 + wave;
     *(lds_u32 *)(lbase + GCTR_OFF) = (uint32_t)(blk0 + NW);
     const uint32_t ctr_addr = (uint32_t)(uintptr_t)(lbase + GCTR_OFF);
-    load_k(kbuf, blk < blk1 ? blk : 0);
+    load_k(kbuf, blk < blk1 ? blk : 0, blk < blk1);
 
 #pragma unroll
     for (int v = 0; v < VPT / 2; ++v) {
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     }
     lds_u8 *pst = lbase + PST_OFF + wave * PST_WAVE;  // hi at g * P_ROW + token * 2, lo at GMAX * P_ROW + the same
 
-    auto process = [&](const int blk_id, const int next_id) {
+    auto process = [&](const int blk_id, const int next_id, const bool next_live) {
         // ---------------- score pass: sc[g] = q_g . K^_token for this lane's token
         f32x4 sc0 = {0.f, 0.f, 0.f, 0.f}, sc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -205,7 +208,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
             else
                 sc0 = __builtin_amdgcn_mfma_f32_4x4x4f16(A, B, sc0, 0, 0, 0);
         }
-        load_k(kbuf, next_id);  // the score pass is done with the K codes of this block
+        load_k(kbuf, next_id, next_live);  // the score pass is done with the K codes of this block
         const bool valid = blk_id * 64 + lane < N;
 
         // ---------------- running softmax, one per head; weights staged as fp16 hi + lo
@@ -259,7 +262,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     while (blk < blk1) {
         const int nb = lds_grab(ctr_addr);
         load_v(blk);
-        process(blk, nb < blk1 ? nb : blk);
+        process(blk, nb < blk1 ? nb : blk, nb < blk1);
         blk = nb;
     }
 
