@@ -8,14 +8,17 @@
 // heads — a genuine small dense product — goes to the matrix cores:
 //
 //   score pass  lane = token.  The K CODEBOOK image (not a per-query table) sits in LDS; a
-//               lane gathers the two centroids of a 4-dim slice of its token (2 x ds_read_b32)
-//               and v_mfma_f32_4x4x4_16B_f16 multiplies, per quad of lanes, the 4 heads' query
+//               lane gathers the centroids of its token, 4 subspaces (8 dims) per step, and
+//               v_mfma_f32_4x4x4_16B_f16 multiplies, per quad of lanes, the 4 heads' query
 //               slice (A, 4 heads x 4 dims, from LDS) with the quad's 4 tokens (B, 4 dims x 4
 //               tokens): 32 instructions give all G scores of 64 tokens.  fp16 x fp16 products
 //               are exact in the fp32 accumulator.  The instruction needs the 4 lanes of a quad
-//               on the same dims, so the K code layout rotates by quad (PQ_K_SKEW_QUAD): the 16
-//               quads of a gather touch 16 different table columns, 4 lanes each (a 4-way LDS
-//               bank conflict, measured at 8 cycles per gather instead of 2).
+//               on the same dims, so the K code layout rotates by quad (PQ_K_SKEW_QUAD) and the
+//               16 quads of a step work on 16 different groups of 4 columns; inside a quad the
+//               lanes gather their 4 subspaces in 4 different orders and rotate the results back
+//               in registers, so that every gather touches 64 different columns (no bank
+//               conflict; gathering in the same order was a 4-way conflict, 8 cycles per gather
+//               instead of 2).
 //   softmax     per head: wave maximum, running maximum / rescale; the weights are split into
 //               an fp16 high and low part (p = hi + lo to 2^-22) and staged in LDS.
 //   value pass  lane = subspace, as in the per-head kernel: one gather per code byte from the V
@@ -175,8 +178,15 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
             v |= (uint32_t)(((4 * r + k + 4 * quad) & 63) << 2) << (8 * k);
         idx[r] = v;
     }
+    // gather r of a step: this lane's byte (r + row) % 4 -> address = code << 8 | column
+    uint32_t ksel[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint32_t kk = (uint32_t)(r + row) & 3u;
+        ksel[r] = 0x0c0c0000u | ((4u + kk) << 8) | kk;
+    }
     const uint32_t vcol = (uint32_t)(lane * 4) | ((VIMG_OFF >> 16) << 8);
-    // A operand of the score pass at step u: q[row][4 sigma .. 4 sigma + 3], sigma = (u + 2 quad) % 32
+    // A operands of the score pass at step U: q[row][4 sigma .. 4 sigma + 7], sigma = (2 U + 2 quad) % 32
     const uint32_t qa_base = (uint32_t)(Q_OFF + row * Q_ROW);
 
     float m_run[GMAX], l_lane[GMAX];
@@ -190,23 +200,31 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
 
     auto process = [&](const int blk_id, const int next_id, const bool next_live) {
         // ---------------- score pass: sc[g] = q_g . K^_token for this lane's token
+        // One step = one word of this lane's codes = the 4 subspaces 4 (U + quad) .. + 3 of its token.
+        // The four lanes of a quad need the same subspaces but must not gather them in the same
+        // order (same column, four rows = one bank four times): in gather r lane `row` takes byte
+        // (r + row) % 4, so the 64 lanes of every gather touch 64 different columns.  The four
+        // results are then rotated back inside the lane (two conditional-move stages).
         f32x4 sc0 = {0.f, 0.f, 0.f, 0.f}, sc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int u = 0; u < 32; ++u) {
-            const uint32_t w = comp(kbuf[u >> 3], (u >> 1) & 3);
-            const int e = 2 * (u & 1);
-            const uint32_t a0 = __builtin_amdgcn_perm(w, idx[u >> 1], 0x0c0c0000u | ((4 + e) << 8) | e);
-            const uint32_t a1 = __builtin_amdgcn_perm(w, idx[u >> 1], 0x0c0c0000u | ((5 + e) << 8) | (e + 1));
-            const uint32_t c0 = *(lds_u32 *)(lbase + a0);
-            const uint32_t c1 = *(lds_u32 *)(lbase + a1);
-            const uint32_t sigma = (uint32_t)(u + 2 * quad) & 31u;
-            const u32x2 qa = *(lds_u32x2 *)(lbase + qa_base + sigma * 8);
-            const f16x4 A = __builtin_bit_cast(f16x4, qa);
-            const f16x4 B = as_f16x4(c0, c1);
-            if (u & 1)
-                sc1 = __builtin_amdgcn_mfma_f32_4x4x4f16(A, B, sc1, 0, 0, 0);
-            else
-                sc0 = __builtin_amdgcn_mfma_f32_4x4x4f16(A, B, sc0, 0, 0, 0);
+        for (int U = 0; U < 16; ++U) {
+            const uint32_t w = comp(kbuf[U >> 2], U & 3);
+            uint32_t got[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                got[r] = *(lds_u32 *)(lbase + __builtin_amdgcn_perm(w, idx[U], ksel[r]));
+            uint32_t t[4], c[4];
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+                t[m] = (row & 1) ? got[(m + 3) & 3] : got[m];
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+                c[m] = (row & 2) ? t[(m + 2) & 3] : t[m];
+            const uint32_t sigma = (uint32_t)(2 * U + 2 * quad) & 31u;  // even: sigma + 1 does not wrap
+            const f16x4 A0 = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(lbase + qa_base + sigma * 8));
+            const f16x4 A1 = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(lbase + qa_base + sigma * 8 + 8));
+            sc0 = __builtin_amdgcn_mfma_f32_4x4x4f16(A0, as_f16x4(c[0], c[1]), sc0, 0, 0, 0);
+            sc1 = __builtin_amdgcn_mfma_f32_4x4x4f16(A1, as_f16x4(c[2], c[3]), sc1, 0, 0, 0);
         }
         load_k(kbuf, next_id, next_live);  // the score pass is done with the K codes of this block
         const bool valid = blk_id * 64 + lane < N;
