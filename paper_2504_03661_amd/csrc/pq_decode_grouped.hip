@@ -50,11 +50,15 @@ constexpr int KIMG_OFF = 0;                  // fp16 K codebook image [256][256 
 constexpr int VIMG_OFF = 65536;              // fp16 V codebook image [256][256 bytes]
 // Rows of the two A-operand tables are padded by 8 bytes: the 4 lanes of a quad read the same
 // offset of 4 different rows, and an unpadded row stride is a multiple of the bank count.
-constexpr int Q_ROW = 256 + 8;               // bytes per head of q
-constexpr int Q_OFF = 131072;                // fp16 q [4][128 (+4)]
+constexpr int Q_OFF = 131072;                // fp16 q, 4 rows of 256 bytes at q_row(g)
+// Row offsets of q: in a score step the lanes of quad k read 16 bytes at 16 (U + k) of the 4 rows.
+// The rows are a quarter of the bank cycle apart, so the 4 quads of a quarter-wavefront (16-byte
+// reads are served 16 lanes at a time) cover the 64 banks once.
+__host__ __device__ constexpr int q_row(int g) { return g * 320; }
 constexpr int P_ROW = 128 + 8;               // bytes per head of staged weights
 constexpr int PST_WAVE = 2 * GMAX * P_ROW;   // per wavefront: hi [4][64 (+4)] fp16, then lo likewise
-constexpr int PST_OFF = Q_OFF + 1088;
+constexpr int PST_OFF = Q_OFF + 1216;
+static_assert(q_row(3) + 256 <= 1216, "q rows fit");
 constexpr int GCTR_OFF = PST_OFF + GNW * PST_WAVE;  // uint32 block counter, uint32 "last ticket" flag
 constexpr int GSMEM_BYTES = GCTR_OFF + 16;
 // wavefront partials float [GNW][4][PQ_PART_STRIDE] reuse the K image once every wavefront has left the scan
@@ -161,8 +165,8 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     }
     if (tid < 64) {  // padded rows are 8-byte, not 16-byte, aligned: two 8-byte stores
         const u32x2 qlo = {qraw.x, qraw.y}, qhi = {qraw.z, qraw.w};
-        *(lds_u32x2 *)(lbase + Q_OFF + (tid >> 4) * Q_ROW + (tid & 15) * 16) = qlo;
-        *(lds_u32x2 *)(lbase + Q_OFF + (tid >> 4) * Q_ROW + (tid & 15) * 16 + 8) = qhi;
+        *(lds_u32x2 *)(lbase + Q_OFF + q_row(tid >> 4) + (tid & 15) * 16) = qlo;
+        *(lds_u32x2 *)(lbase + Q_OFF + q_row(tid >> 4) + (tid & 15) * 16 + 8) = qhi;
     }
     __syncthreads();
 
@@ -185,9 +189,11 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         const uint32_t kk = (uint32_t)(r + row) & 3u;
         ksel[r] = 0x0c0c0000u | ((4u + kk) << 8) | kk;
     }
+    const uint32_t rot1 = (row & 1) ? 0x07060504u : 0x03020100u;  // v_perm selector: first / second operand
+    const uint32_t rot2 = (row & 2) ? 0x07060504u : 0x03020100u;
     const uint32_t vcol = (uint32_t)(lane * 4) | ((VIMG_OFF >> 16) << 8);
     // A operands of the score pass at step U: q[row][4 sigma .. 4 sigma + 7], sigma = (2 U + 2 quad) % 32
-    const uint32_t qa_base = (uint32_t)(Q_OFF + row * Q_ROW);
+    const uint32_t qa_base = (uint32_t)(Q_OFF + q_row(row));
 
     float m_run[GMAX], l_lane[GMAX];
     f32x4 accx = {0.f, 0.f, 0.f, 0.f}, accy = {0.f, 0.f, 0.f, 0.f};  // element g: head g, dims 2 lane / 2 lane + 1
@@ -213,13 +219,16 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 got[r] = *(lds_u32 *)(lbase + __builtin_amdgcn_perm(w, idx[U], ksel[r]));
+            // rotate right by `row` registers: by 1 if bit 0 of row, then by 2 if bit 1 (v_perm as a
+            // two-way select with a per-lane selector; written as ?: the compiler turns the pair of
+            // stages into twelve compare-and-selects)
             uint32_t t[4], c[4];
 #pragma unroll
             for (int m = 0; m < 4; ++m)
-                t[m] = (row & 1) ? got[(m + 3) & 3] : got[m];
+                t[m] = __builtin_amdgcn_perm(got[(m + 3) & 3], got[m], rot1);
 #pragma unroll
             for (int m = 0; m < 4; ++m)
-                c[m] = (row & 2) ? t[(m + 2) & 3] : t[m];
+                c[m] = __builtin_amdgcn_perm(t[(m + 2) & 3], t[m], rot2);
             const uint32_t sigma = (uint32_t)(2 * U + 2 * quad) & 31u;  // even: sigma + 1 does not wrap
             const f16x4 A0 = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(lbase + qa_base + sigma * 8));
             const f16x4 A1 = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(lbase + qa_base + sigma * 8 + 8));
@@ -295,7 +304,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
 #pragma unroll
             for (int g = 0; g < GMAX; ++g) {
                 // this lane's dims (2 lane, 2 lane + 1) of head g's query
-                const uint32_t qw = *(lds_u32 *)(lbase + Q_OFF + g * Q_ROW + lane * 4);
+                const uint32_t qw = *(lds_u32 *)(lbase + Q_OFF + q_row(g) + lane * 4);
                 const __half2 qh = *(const __half2 *)&qw;
                 const float s = wave_sum(fmaf(__low2float(qh), k0, __high2float(qh) * k1)) * a.scale_log2e;
                 const float m_new = fmaxf(m_run[g], s);
