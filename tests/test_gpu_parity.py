@@ -315,6 +315,16 @@ def test_argument_errors_on_gpu():
 # ------------------------------------------------------------------ the named workloads at full size
 
 
+def test_decode_at_maximum_capacity():
+    """One head at the capacity limit of the interface, 2^24 tokens (1 GiB of K codes, 1 GiB of V codes), with
+    the largest split count; the whole output row is compared with the oracle."""
+    n = 1 << 24
+    w = W.Workload("max_capacity", 1, 1, 1, 128, 64, n, "f16", recent_cap=4, recent_fixed=4, seed=99)
+    data = W.generate(w)
+    got = gpu_decode(w, data, n_splits=64)
+    check(got, oracle_out(w, data), "2^24 tokens")
+
+
 def test_cfg1_full_size():
     w = W.config(1)
     data = W.generate(w)
