@@ -146,6 +146,24 @@ int pq_pack_codes(pq_attn_ctx *ctx, int32_t kind /* pq_code_kind */, const uint8
 int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32_t n_tokens, uint8_t *token_major,
                     void *hip_stream);
 
+/* Offline codebook training (Section II-C, training phase; Section III-A, "Offline PQ Codebook Training"):
+ * k-means per (KV head, subspace) on sampled key or value vectors, n_iters iterations of Lloyd's algorithm
+ * from the caller's initial centroids.  Assignment: nearest centroid by the rule and arithmetic of
+ * pq_encode_append (IEEE double, ties to the lowest index).  Update: a centroid with members becomes their
+ * mean — exact member sum, divided in double, rounded to float and then to fp16 — and one without keeps its
+ * value.  The result does not depend on the order in which samples are processed.
+ *
+ *   samples    device [Hkv][n_samples][d] fp16 (finite), 1 <= n_samples <= 2^20 (else PQ_ERR_CAPACITY)
+ *   codebook   device [Hkv][M][256][ds] fp16: initial centroids in, trained centroids out (in place)
+ *   workspace  device, 8-byte aligned, at least pq_kmeans_workspace_bytes(ctx) bytes (else PQ_ERR_CAPACITY);
+ *              contents need not be initialised and are garbage afterwards
+ *
+ * fp16 contexts only (PQ_ERR_UNSUPPORTED otherwise).  Asynchronous on the stream.  Training a codebook that
+ * is registered with the context in place requires pq_attn_set_codebooks afterwards. */
+int64_t pq_kmeans_workspace_bytes(const pq_attn_ctx *ctx);
+int pq_kmeans_fit(pq_attn_ctx *ctx, const void *samples /* device */, int32_t n_samples, void *codebook /* device */,
+                  int32_t n_iters, void *workspace /* device */, int64_t workspace_bytes, void *hip_stream);
+
 /* Measurement aid, not part of the method: one kernel that only reads `bytes` bytes (a multiple of
  * 16, 16-byte aligned, device memory) with the load instruction the decode kernels use for codes.
  * The benchmark times it to report what HBM delivers to a pure read on the box it runs on, beside

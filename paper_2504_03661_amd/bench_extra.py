@@ -3,6 +3,7 @@
 
     python -m paper_2504_03661_amd.bench_extra prefill   # bulk encode of a 32K-token prompt, all heads, K and V
     python -m paper_2504_03661_amd.bench_extra async     # encode on a second stream while decode runs
+    python -m paper_2504_03661_amd.bench_extra train     # offline codebook training (k-means), 64K samples x 32 heads
 
 prefill: the nearest-centroid encode at prompt shape (Section III-A, "Online Prefill with KV Cache
 Quantization"): vectors per second against the fp64 vector-ALU roofline (2 ds + 3 operations per
@@ -11,6 +12,10 @@ Quantization"): vectors per second against the fp64 vector-ALU roofline (2 ds + 
 async: Section III-B's asynchronous quantization with what this pool allows — two streams of DEFAULT
 priority.  Decode reads the visible lengths, encode appends behind them using a second length array, so the
 two kernels touch disjoint data; the caller publishes the new lengths between steps.
+
+train: Lloyd iterations of the per-subspace k-means (Section III-A, "Offline PQ Codebook Training") on 65 536
+sampled vectors per head, 32 heads, M = 64: time per iteration against the same fp64 vector-ALU roofline (the
+assignment step is the encode's scan), with the oracle timed on a small sample beside it.
 Each mode prints one JSON line.
 """
 import json
@@ -115,12 +120,59 @@ def async_encode():
                       "streams": "two streams of default priority"}))
 
 
+def train():
+    import numpy as np
+    import torch
+    from paper_2504_03661_amd import binding as B
+    from synth import workloads as W
+
+    Hkv, M, n, iters = 32, 64, 65536, 5
+    d = W.training_samples(Hkv, n, 128, M, seed=5)
+    cfg = B.PQAttnConfig(batch=1, n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=128, n_subspaces=M, n_centroids=256,
+                         max_context=64, max_recent=0, dtype=B.PQ_F16, device=0, n_splits=0)
+    ctx = B.pq_attn_create(cfg)
+    x = torch.from_numpy(d["samples"]).cuda()
+    init = torch.from_numpy(d["init"]).cuda()
+    cb = init.clone()
+    nbytes = B.pq_kmeans_workspace_bytes(ctx)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+
+    def run():
+        cb.copy_(init)
+        B.pq_kmeans_fit(ctx, x, n, cb, iters, ws, nbytes)
+
+    ms = _span_ms(run, 3, warmup=1) / iters
+    ds = 128 // M
+    ops = Hkv * M * n * 256 * (2 * ds + 3)
+    trained = cb.cpu().numpy()
+    B.pq_attn_destroy(ctx)
+
+    # the oracle on 2 heads x 4096 samples, one iteration
+    from oracle import pq_kmeans_oracle as K
+    sub = {"samples": d["samples"][:2, :4096], "init": d["init"][:2]}
+    t = time.perf_counter()
+    K.kmeans_lloyd(sub["samples"], sub["init"], 1)
+    cpu_s = time.perf_counter() - t
+    print(json.dumps({"mode": "kmeans_train", "workload": f"{Hkv} heads x {n} samples, M={M}, {iters} Lloyd iterations",
+                      "ms_per_iteration": round(ms, 3),
+                      "sub_vectors_per_s": round(Hkv * M * n / (ms * 1e-3), 1),
+                      "alu": {"bound": "alu", "achieved": round(ops / (ms * 1e-3) / 1e12, 2),
+                              "peak": round(ALU_LANE_OPS_PER_S / 1e12, 1), "unit": "T fp64 vector operations/s",
+                              "frac": round(ops / (ms * 1e-3) / ALU_LANE_OPS_PER_S, 4)},
+                      "inertia_initial": round(K.inertia(d["samples"][:1, :8192], d["init"][:1]), 1),
+                      "inertia_trained": round(K.inertia(d["samples"][:1, :8192], trained[:1]), 1),
+                      "cpu_baseline": {"kind": "oracle", "sample": "2 heads x 4096 samples, 1 iteration",
+                                       "sub_vectors_per_s": round(2 * M * 4096 / cpu_s, 1)}}))
+
+
 if __name__ == "__main__":
     mode = sys.argv[1] if len(sys.argv) > 1 else ""
     if mode == "prefill":
         prefill()
     elif mode == "async":
         async_encode()
+    elif mode == "train":
+        train()
     else:
         print(__doc__)
         sys.exit(2)

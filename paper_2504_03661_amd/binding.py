@@ -87,6 +87,10 @@ def load_library():
     L.pq_pack_codes.argtypes = [vp, i32, vp, i32, vp, vp]
     L.pq_unpack_codes.restype = ctypes.c_int
     L.pq_unpack_codes.argtypes = [vp, i32, vp, i32, vp, vp]
+    L.pq_kmeans_workspace_bytes.restype = ctypes.c_int64
+    L.pq_kmeans_workspace_bytes.argtypes = [vp]
+    L.pq_kmeans_fit.restype = ctypes.c_int
+    L.pq_kmeans_fit.argtypes = [vp, vp, i32, vp, i32, vp, ctypes.c_int64, vp]
     L.pq_stream_read_probe.restype = ctypes.c_int
     L.pq_stream_read_probe.argtypes = [vp, vp, ctypes.c_int64, vp]
     L.pq_attn_device_error.restype = ctypes.c_int
@@ -176,6 +180,18 @@ def pq_pack_codes(ctx, kind, token_major, n_tokens, packed, stream=None) -> None
 def pq_unpack_codes(ctx, kind, packed, n_tokens, token_major, stream=None) -> None:
     _check(load_library().pq_unpack_codes(ctx, int(kind), _addr(packed), int(n_tokens), _addr(token_major),
                                           _stream(stream)), "pq_unpack_codes")
+
+
+def pq_kmeans_workspace_bytes(ctx) -> int:
+    n = int(load_library().pq_kmeans_workspace_bytes(ctx))
+    if n < 0:
+        raise PQAttnError(n, "pq_kmeans_workspace_bytes")
+    return n
+
+
+def pq_kmeans_fit(ctx, samples, n_samples, codebook, n_iters, workspace, workspace_bytes, stream=None) -> None:
+    _check(load_library().pq_kmeans_fit(ctx, _addr(samples), int(n_samples), _addr(codebook), int(n_iters),
+                                        _addr(workspace), int(workspace_bytes), _stream(stream)), "pq_kmeans_fit")
 
 
 def pq_stream_read_probe(ctx, src, n_bytes, stream=None) -> None:

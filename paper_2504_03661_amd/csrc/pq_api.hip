@@ -307,6 +307,34 @@ int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32
     return pack_common(ctx, kind, token_major, n_tokens, const_cast<uint8_t *>(packed), true, hip_stream);
 }
 
+int64_t pq_kmeans_workspace_bytes(const pq_attn_ctx *ctx)
+{
+    if (ctx == nullptr)
+        return PQ_ERR_NULL;
+    if (ctx->cfg.dtype != PQ_F16)
+        return PQ_ERR_UNSUPPORTED;
+    return pq_kmeans_accumulator_bytes(ctx);
+}
+
+int pq_kmeans_fit(pq_attn_ctx *ctx, const void *samples, int32_t n_samples, void *codebook, int32_t n_iters,
+                  void *workspace, int64_t workspace_bytes, void *hip_stream)
+{
+    if (ctx == nullptr || samples == nullptr || codebook == nullptr || workspace == nullptr)
+        return PQ_ERR_NULL;
+    if (ctx->cfg.dtype != PQ_F16)
+        return PQ_ERR_UNSUPPORTED;
+    if (n_samples < 1 || n_iters < 1 || ((uintptr_t)workspace & 7) != 0)
+        return PQ_ERR_SHAPE;
+    if (n_samples > (1 << 20) || workspace_bytes < pq_kmeans_accumulator_bytes(ctx))
+        return PQ_ERR_CAPACITY;
+    device_guard guard(ctx->cfg.device);
+    if (!guard.ok)
+        return PQ_ERR_HIP;
+    return pq_launch_kmeans(ctx, samples, n_samples, codebook, n_iters, workspace, (hipStream_t)hip_stream) == hipSuccess
+               ? PQ_OK
+               : PQ_ERR_HIP;
+}
+
 int pq_stream_read_probe(pq_attn_ctx *ctx, const void *src, int64_t bytes, void *hip_stream)
 {
     if (ctx == nullptr || src == nullptr)

@@ -104,3 +104,8 @@ hipError_t pq_launch_pack_codebook(const pq_attn_ctx *ctx, const void *src, void
 hipError_t pq_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint8_t *token_major, int n_tokens,
                                 uint8_t *packed, bool unpack, hipStream_t s);
 hipError_t pq_launch_stream_read(const void *src, int64_t bytes, uint32_t *sink, hipStream_t s);
+// offline codebook training (fp16 contexts): accumulator bytes the caller's workspace must hold, and n_iters Lloyd
+// iterations over samples [Hkv][n_samples][d], codebook [Hkv][M][256][ds] updated in place
+int64_t pq_kmeans_accumulator_bytes(const pq_attn_ctx *ctx);
+hipError_t pq_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n_samples, void *codebook, int n_iters,
+                            void *workspace, hipStream_t s);

@@ -1,0 +1,165 @@
+// Offline codebook training: k-means per (KV head, subspace) by Lloyd's iteration on sampled
+// key / value vectors (Section II-C, training phase; Section III-A, "Offline PQ Codebook Training").
+//
+// One iteration = two kernels.
+//   assign   every sample sub-vector goes to its nearest centroid — the rule and the arithmetic of
+//            the encode kernel: squared Euclidean distance decided in IEEE double as
+//            dist = fma(x_j - c_j, x_j - c_j, dist), equal distances to the lowest index — and is
+//            added to that centroid's member sum and count.  fp16 values are integers times
+//            2^-24, so the sums are kept as 64-bit integers: exact, and independent of the order in
+//            which the atomics land (n_samples <= 2^20 keeps them below 2^61).
+//   update   centroid = double(sum) * 2^-24 / count in IEEE double, rounded to float and from there
+//            to fp16; a centroid without members keeps its value.  The kernel also clears the
+//            accumulators for the next iteration.
+// The paper does not say how it initialises, iterates or treats empty clusters; the initial
+// centroids are the caller's, the iteration count too.
+//
+// Mapping of `assign`: one workgroup = (head, subspace, slice of samples), 4 wavefronts sharing the
+// widened codebook (LDS, broadcast reads) and the slice's partial sums (LDS atomics); lane =
+// sample; the partial sums reach memory with one 64-bit atomic per touched entry.  Bound by the
+// fp64 vector ALU like the encode: (2 ds + 3) operations per (sub-vector, centroid).
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include "pq_internal.h"
+
+namespace {
+
+constexpr int KM_WAVES = 4;
+constexpr int KM_CHUNKS = 4;                           // 64-sample chunks per wavefront
+constexpr int KM_SLICE = KM_WAVES * KM_CHUNKS * 64;    // samples per workgroup
+
+template <int M, int DS>
+__global__ __launch_bounds__(KM_WAVES * 64) void pq_kmeans_assign_kernel(const __half *samples, const __half *codebook,
+                                                                        unsigned long long *sums, unsigned int *counts,
+                                                                        int n_samples, int n_slices)
+{
+#pragma clang fp contract(off)
+    __shared__ double cb[256 * DS];
+    __shared__ unsigned long long part_sum[256 * DS];
+    __shared__ unsigned int part_cnt[256];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int head = blockIdx.x / n_slices;
+    const int slice = blockIdx.x - head * n_slices;
+    const int i = blockIdx.y;  // subspace
+
+    const int64_t cb_base = ((int64_t)head * M + i) * 256 * DS;
+    for (int e = tid; e < 256 * DS; e += KM_WAVES * 64) {
+        cb[e] = (double)__half2float(codebook[cb_base + e]);
+        part_sum[e] = 0ull;
+    }
+    for (int e = tid; e < 256; e += KM_WAVES * 64)
+        part_cnt[e] = 0u;
+    __syncthreads();
+
+    for (int ch = 0; ch < KM_CHUNKS; ++ch) {
+        const int s = slice * KM_SLICE + (ch * KM_WAVES + wave) * 64 + lane;
+        if (s >= n_samples)
+            continue;
+        float xf[DS];
+        double x[DS];
+#pragma unroll
+        for (int j = 0; j < DS; ++j) {
+            xf[j] = __half2float(samples[((int64_t)head * n_samples + s) * PQ_HEAD_DIM + i * DS + j]);
+            x[j] = (double)xf[j];
+        }
+        int best = 0;
+        double best_dist = __builtin_huge_val();
+        for (int c = 0; c < 256; ++c) {
+            double dist = 0.0;
+#pragma unroll
+            for (int j = 0; j < DS; ++j) {
+                const double diff = x[j] - cb[c * DS + j];
+                dist = __builtin_fma(diff, diff, dist);
+            }
+            best = dist < best_dist ? c : best;  // strict "<", ascending scan: lowest index among equals
+            best_dist = __builtin_fmin(best_dist, dist);
+        }
+#pragma unroll
+        for (int j = 0; j < DS; ++j) {
+            // exact: an fp16 value times 2^24 is an integer below 2^41 in magnitude
+            const long long fixed = (long long)(xf[j] * 16777216.0f);
+            atomicAdd(&part_sum[best * DS + j], (unsigned long long)fixed);
+        }
+        atomicAdd(&part_cnt[best], 1u);
+    }
+    __syncthreads();
+
+    const int64_t acc_base = ((int64_t)head * M + i) * 256;
+    for (int e = tid; e < 256 * DS; e += KM_WAVES * 64)
+        if (part_sum[e] != 0ull)
+            atomicAdd(&sums[acc_base * DS + e], part_sum[e]);
+    for (int e = tid; e < 256; e += KM_WAVES * 64)
+        if (part_cnt[e] != 0u)
+            atomicAdd(&counts[acc_base + e], part_cnt[e]);
+}
+
+// one thread per (head, subspace, centroid)
+template <int DS>
+__global__ void pq_kmeans_update_kernel(__half *codebook, unsigned long long *sums, unsigned int *counts, int64_t n)
+{
+#pragma clang fp contract(off)
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n)
+        return;
+    const unsigned int count = counts[e];
+    if (count != 0u) {
+#pragma unroll
+        for (int j = 0; j < DS; ++j) {
+            const double sum = (double)(long long)sums[e * DS + j];
+            const double mean = sum * 5.9604644775390625e-08 / (double)count;  // 2^-24, then one division
+            codebook[e * DS + j] = __float2half_rn((float)mean);
+            sums[e * DS + j] = 0ull;
+        }
+        counts[e] = 0u;
+    }
+}
+
+__global__ void pq_clear_words_kernel(uint32_t *p, int64_t n)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < n)
+        p[e] = 0u;
+}
+
+}  // namespace
+
+int64_t pq_kmeans_accumulator_bytes(const pq_attn_ctx *ctx)
+{
+    const int64_t n = (int64_t)ctx->cfg.n_kv_heads * ctx->cfg.n_subspaces * 256;
+    return n * ctx->ds * 8 + n * 4;
+}
+
+hipError_t pq_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n_samples, void *codebook, int n_iters,
+                            void *workspace, hipStream_t s)
+{
+    const int Hkv = ctx->cfg.n_kv_heads, M = ctx->cfg.n_subspaces, DS = ctx->ds;
+    const int64_t n = (int64_t)Hkv * M * 256;
+    unsigned long long *sums = (unsigned long long *)workspace;
+    unsigned int *counts = (unsigned int *)(sums + n * DS);
+    const int64_t words = pq_kmeans_accumulator_bytes(ctx) / 4;
+    hipLaunchKernelGGL(pq_clear_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, s,
+                       (uint32_t *)workspace, words);
+    const int n_slices = (n_samples + KM_SLICE - 1) / KM_SLICE;
+    const dim3 grid((unsigned)(Hkv * n_slices), (unsigned)M), block(KM_WAVES * 64);
+    for (int it = 0; it < n_iters; ++it) {
+        if (M == 64) {
+            hipLaunchKernelGGL((pq_kmeans_assign_kernel<64, 2>), grid, block, 0, s, (const __half *)samples,
+                               (const __half *)codebook, sums, counts, n_samples, n_slices);
+            hipLaunchKernelGGL(pq_kmeans_update_kernel<2>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                               (__half *)codebook, sums, counts, n);
+        } else {
+            hipLaunchKernelGGL((pq_kmeans_assign_kernel<32, 4>), grid, block, 0, s, (const __half *)samples,
+                               (const __half *)codebook, sums, counts, n_samples, n_slices);
+            hipLaunchKernelGGL(pq_kmeans_update_kernel<4>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                               (__half *)codebook, sums, counts, n);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return e;
+    }
+    return hipGetLastError();
+}
