@@ -40,11 +40,21 @@
 #include <omp.h>
 #endif
 
+/* Width of a centroid index.  The 8-bit settings (256 centroids) store one byte per code; the
+ * paper's 12-bit setting (M = 32, 4096 centroids per subspace; Section IV-A, footnote on the
+ * (M, nbits) pairs) needs 16.  pq_oracle16.c compiles this file a second time with 16-bit codes
+ * and the function names suffixed _u16; nothing else differs. */
+#ifndef PQ_CODE_T
+#define PQ_CODE_T uint8_t
+#define PQ_NAME(n) n
+#endif
+#define PQ_MAX_CENTROIDS (1 << (8 * (int)sizeof(PQ_CODE_T)))
+
 /* Eq. 5: de-quantize n tokens of one KV head.
  *   codes    [n][M]            one centroid index per subspace
  *   codebook [M][C][ds]        centroids of this head
  *   out      [n][M*ds]         concatenation over subspaces of the gathered centroids */
-void oracle_pq_dequantize(const uint8_t *codes, const double *codebook, int64_t n, int M, int C, int ds,
+void PQ_NAME(oracle_pq_dequantize)(const PQ_CODE_T *codes, const double *codebook, int64_t n, int M, int C, int ds,
                           double *out)
 {
     const int d = M * ds;
@@ -58,7 +68,7 @@ void oracle_pq_dequantize(const uint8_t *codes, const double *codebook, int64_t 
 
 /* Eq. 1 for one query row: out = softmax(scale * q K^T) V over n rows of width d.
  * weights (optional, length n) receives the softmax weights.  n == 0 gives zeros. */
-void oracle_dense_attention(const double *q, const double *keys, const double *values, int64_t n, int d,
+void PQ_NAME(oracle_dense_attention)(const double *q, const double *keys, const double *values, int64_t n, int d,
                             double scale, double *out, double *weights)
 {
     for (int k = 0; k < d; ++k)
@@ -105,13 +115,13 @@ void oracle_dense_attention(const double *q, const double *keys, const double *v
  *
  * Query head hq reads KV head hq / (Hq / Hkv).  A sequence with no token at all
  * gives a row of zeros.  Returns 0, or -1 on a shape error / failed allocation. */
-int oracle_pq_decode(int B, int Hq, int Hkv, int d, int M, int C, const double *q, const uint8_t *k_codes,
-                     const uint8_t *v_codes, int64_t ctx_cap, const int32_t *ctx_len, const double *k_codebook,
+int PQ_NAME(oracle_pq_decode)(int B, int Hq, int Hkv, int d, int M, int C, const double *q, const PQ_CODE_T *k_codes,
+                     const PQ_CODE_T *v_codes, int64_t ctx_cap, const int32_t *ctx_len, const double *k_codebook,
                      const double *v_codebook, const double *recent_k, const double *recent_v, int64_t rec_cap,
                      const int32_t *recent_len, double scale, const int32_t *pairs, int64_t n_pairs, double *out,
                      double *weight_sum)
 {
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || M <= 0 || d % M || Hq % Hkv || C <= 0 || C > 256)
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || M <= 0 || d % M || Hq % Hkv || C <= 0 || C > PQ_MAX_CENTROIDS)
         return -1;
     const int ds = d / M;
     const int G = Hq / Hkv;
@@ -145,15 +155,15 @@ int oracle_pq_decode(int B, int Hq, int Hkv, int d, int M, int C, const double *
             continue;
         }
         const int64_t head = (int64_t)b * Hkv + hkv;
-        oracle_pq_dequantize(k_codes + head * ctx_cap * M, k_codebook + (int64_t)hkv * M * C * ds, N, M, C, ds,
+        PQ_NAME(oracle_pq_dequantize)(k_codes + head * ctx_cap * M, k_codebook + (int64_t)hkv * M * C * ds, N, M, C, ds,
                              keys);
-        oracle_pq_dequantize(v_codes + head * ctx_cap * M, v_codebook + (int64_t)hkv * M * C * ds, N, M, C, ds,
+        PQ_NAME(oracle_pq_dequantize)(v_codes + head * ctx_cap * M, v_codebook + (int64_t)hkv * M * C * ds, N, M, C, ds,
                              vals);
         if (R > 0) {
             memcpy(keys + N * d, recent_k + head * rec_cap * d, (size_t)R * d * sizeof(double));
             memcpy(vals + N * d, recent_v + head * rec_cap * d, (size_t)R * d * sizeof(double));
         }
-        oracle_dense_attention(q + ((int64_t)b * Hq + hq) * d, keys, vals, n, d, scale, o, wts);
+        PQ_NAME(oracle_dense_attention)(q + ((int64_t)b * Hq + hq) * d, keys, vals, n, d, scale, o, wts);
         if (weight_sum) {
             double sum = 0.0;
             for (int64_t t = 0; t < n; ++t)
@@ -173,8 +183,8 @@ int oracle_pq_decode(int B, int Hq, int Hkv, int d, int M, int C, const double *
  *   codes    [n][M]
  * The scan starts at centroid 0 and replaces the best only on a strictly smaller
  * distance, so equal distances keep the lowest index. */
-void oracle_pq_encode_head(const double *x, const double *codebook, int64_t n, int M, int C, int ds,
-                           uint8_t *codes)
+void PQ_NAME(oracle_pq_encode_head)(const double *x, const double *codebook, int64_t n, int M, int C, int ds,
+                           PQ_CODE_T *codes)
 {
     const int d = M * ds;
     for (int64_t t = 0; t < n; ++t)
@@ -192,7 +202,7 @@ void oracle_pq_encode_head(const double *x, const double *codebook, int64_t n, i
                     best_dist = dist;
                 }
             }
-            codes[t * M + i] = (uint8_t)best;
+            codes[t * M + i] = (PQ_CODE_T)best;
         }
 }
 
@@ -200,22 +210,22 @@ void oracle_pq_encode_head(const double *x, const double *codebook, int64_t n, i
  *   x        [B][Hkv][n_new][d]
  *   codebook [Hkv][M][C][ds]
  *   codes    [B][Hkv][n_new][M] */
-int oracle_pq_encode(int B, int Hkv, int d, int M, int C, int64_t n_new, const double *x, const double *codebook,
-                     uint8_t *codes)
+int PQ_NAME(oracle_pq_encode)(int B, int Hkv, int d, int M, int C, int64_t n_new, const double *x, const double *codebook,
+                     PQ_CODE_T *codes)
 {
-    if (B <= 0 || Hkv <= 0 || M <= 0 || d % M || C <= 0 || C > 256 || n_new < 0)
+    if (B <= 0 || Hkv <= 0 || M <= 0 || d % M || C <= 0 || C > PQ_MAX_CENTROIDS || n_new < 0)
         return -1;
     const int ds = d / M;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int64_t w = 0; w < (int64_t)B * Hkv; ++w) {
         const int hkv = (int)(w % Hkv);
-        oracle_pq_encode_head(x + w * n_new * d, codebook + (int64_t)hkv * M * C * ds, n_new, M, C, ds,
+        PQ_NAME(oracle_pq_encode_head)(x + w * n_new * d, codebook + (int64_t)hkv * M * C * ds, n_new, M, C, ds,
                               codes + w * n_new * M);
     }
     return 0;
 }
 
-int oracle_num_threads(void)
+int PQ_NAME(oracle_num_threads)(void)
 {
     int n = 1;
 #ifdef _OPENMP

@@ -36,12 +36,23 @@ def lib():
         L.oracle_dense_attention.restype = None
         L.oracle_dense_attention.argtypes = [vp, vp, vp, i64, i32, dbl, vp, vp]
         L.oracle_num_threads.restype = ctypes.c_int
+        # the same routines for 16-bit centroid indices (more than 256 centroids per subspace)
+        for name in ("oracle_pq_decode", "oracle_pq_encode", "oracle_pq_dequantize"):
+            wide = getattr(L, name + "_u16")
+            wide.restype = getattr(L, name).restype
+            wide.argtypes = getattr(L, name).argtypes
         _lib = L
     return _lib
 
 
 def _f64(a) -> np.ndarray:
     return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+def _code_width(n_centroids: int):
+    """(numpy dtype of a centroid index, suffix of the C routine) for a codebook of this size."""
+    assert 1 <= n_centroids <= 65536
+    return (np.uint8, "") if n_centroids <= 256 else (np.uint16, "_u16")
 
 
 def _ptr(a: Optional[np.ndarray]):
@@ -53,13 +64,16 @@ def num_threads() -> int:
 
 
 def dequantize(codes: np.ndarray, codebook: np.ndarray) -> np.ndarray:
-    """Eq. 5 for one head: codes [n, M] uint8, codebook [M, C, ds] -> [n, M*ds] float64."""
-    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    """Eq. 5 for one head: codes [n, M] (uint8, or uint16 for more than 256 centroids), codebook [M, C, ds]
+    -> [n, M*ds] float64."""
     cb = _f64(codebook)
-    n, M = codes.shape
     _, C, ds = cb.shape
+    code_t, suffix = _code_width(C)
+    assert int(np.max(codes, initial=0)) < C
+    codes = np.ascontiguousarray(codes, dtype=code_t)
+    n, M = codes.shape
     out = np.empty((n, M * ds), dtype=np.float64)
-    lib().oracle_pq_dequantize(_ptr(codes), _ptr(cb), n, M, C, ds, _ptr(out))
+    getattr(lib(), "oracle_pq_dequantize" + suffix)(_ptr(codes), _ptr(cb), n, M, C, ds, _ptr(out))
     return out
 
 
@@ -83,13 +97,16 @@ def decode(q, k_codes, v_codes, ctx_len, k_codebook, v_codebook, recent_k=None, 
     """
     qd = _f64(q)
     B, Hq, d = qd.shape
-    k_codes = np.ascontiguousarray(k_codes, dtype=np.uint8)
-    v_codes = np.ascontiguousarray(v_codes, dtype=np.uint8)
+    kcb, vcb = _f64(k_codebook), _f64(v_codebook)
+    C, ds = kcb.shape[2], kcb.shape[3]
+    code_t, suffix = _code_width(C)
+    if C < np.iinfo(code_t).max + 1:
+        assert int(np.max(k_codes, initial=0)) < C and int(np.max(v_codes, initial=0)) < C
+    k_codes = np.ascontiguousarray(k_codes, dtype=code_t)
+    v_codes = np.ascontiguousarray(v_codes, dtype=code_t)
     _, Hkv, ctx_cap, M = k_codes.shape
     assert v_codes.shape == k_codes.shape
-    kcb, vcb = _f64(k_codebook), _f64(v_codebook)
     assert kcb.shape == vcb.shape and kcb.shape[0] == Hkv and kcb.shape[1] == M
-    C, ds = kcb.shape[2], kcb.shape[3]
     assert M * ds == d
     cl = np.ascontiguousarray(ctx_len, dtype=np.int32)
     assert cl.shape == (B,) and (cl >= 0).all() and (cl <= ctx_cap).all()
@@ -113,7 +130,7 @@ def decode(q, k_codes, v_codes, ctx_len, k_codebook, v_codebook, recent_k=None, 
         pr = np.ascontiguousarray(np.unique(np.asarray(pairs, dtype=np.int32).reshape(-1, 2), axis=0))
         n_pairs = pr.shape[0]
         assert (pr[:, 0] >= 0).all() and (pr[:, 0] < B).all() and (pr[:, 1] >= 0).all() and (pr[:, 1] < Hq).all()
-    rc = lib().oracle_pq_decode(B, Hq, Hkv, d, M, C, _ptr(qd), _ptr(k_codes), _ptr(v_codes), ctx_cap, _ptr(cl),
+    rc = getattr(lib(), "oracle_pq_decode" + suffix)(B, Hq, Hkv, d, M, C, _ptr(qd), _ptr(k_codes), _ptr(v_codes), ctx_cap, _ptr(cl),
                                 _ptr(kcb), _ptr(vcb), _ptr(rk), _ptr(rv), rec_cap, _ptr(rl),
                                 float(np.float32(scale)), _ptr(pr), n_pairs, _ptr(out), _ptr(wsum))
     if rc != 0:
@@ -122,13 +139,14 @@ def decode(q, k_codes, v_codes, ctx_len, k_codebook, v_codebook, recent_k=None, 
 
 
 def encode(x, codebook) -> np.ndarray:
-    """Eq. 4: x [B, Hkv, n, d], codebook [Hkv, M, C, ds] -> codes [B, Hkv, n, M] uint8."""
+    """Eq. 4: x [B, Hkv, n, d], codebook [Hkv, M, C, ds] -> codes [B, Hkv, n, M] (uint8; uint16 when C > 256)."""
     xd, cb = _f64(x), _f64(codebook)
     B, Hkv, n, d = xd.shape
     _, M, C, ds = cb.shape
     assert cb.shape[0] == Hkv and M * ds == d
-    codes = np.empty((B, Hkv, n, M), dtype=np.uint8)
-    rc = lib().oracle_pq_encode(B, Hkv, d, M, C, n, _ptr(xd), _ptr(cb), _ptr(codes))
+    code_t, suffix = _code_width(C)
+    codes = np.empty((B, Hkv, n, M), dtype=code_t)
+    rc = getattr(lib(), "oracle_pq_encode" + suffix)(B, Hkv, d, M, C, n, _ptr(xd), _ptr(cb), _ptr(codes))
     if rc != 0:
         raise RuntimeError("oracle_pq_encode failed (shape error)")
     return codes

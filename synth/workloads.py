@@ -8,9 +8,9 @@ here so that the two sides see identical bits.
 All tensors are numpy arrays in the *logical* layouts of the problem statement:
 
     q            [B, Hq, d]                 dtype
-    k_codebook   [Hkv, M, 256, ds]          dtype   (ds = d / M)
-    v_codebook   [Hkv, M, 256, ds]          dtype
-    k_codes      [B, Hkv, ctx_cap, M]       uint8   (token-major)
+    k_codebook   [Hkv, M, C, ds]            dtype   (ds = d / M; C = 256, or 4096 for the 12-bit setting)
+    v_codebook   [Hkv, M, C, ds]            dtype
+    k_codes      [B, Hkv, ctx_cap, M]       uint8   (token-major; uint16 when C = 4096)
     v_codes      [B, Hkv, ctx_cap, M]       uint8
     ctx_len      [B]                        int32
     recent_k/v   [B, Hkv, rec_cap, d]       dtype   (rows >= recent_len[b] are NaN)
@@ -54,6 +54,7 @@ class Workload:
     n_new: int = 0               # tokens appended per step through encode
     seed: int = BASE_SEED
     ctx_lens: Optional[tuple] = None     # explicit per-sequence lengths (tests)
+    n_centroids: int = N_CENTROIDS       # 256 (8-bit codes) or 4096 (12-bit codes, held in uint16)
 
     @property
     def sub_dim(self) -> int:
@@ -113,9 +114,9 @@ def generate(w: Workload, ctx_cap: Optional[int] = None) -> Dict[str, np.ndarray
     out["q"] = _normal(rng, (B, Hq, d), dt)
 
     def codebook():
-        cb = rng.standard_normal((Hkv, M, N_CENTROIDS, ds), dtype=np.float32)
+        cb = rng.standard_normal((Hkv, M, w.n_centroids, ds), dtype=np.float32)
         if w.outlier_frac > 0.0:
-            mask = rng.random((Hkv, M, N_CENTROIDS, ds)) < w.outlier_frac
+            mask = rng.random((Hkv, M, w.n_centroids, ds)) < w.outlier_frac
             cb = np.where(mask, cb * np.float32(w.outlier_scale), cb)
         return cb.astype(dt)
 
@@ -123,7 +124,8 @@ def generate(w: Workload, ctx_cap: Optional[int] = None) -> Dict[str, np.ndarray
     out["v_codebook"] = codebook()
 
     def codes():
-        return rng.integers(0, N_CENTROIDS, size=(B, Hkv, cap, M), dtype=np.uint8)
+        return rng.integers(0, w.n_centroids, size=(B, Hkv, cap, M),
+                            dtype=np.uint8 if w.n_centroids <= 256 else np.uint16)
 
     out["k_codes"] = codes()
     out["v_codes"] = codes()

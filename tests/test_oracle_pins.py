@@ -310,3 +310,58 @@ def test_encode_equidistant_tie_goes_to_lowest_index():
     cb[0, 0, 77] = [0.25, 0.5]     # same norm, third tie
     x = np.zeros((1, 1, 1, 2))
     assert O.encode(x, cb)[0, 0, 0, 0] == 4
+
+
+# ------------------------------------------------------------------ 12-bit codes (4096 centroids, 16-bit indices)
+
+
+def test_wide_code_routines_agree_with_the_byte_routines_on_byte_sized_codebooks():
+    """The 16-bit-index build of the oracle is the same source: on a 256-centroid problem it must return
+    exactly what the byte build returns (checked against brute force above)."""
+    w, data = small(7, d=16, M=4, R=3, dtype="f16", lens=(29, 8))
+    ref = run_oracle(w, data)
+    L = O.lib()
+    f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    k16 = np.ascontiguousarray(data["k_codes"], dtype=np.uint16)
+    v16 = np.ascontiguousarray(data["v_codes"], dtype=np.uint16)
+    out = np.full(ref.shape, np.nan)
+    wsum = np.full(ref.shape[:2], np.nan)
+    q, kcb, vcb, rk, rv = f64(data["q"]), f64(data["k_codebook"]), f64(data["v_codebook"]), f64(data["recent_k"]), f64(data["recent_v"])
+    cl = np.ascontiguousarray(data["ctx_len"], dtype=np.int32)
+    rl = np.ascontiguousarray(data["recent_len"], dtype=np.int32)
+    p = lambda a: a.ctypes.data
+    rc = L.oracle_pq_decode_u16(w.batch, w.n_q_heads, w.n_kv_heads, 16, 4, 256, p(q), p(k16), p(v16), k16.shape[2], p(cl),
+                                p(kcb), p(vcb), p(rk), p(rv), rk.shape[2], p(rl), float(W.attention_scale(w)), None, 0,
+                                p(out), p(wsum))
+    assert rc == 0
+    assert (out == ref).all()
+
+
+@pytest.mark.parametrize("seed,R", [(0, 4), (1, 0)])
+def test_decode_with_4096_centroids_matches_brute_force_library_softmax(seed, R):
+    """Brute force (numpy gather + scipy softmax) on a tiny 12-bit problem: M = 4 subspaces of 4 dims, 4096
+    centroids each, codes up to 4095 held in uint16."""
+    w = W.Workload("t12", 2, 2, 2, 16, 4, 45, "f16", recent_cap=R, recent_fixed=R if R else None, seed=2000 + seed,
+                   ctx_lens=(45, 13), n_centroids=4096)
+    data = W.generate(w)
+    assert data["k_codes"].dtype == np.uint16 and data["k_codes"].max() > 255
+    out = run_oracle(w, data)
+    for b in range(2):
+        for h in range(2):
+            np.testing.assert_allclose(out[b, h], brute_force(data, W.attention_scale(w), b, h), rtol=1e-12, atol=1e-13)
+
+
+def test_encode_with_4096_centroids_matches_library_vector_quantizer():
+    """scipy.cluster.vq.vq on each subspace (float64 Euclidean nearest neighbour); random data, no ties."""
+    rng = np.random.default_rng(12)
+    cb = rng.standard_normal((1, 2, 4096, 4)).astype(np.float16)
+    x = rng.standard_normal((1, 1, 300, 8)).astype(np.float16)
+    codes = O.encode(x, cb)
+    assert codes.dtype == np.uint16 and codes.max() > 255
+    for i in range(2):
+        want, _ = scipy.cluster.vq.vq(x[0, 0, :, 4 * i:4 * i + 4].astype(np.float64), cb[0, i].astype(np.float64))
+        assert (codes[0, 0, :, i] == want).all()
+    # exact hits and duplicated centroids: the lowest index wins
+    cb[0, 0, 4000] = cb[0, 0, 17]
+    x[0, 0, 0, :4] = cb[0, 0, 4000]
+    assert O.encode(x, cb)[0, 0, 0, 0] == 17
