@@ -82,7 +82,7 @@ int pq_attn_destroy(pq_attn_ctx *ctx);
 int pq_attn_n_splits(const pq_attn_ctx *ctx);
 
 /* Registers the codebooks trained offline (Section III-A, "Offline PQ Codebook
- * Training"): C_K, C_V as [Hkv][M][256][ds] in the context dtype, device memory.
+ * Training"): C_K, C_V as [Hkv][M][C][ds] in the context dtype, device memory.
  * The library keeps its own re-packed copy (centroid-major, the image the decode
  * kernel streams into LDS), so the caller's tensors are only read during this
  * call's kernels.  pq_attn_decode and pq_encode_append call this themselves when
@@ -101,7 +101,7 @@ int pq_attn_set_codebooks(pq_attn_ctx *ctx, const void *k_codebook /* device */,
  *   k_codes     device, pq_attn_codes_bytes()     device layout (PQ_CODES_K)
  *   v_codes     device, pq_attn_codes_bytes()     device layout (PQ_CODES_V)
  *   ctx_len     device [B] int32                  N_b, clamped to [0, max_context]
- *   k_codebook  device [Hkv][M][256][ds] dtype    or NULL = the registered ones
+ *   k_codebook  device [Hkv][M][C][ds] dtype      or NULL = the registered ones
  *   v_codebook  likewise
  *   recent_k/v  device [B][Hkv][max_recent][d]    dtype; both NULL = no window
  *   recent_len  device [B] int32                  R_b, clamped to [0, max_recent]; NULL = all 0
@@ -131,6 +131,9 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
  * two are given different length arrays and the decode does not attend over the positions being
  * written (asynchronous quantization, Section III-B); the caller publishes the new lengths afterwards.
  *
+ * With 12-bit codes the call stages the codes in context-owned memory; an append larger than any before on
+ * this context allocates that memory and synchronises the device first.
+ *
  * 0 < n_new <= max_context, else PQ_ERR_CAPACITY.  Tokens that would land beyond
  * max_context for some sequence are dropped, that sequence's length saturates, and
  * bit 0 of the device error word is set (see pq_attn_device_error). */
@@ -138,12 +141,12 @@ int pq_encode_append(pq_attn_ctx *ctx, const void *new_k, const void *new_v, int
                      const void *v_codebook, uint8_t *k_codes, uint8_t *v_codes, int32_t *ctx_len, void *hip_stream);
 
 /* Layout conversion of code tensors (device to device, asynchronous).
- *   token_major device [B][Hkv][n_tokens][M] uint8, n_tokens <= max_context
+ *   token_major device [B][Hkv][n_tokens][M] uint8 (uint16 for 12-bit codes), n_tokens <= max_context
  *   packed      device, pq_attn_codes_bytes()
  * pack writes tokens 0..n_tokens-1 of every head; unpack reads them. */
-int pq_pack_codes(pq_attn_ctx *ctx, int32_t kind /* pq_code_kind */, const uint8_t *token_major, int32_t n_tokens,
+int pq_pack_codes(pq_attn_ctx *ctx, int32_t kind /* pq_code_kind */, const void *token_major, int32_t n_tokens,
                   uint8_t *packed, void *hip_stream);
-int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32_t n_tokens, uint8_t *token_major,
+int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32_t n_tokens, void *token_major,
                     void *hip_stream);
 
 /* Offline codebook training (Section II-C, training phase; Section III-A, "Offline PQ Codebook Training"):
@@ -158,7 +161,7 @@ int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32
  *   workspace  device, 8-byte aligned, at least pq_kmeans_workspace_bytes(ctx) bytes (else PQ_ERR_CAPACITY);
  *              contents need not be initialised and are garbage afterwards
  *
- * fp16 contexts only (PQ_ERR_UNSUPPORTED otherwise).  Asynchronous on the stream.  Training a codebook that
+ * fp16 contexts with 8-bit codes only (PQ_ERR_UNSUPPORTED otherwise).  Asynchronous on the stream.  Training a codebook that
  * is registered with the context in place requires pq_attn_set_codebooks afterwards. */
 int64_t pq_kmeans_workspace_bytes(const pq_attn_ctx *ctx);
 int pq_kmeans_fit(pq_attn_ctx *ctx, const void *samples /* device */, int32_t n_samples, void *codebook /* device */,

@@ -1,0 +1,232 @@
+// 12-bit codes (M = 32 subspaces of 4 dims, 4096 centroids per subspace — the paper's 3-bit-per-
+// dimension setting, Section IV-A): nearest-centroid encode and the conversions between the logical
+// token-major form [B][Hkv][n][32] uint16 and the device layouts of pq_internal.h.
+//
+// Encode (Eq. 4 with Section II-C's nearest-centroid assignment) follows the 8-bit encode kernel: lane =
+// token, squared Euclidean distance decided in IEEE double as dist = fma(x_j - c_j, x_j - c_j, dist),
+// strict "<" on an ascending scan so that equal distances go to the lowest index.  A subspace's 4096
+// centroids, widened to double, take 128 KiB: they pass through LDS in four tiles of 1024.
+// Two 12-bit codes share bytes, so the kernel does not write the device layout itself: codes go to a
+// token-major staging buffer and a second kernel packs them behind the current lengths, one thread per
+// 12-byte unit (a V unit holds 8 tokens of one subspace: the thread keeps the codes of tokens it does
+// not append).
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include "pq_internal.h"
+
+namespace {
+
+constexpr int E12_WAVES = 4;
+constexpr int E12_TILE = 1024;  // centroids per LDS tile
+
+__device__ inline void pack8(const uint32_t (&c)[8], uint32_t (&w)[3])
+{
+    w[0] = c[0] | (c[1] << 12) | (c[2] << 24);
+    w[1] = (c[2] >> 8) | (c[3] << 4) | (c[4] << 16) | (c[5] << 28);
+    w[2] = (c[5] >> 4) | (c[6] << 8) | (c[7] << 20);
+}
+
+__device__ inline void unpack8(const uint32_t (&w)[3], uint32_t (&c)[8])
+{
+    c[0] = w[0] & 0xfffu;
+    c[1] = (w[0] >> 12) & 0xfffu;
+    c[2] = ((w[0] >> 24) | (w[1] << 8)) & 0xfffu;
+    c[3] = (w[1] >> 4) & 0xfffu;
+    c[4] = (w[1] >> 16) & 0xfffu;
+    c[5] = ((w[1] >> 28) | (w[2] << 4)) & 0xfffu;
+    c[6] = (w[2] >> 8) & 0xfffu;
+    c[7] = w[2] >> 20;
+}
+
+__global__ __launch_bounds__(E12_WAVES * 64) void pq12_encode_kernel(const __half *x0, const __half *x1,
+                                                                    const __half *cb0, const __half *cb1,
+                                                                    uint16_t *out0, uint16_t *out1, int Hkv, int n_new)
+{
+#pragma clang fp contract(off)
+    __shared__ double tile[E12_TILE * 4];
+
+    const int tid = threadIdx.x;
+    const int which = blockIdx.z;  // 0: keys, 1: values
+    const int i = blockIdx.y;      // subspace
+    const int n_chunks = (n_new + E12_WAVES * 64 - 1) / (E12_WAVES * 64);
+    const int chunk = blockIdx.x % n_chunks;
+    const int head = blockIdx.x / n_chunks;  // b * Hkv + hkv
+    const int hkv = head % Hkv;
+    const __half *x = which ? x1 : x0;
+    const __half *cb = (which ? cb1 : cb0) + ((int64_t)hkv * PQ12_M + i) * PQ12_CENTROIDS * 4;
+    uint16_t *out = which ? out1 : out0;
+
+    const int tok = chunk * (E12_WAVES * 64) + tid;
+    const bool live = tok < n_new;
+    double xv[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        xv[j] = live ? (double)__half2float(x[((int64_t)head * n_new + tok) * PQ_HEAD_DIM + i * 4 + j]) : 0.0;
+
+    int best = 0;
+    double best_dist = __builtin_huge_val();
+    for (int t0 = 0; t0 < PQ12_CENTROIDS; t0 += E12_TILE) {
+        __syncthreads();  // the previous tile has been scanned by every wavefront
+        for (int e = tid; e < E12_TILE * 4; e += E12_WAVES * 64)
+            tile[e] = (double)__half2float(cb[t0 * 4 + e]);
+        __syncthreads();
+        for (int c = 0; c < E12_TILE; ++c) {
+            double dist = 0.0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double diff = xv[j] - tile[c * 4 + j];
+                dist = __builtin_fma(diff, diff, dist);
+            }
+            best = dist < best_dist ? t0 + c : best;  // ascending scan, strict "<": lowest index among equals
+            best_dist = __builtin_fmin(best_dist, dist);
+        }
+    }
+    if (live)
+        out[((int64_t)head * n_new + tok) * PQ12_M + i] = (uint16_t)best;
+}
+
+// K units: one thread per (head, token j of the source, group of 8 subspaces)
+__global__ void pq12_pack_k_kernel(const uint16_t *src, uint8_t *dst, const int32_t *pos0, int n, int Hkv, int max_context,
+                                   int64_t head_stride, int64_t total)
+{
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= total)
+        return;
+    const int g = (int)(x & 3);
+    const int64_t j = (x >> 2) % n;
+    const int64_t head = (x >> 2) / n;
+    int64_t p0 = pos0 ? pos0[head / Hkv] : 0;
+    p0 = p0 < 0 ? 0 : p0;
+    const int64_t pos = p0 + j;
+    if (pos >= max_context)
+        return;
+    uint32_t c[8], w[3];
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+        c[s] = src[(head * n + j) * PQ12_M + 8 * g + s] & 0xfffu;
+    pack8(c, w);
+    int slot;
+    uint32_t *d = (uint32_t *)(dst + head * head_stride + pq12_k_unit(pos, 8 * g, &slot));
+    d[0] = w[0];
+    d[1] = w[1];
+    d[2] = w[2];
+}
+
+// V units: one thread per (head, 128-token block touched by the source, group of 4 subspaces, lane)
+__global__ void pq12_pack_v_kernel(const uint16_t *src, uint8_t *dst, const int32_t *pos0, int n, int Hkv, int max_context,
+                                   int64_t cap_padded, int64_t head_stride, int n_vb, int64_t total)
+{
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= total)
+        return;
+    const int lane = (int)(x & 63);
+    const int g = (int)((x >> 6) & 7);
+    const int64_t vb_rel = (x >> 9) % n_vb;
+    const int64_t head = (x >> 9) / n_vb;
+    int64_t p0 = pos0 ? pos0[head / Hkv] : 0;
+    p0 = p0 < 0 ? 0 : p0;
+    const int64_t vblock = (p0 >> 7) + vb_rel;
+    if (vblock * 128 >= cap_padded)
+        return;
+    const int sub = 4 * g + (lane & 3);
+    bool any = false;
+    int64_t jj[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int64_t tok = vblock * 128 + (lane >> 2) + 16 * k;
+        const int64_t j = tok - p0;
+        jj[k] = (j >= 0 && j < n && tok < max_context) ? j : -1;
+        any = any || jj[k] >= 0;
+    }
+    if (!any)
+        return;
+    int slot;
+    uint32_t *d = (uint32_t *)(dst + head * head_stride + pq12_v_unit(vblock * 128 + (lane >> 2), sub, &slot));
+    uint32_t w[3] = {d[0], d[1], d[2]}, c[8];
+    unpack8(w, c);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+        if (jj[k] >= 0)
+            c[k] = src[(head * n + jj[k]) * PQ12_M + sub] & 0xfffu;
+    pack8(c, w);
+    d[0] = w[0];
+    d[1] = w[1];
+    d[2] = w[2];
+}
+
+// one thread per code of the token-major tensor
+__global__ void pq12_unpack_kernel(const uint8_t *packed, uint16_t *token_major, int kind, int n, int64_t head_stride,
+                                   int64_t total)
+{
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= total)
+        return;
+    const int i = (int)(x % PQ12_M);
+    const int64_t t = (x / PQ12_M) % n;
+    const int64_t head = x / ((int64_t)PQ12_M * n);
+    int slot;
+    const int64_t unit = kind == PQ_CODES_K ? pq12_k_unit(t, i, &slot) : pq12_v_unit(t, i, &slot);
+    const uint8_t *b = packed + head * head_stride + unit + ((3 * slot) >> 1);
+    const uint32_t two = (uint32_t)b[0] | ((uint32_t)b[1] << 8);
+    token_major[x] = (uint16_t)((two >> (4 * (slot & 1))) & 0xfffu);
+}
+
+hipError_t launch_pack(const pq_attn_ctx *ctx, int kind, const uint16_t *src, int n, uint8_t *dst, const int32_t *pos0,
+                       hipStream_t s)
+{
+    const int64_t heads = (int64_t)ctx->cfg.batch * ctx->cfg.n_kv_heads;
+    const int64_t head_stride = ctx->cap_padded * PQ12_TOKEN_BYTES;
+    if (n == 0)
+        return hipSuccess;
+    if (kind == PQ_CODES_K) {
+        const int64_t total = heads * n * 4;
+        hipLaunchKernelGGL(pq12_pack_k_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, src, dst, pos0, n,
+                           ctx->cfg.n_kv_heads, ctx->cfg.max_context, head_stride, total);
+    } else {
+        const int n_vb = ((n + 127) >> 7) + 1;
+        const int64_t total = heads * n_vb * 512;
+        hipLaunchKernelGGL(pq12_pack_v_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, src, dst, pos0, n,
+                           ctx->cfg.n_kv_heads, ctx->cfg.max_context, ctx->cap_padded, head_stride, n_vb, total);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool pq_config_is_12bit(const pq_attn_config *cfg) { return cfg->n_centroids == PQ12_CENTROIDS; }
+
+hipError_t pq12_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint16_t *token_major, int n_tokens,
+                                  uint8_t *packed, bool unpack, hipStream_t s)
+{
+    if (!unpack)
+        return launch_pack(ctx, kind, token_major, n_tokens, packed, nullptr, s);
+    const int64_t heads = (int64_t)ctx->cfg.batch * ctx->cfg.n_kv_heads;
+    const int64_t total = heads * n_tokens * PQ12_M;
+    if (total == 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(pq12_unpack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, packed,
+                       const_cast<uint16_t *>(token_major), kind, n_tokens, ctx->cap_padded * PQ12_TOKEN_BYTES, total);
+    return hipGetLastError();
+}
+
+hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len,
+                                     unsigned int *dev_err, hipStream_t s)
+{
+    const int n_chunks = (a.n_new + E12_WAVES * 64 - 1) / (E12_WAVES * 64);
+    const dim3 grid((unsigned)(a.B * a.Hkv * n_chunks), PQ12_M, 2);
+    hipLaunchKernelGGL(pq12_encode_kernel, grid, dim3(E12_WAVES * 64), 0, s, (const __half *)a.x[0],
+                       (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
+                       ctx->stage[0], ctx->stage[1], a.Hkv, a.n_new);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return e;
+    e = launch_pack(ctx, PQ_CODES_K, ctx->stage[0], a.n_new, a.codes[0], a.ctx_len, s);
+    if (e != hipSuccess)
+        return e;
+    e = launch_pack(ctx, PQ_CODES_V, ctx->stage[1], a.n_new, a.codes[1], a.ctx_len, s);
+    if (e != hipSuccess)
+        return e;
+    // the lengths move only after both packing kernels have read the old ones (stream order)
+    return pq_launch_bump_len(ctx_len, a.B, a.n_new, a.max_context, dev_err, s);
+}

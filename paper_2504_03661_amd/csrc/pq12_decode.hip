@@ -1,0 +1,321 @@
+// Decode attention over a KV cache quantized with 12-bit PQ codes (M = 32 subspaces of 4 dims, 4096
+// centroids per subspace: the paper's 3-bit-per-dimension setting, Section IV-A), one fused kernel.
+//
+// Same result as the 8-bit kernels (Eq. 7 = Eq. 6: tables q^i . (C_K^i)^T sampled by the key codes, one
+// softmax shared with the full-precision rows, values aggregated through C_V by the value codes), but
+// the tables no longer fit: 32 x 4096 fp32 table entries are 512 KiB, the fp16 value codebook 1 MiB, the
+// LDS of a compute unit 160 KiB.  So a workgroup takes its context split in chunks of 4096 tokens and
+// walks the SUBSPACES in groups, with one 128 KiB table region in LDS that is refilled per group:
+//
+//   score passes   4 groups of 8 subspaces: build the group's table [8][4096] fp32 from the key codebook
+//                  (L2) and the query, then every wavefront adds, for its 4 blocks of 64 tokens
+//                  (lane = token, partial scores in registers), the 8 sampled entries per token;
+//   softmax        chunk maximum over the workgroup, running maximum / rescale across chunks, the
+//                  chunk's weights to LDS (16 KiB);
+//   value passes   8 groups of 4 subspaces: copy the group's slice of the value codebook (128 KiB) to
+//                  LDS, then lane = (subspace of the group, one of 16 token streams) gathers the 8-byte
+//                  centroid of its subspace for every 16th token and accumulates weight x centroid;
+//                  the 16 streams are summed once, at the end.
+// The code tensors are group-major (pq_internal.h) so that every pass streams exactly its own bytes:
+// each code byte still comes from HBM once.  What is new against the 8-bit kernels is table traffic:
+// 2 MiB of codebook per 4096-token chunk from L2 against 384 KiB of codes from HBM.
+// Gathers from a [subspace][code] table hit random banks (no layout can avoid that for random
+// codes); the recent rows, the split merge and the ticket protocol are those of the 8-bit kernel.
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include "pq_internal.h"
+#include "pq_device_utils.h"
+
+namespace {
+
+constexpr int NW12 = 16;
+constexpr int CHUNK_VB = 32;                          // 128-token blocks per chunk (4096 tokens)
+constexpr int TAB_OFF = 0;                            // 128 KiB: score table [8][4096] fp32 / value image [4][4096][4] fp16
+constexpr int P_OFF = 131072;                         // float [4096]: weights of the chunk
+constexpr int Q12_OFF = P_OFF + 16384;                // float [128]: query x scale x log2(e)
+constexpr int WMAX_OFF = Q12_OFF + 512;               // float [16]
+constexpr int PART12_OFF = WMAX_OFF + 64;             // float [16][PQ_PART_STRIDE]
+constexpr int SMEM12_BYTES = PART12_OFF + NW12 * PQ_PART_STRIDE * 4;
+static_assert(SMEM12_BYTES <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+
+__device__ inline void unpack8(const uint32_t w0, const uint32_t w1, const uint32_t w2, uint32_t (&c)[8])
+{
+    c[0] = w0 & 0xfffu;
+    c[1] = (w0 >> 12) & 0xfffu;
+    c[2] = ((w0 >> 24) | (w1 << 8)) & 0xfffu;
+    c[3] = (w1 >> 4) & 0xfffu;
+    c[4] = (w1 >> 16) & 0xfffu;
+    c[5] = ((w1 >> 28) | (w2 << 4)) & 0xfffu;
+    c[6] = (w2 >> 8) & 0xfffu;
+    c[7] = w2 >> 20;
+}
+
+__device__ inline float dot4(const f32x4 &q, uint32_t lo, uint32_t hi)
+{
+    const __half2 a = *(const __half2 *)&lo, b = *(const __half2 *)&hi;
+    float e = q.x * __low2float(a);
+    e = fmaf(q.y, __high2float(a), e);
+    e = fmaf(q.z, __low2float(b), e);
+    return fmaf(q.w, __high2float(b), e);
+}
+
+__global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_args a)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM12_BYTES];
+    lds_u8 *lbase = (lds_u8 *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const uint32_t grid = gridDim.x;
+    uint32_t logical = blockIdx.x;
+    if ((grid & 7u) == 0)
+        logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
+    const int S = a.S;
+    const int bh = (int)(logical / (uint32_t)S);
+    const int split = (int)(logical - (uint32_t)bh * (uint32_t)S);
+    const int b = (int)((uint32_t)bh / (uint32_t)a.Hq);
+    const int hq = bh - b * a.Hq;
+    const int hkv = (int)((uint32_t)hq / (uint32_t)a.G);
+
+    int N = a.ctx_len[b];
+    int R = (a.recent_k != nullptr && a.recent_len != nullptr) ? a.recent_len[b] : 0;
+    N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
+    R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
+    const uint32_t nvb = (uint32_t)(N + 127) >> 7;  // 128-token blocks of the sequence
+    const int vb0 = (int)(nvb * (uint32_t)split / (uint32_t)S);
+    const int vb1 = (int)(nvb * (uint32_t)(split + 1) / (uint32_t)S);
+    const int r0 = (int)((uint32_t)R * (uint32_t)split / (uint32_t)S);
+    const int r1 = (int)((uint32_t)R * (uint32_t)(split + 1) / (uint32_t)S);
+
+    const uint8_t *k_head = a.k_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
+    const uint8_t *v_head = a.v_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
+    const __half *kcb = (const __half *)a.kcb_packed + (int64_t)hkv * PQ12_M * PQ12_CENTROIDS * 4;
+    const __half *vcb = (const __half *)a.vcb_packed + (int64_t)hkv * PQ12_M * PQ12_CENTROIDS * 4;
+
+    lds_f32 *qs = (lds_f32 *)(lbase + Q12_OFF);
+    lds_f32 *pw = (lds_f32 *)(lbase + P_OFF);
+    lds_f32 *wmax = (lds_f32 *)(lbase + WMAX_OFF);
+    if (tid < PQ_HEAD_DIM)
+        qs[tid] = __half2float(((const __half *)a.q)[((int64_t)b * a.Hq + hq) * PQ_HEAD_DIM + tid]) * a.scale_log2e;
+
+    float m_run = NEG_BIG;  // running maximum, the same in every wavefront of the workgroup
+    float l_lane = 0.f;
+    float acc[8][4];
+#pragma unroll
+    for (int g = 0; g < 8; ++g)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[g][j] = 0.f;
+
+    for (int vbc = vb0; vbc < vb1; vbc += CHUNK_VB) {
+        // ---------------- score passes: 4 groups of 8 subspaces
+        float score[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int g = 0; g < 4; ++g) {
+            __syncthreads();  // the table region is free (and, the first time, the query is in LDS)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int sub = 8 * g + i;
+                const u32x4 *src = (const u32x4 *)(kcb + ((int64_t)sub * PQ12_CENTROIDS + 4 * tid) * 4);
+                const u32x4 c01 = src[0], c23 = src[1];  // centroids 4 tid .. 4 tid + 3, four fp16 each
+                const f32x4 q4 = *(lds_f32x4 *)(lbase + Q12_OFF + sub * 16);
+                f32x4 ent;
+                ent.x = dot4(q4, c01.x, c01.y);
+                ent.y = dot4(q4, c01.z, c01.w);
+                ent.z = dot4(q4, c23.x, c23.y);
+                ent.w = dot4(q4, c23.z, c23.w);
+                *(lds_f32x4 *)(lbase + TAB_OFF + (i * PQ12_CENTROIDS + 4 * tid) * 4) = ent;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+                const int kblk = 2 * vbc + 4 * wave + jb;  // 64-token block of the head
+                if (kblk < 2 * vb1) {
+                    const uint32_t *src = (const uint32_t *)(k_head + (((int64_t)kblk * 4 + g) * 64 + lane) * 12);
+                    uint32_t c[8];
+                    unpack8(src[0], src[1], src[2], c);
+                    float sum = 0.f;
+#pragma unroll
+                    for (int s = 0; s < 8; ++s)
+                        sum += *(lds_f32 *)(lbase + TAB_OFF + (s * PQ12_CENTROIDS + c[s]) * 4);
+                    score[jb] += sum;
+                }
+            }
+        }
+
+        // ---------------- softmax of the chunk
+        float s4[4];
+        bool valid[4];
+        float mx = NEG_BIG;
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) {
+            const int kblk = 2 * vbc + 4 * wave + jb;
+            valid[jb] = kblk < 2 * vb1 && kblk * 64 + lane < N;
+            s4[jb] = valid[jb] ? score[jb] : NEG_BIG;
+            mx = fmaxf(mx, s4[jb]);
+        }
+        mx = wave_max(mx);
+        if (lane == 0)
+            wmax[wave] = mx;
+        __syncthreads();
+        const float m_new = fmaxf(m_run, wave_max(wmax[lane & 15]));
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_lane *= alpha;
+#pragma unroll
+        for (int g = 0; g < 8; ++g)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[g][j] *= alpha;
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) {
+            const float p = valid[jb] ? __builtin_amdgcn_exp2f(s4[jb] - m_new) : 0.f;
+            l_lane += p;
+            pw[(4 * wave + jb) * 64 + lane] = p;
+        }
+        m_run = m_new;
+
+        // ---------------- value passes: 8 groups of 4 subspaces
+        for (int g = 0; g < 8; ++g) {
+            __syncthreads();  // weights written (first group); table region free
+            {
+                const u32x4 *src = (const u32x4 *)(vcb + (int64_t)(4 * g) * PQ12_CENTROIDS * 4);
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    *(lds_u32x4 *)(lbase + TAB_OFF + (tid + k * (NW12 * 64)) * 16) = src[tid + k * (NW12 * 64)];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int jv = 0; jv < 2; ++jv) {
+                const int vblk = vbc + 2 * wave + jv;  // 128-token block of the head
+                if (vblk < vb1) {
+                    const uint32_t *src = (const uint32_t *)(v_head + (((int64_t)vblk * 8 + g) * 64 + lane) * 12);
+                    uint32_t c[8];
+                    unpack8(src[0], src[1], src[2], c);
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) {
+                        const float p = pw[(2 * wave + jv) * 128 + (lane >> 2) + 16 * k];
+                        const u32x2 cv = *(lds_u32x2 *)(lbase + TAB_OFF + ((lane & 3) * PQ12_CENTROIDS + c[k]) * 8);
+                        const uint32_t lo = cv.x, hi = cv.y;
+                        const __half2 h0 = *(const __half2 *)&lo, h1 = *(const __half2 *)&hi;
+                        acc[g][0] = fmaf(p, __low2float(h0), acc[g][0]);
+                        acc[g][1] = fmaf(p, __high2float(h0), acc[g][1]);
+                        acc[g][2] = fmaf(p, __low2float(h1), acc[g][2]);
+                        acc[g][3] = fmaf(p, __high2float(h1), acc[g][3]);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---------------- sum the 16 token streams (lanes with equal lane % 4), then lane l owns dims 2l, 2l + 1
+    lds_f32 *part = (lds_f32 *)(lbase + PART12_OFF) + wave * PQ_PART_STRIDE;
+#pragma unroll
+    for (int g = 0; g < 8; ++g)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float v = acc[g][j];
+            v += __shfl_xor(v, 4);
+            v += __shfl_xor(v, 8);
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            if (lane < 4)
+                part[4 + (4 * g + lane) * 4 + j] = v;
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    float o0 = part[4 + 2 * lane], o1 = part[5 + 2 * lane];
+    __syncthreads();  // every wavefront has left the chunk loop: the query in LDS is still needed, the rest is free
+
+    // ---------------- recent full-precision rows of this split (Eq. 7, second term), per wavefront
+    {
+        const float q0 = qs[2 * lane], q1 = qs[2 * lane + 1];
+        const int64_t rbase = ((int64_t)b * a.Hkv + hkv) * a.max_recent;
+        for (int r = r0 + wave; r < r1; r += NW12) {
+            const __half2 kk = *((const __half2 *)((const __half *)a.recent_k + (rbase + r) * PQ_HEAD_DIM) + lane);
+            const __half2 vv = *((const __half2 *)((const __half *)a.recent_v + (rbase + r) * PQ_HEAD_DIM) + lane);
+            const float s = wave_sum(fmaf(q0, __low2float(kk), q1 * __high2float(kk)));
+            const float m_new = fmaxf(m_run, s);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            const float p = __builtin_amdgcn_exp2f(s - m_new);
+            l_lane = fmaf(l_lane, alpha, lane == 0 ? p : 0.f);
+            o0 = fmaf(o0, alpha, p * __low2float(vv));
+            o1 = fmaf(o1, alpha, p * __high2float(vv));
+            m_run = m_new;
+        }
+    }
+
+    // ---------------- merge the wavefronts, publish the split, merge the splits (as in the 8-bit kernel)
+    {
+        const float l_w = wave_sum(l_lane);
+        if (lane == 0) {
+            part[0] = m_run;
+            part[1] = l_w;
+        }
+        part[4 + 2 * lane] = o0;
+        part[5 + 2 * lane] = o1;
+    }
+    __syncthreads();
+    if (wave != 0)
+        return;
+    float *gpart = a.partials + ((int64_t)bh * S + split) * PQ_PART_STRIDE;
+    float *orow = a.out + (int64_t)bh * PQ_HEAD_DIM;
+    const lds_f32 *parts = (const lds_f32 *)(lbase + PART12_OFF);
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int w = 0; w < NW12; ++w)
+        mx = fmaxf(mx, parts[w * PQ_PART_STRIDE]);
+    float l = 0.f;
+    o0 = o1 = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW12; ++w) {
+        const float f = __builtin_amdgcn_exp2f(parts[w * PQ_PART_STRIDE] - mx);
+        o0 = fmaf(parts[w * PQ_PART_STRIDE + 4 + 2 * lane], f, o0);
+        o1 = fmaf(parts[w * PQ_PART_STRIDE + 5 + 2 * lane], f, o1);
+        l = fmaf(parts[w * PQ_PART_STRIDE + 1], f, l);
+    }
+    if (S == 1) {
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        *(float2 *)(orow + 2 * lane) = make_float2(o0 * inv, o1 * inv);
+        return;
+    }
+    // device-scope stores, complete before the ticket; device-scope loads after it (see the 8-bit kernel)
+    publish(gpart + 4 + 2 * lane, o0, o1);
+    if (lane == 0)
+        publish(gpart, mx, l);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    unsigned int ticket = 0;
+    if (lane == 0)
+        ticket = __hip_atomic_fetch_add(a.tickets + bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    ticket = __builtin_amdgcn_readfirstlane(ticket);
+    if (ticket != (unsigned int)(S - 1))
+        return;
+    const float *ps = a.partials + (int64_t)bh * S * PQ_PART_STRIDE;
+    const float2 ml = lane < S ? fetch(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
+    mx = wave_max(ml.x);
+    const float f_lane = __builtin_amdgcn_exp2f(ml.x - mx);
+    l = wave_sum(ml.y * f_lane);
+    o0 = o1 = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const float2 o = fetch(ps + s * PQ_PART_STRIDE + 4 + 2 * lane);
+        const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), s & 63));
+        o0 = fmaf(o.x, f, o0);
+        o1 = fmaf(o.y, f, o1);
+    }
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    *(float2 *)(orow + 2 * lane) = make_float2(o0 * inv, o1 * inv);
+    if (lane == 0)
+        a.tickets[bh] = 0u;
+}
+
+}  // namespace
+
+hipError_t pq12_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
+{
+    (void)ctx;
+    const int grid = a.B * a.Hq * a.S;
+    hipLaunchKernelGGL(pq12_decode_kernel, dim3(grid), dim3(NW12 * 64), 0, s, a);
+    return hipGetLastError();
+}

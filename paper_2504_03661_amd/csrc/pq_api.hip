@@ -40,7 +40,10 @@ int validate(const pq_attn_config *c)
         return PQ_ERR_SHAPE;
     if (c->dtype != PQ_F16 && c->dtype != PQ_F32)
         return PQ_ERR_SHAPE;
-    if (c->n_centroids != 256 || c->head_dim != PQ_HEAD_DIM || (c->n_subspaces != 64 && c->n_subspaces != 32))
+    if (c->head_dim != PQ_HEAD_DIM || (c->n_subspaces != 64 && c->n_subspaces != 32))
+        return PQ_ERR_UNSUPPORTED;
+    // 8-bit codes, or the 12-bit setting: 32 subspaces x 4096 centroids, fp16
+    if (c->n_centroids != 256 && !(c->n_centroids == PQ12_CENTROIDS && c->n_subspaces == PQ12_M && c->dtype == PQ_F16))
         return PQ_ERR_UNSUPPORTED;
     if (c->n_splits > PQ_MAX_SPLITS || c->max_context > PQ_MAX_TOKENS || c->max_recent > PQ_MAX_TOKENS)
         return PQ_ERR_UNSUPPORTED;
@@ -49,7 +52,14 @@ int validate(const pq_attn_config *c)
     return PQ_OK;
 }
 
-int64_t padded_capacity(const pq_attn_config *c) { return ((int64_t)c->max_context + 63) / 64 * 64; }
+int64_t padded_capacity(const pq_attn_config *c)
+{
+    const int64_t block = pq_config_is_12bit(c) ? 128 : 64;
+    return ((int64_t)c->max_context + block - 1) / block * block;
+}
+
+// bytes of one token in one code tensor
+int64_t token_bytes(const pq_attn_config *c) { return pq_config_is_12bit(c) ? PQ12_TOKEN_BYTES : c->n_subspaces; }
 
 // Splits per (sequence, head): a workgroup's tables take most of a compute unit's LDS, so one
 // workgroup is resident per CU at a time and the grid should fill the chip exactly once —
@@ -63,7 +73,9 @@ int choose_splits(const pq_attn_config *c, int n_cu)
     const int64_t heads = (int64_t)c->batch * (pq_config_uses_grouped_kernel(c) ? c->n_kv_heads : c->n_q_heads);
     int64_t s = n_cu / heads;
     const int64_t blocks = padded_capacity(c) / 64;
-    const int64_t max_by_work = blocks / 16 > 0 ? blocks / 16 : 1;
+    // 8-bit kernels: at least a 64-token block per wavefront; 12-bit kernel: at least one 4096-token chunk
+    const int64_t per_split = pq_config_is_12bit(c) ? 64 : 16;
+    const int64_t max_by_work = blocks / per_split > 0 ? blocks / per_split : 1;
     if (s > max_by_work)
         s = max_by_work;
     if (s > PQ_MAX_SPLITS)
@@ -81,10 +93,18 @@ int ensure_codebooks(pq_attn_ctx *ctx, const void *k, const void *v, hipStream_t
         return PQ_ERR_NULL;
     if (!force && k == ctx->reg_k && v == ctx->reg_v)
         return PQ_OK;
-    if (pq_launch_pack_codebook(ctx, k, ctx->kcb_packed, s) != hipSuccess)
-        return PQ_ERR_HIP;
-    if (pq_launch_pack_codebook(ctx, v, ctx->vcb_packed, s) != hipSuccess)
-        return PQ_ERR_HIP;
+    if (pq_config_is_12bit(&ctx->cfg)) {
+        // the 12-bit kernels read the natural layout [Hkv][M][4096][ds]: the context keeps a plain copy
+        const size_t bytes = (size_t)ctx->cfg.n_kv_heads * PQ12_M * PQ12_CENTROIDS * 4 * sizeof(uint16_t);
+        if (hipMemcpyAsync(ctx->kcb_packed, k, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(ctx->vcb_packed, v, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess)
+            return PQ_ERR_HIP;
+    } else {
+        if (pq_launch_pack_codebook(ctx, k, ctx->kcb_packed, s) != hipSuccess)
+            return PQ_ERR_HIP;
+        if (pq_launch_pack_codebook(ctx, v, ctx->vcb_packed, s) != hipSuccess)
+            return PQ_ERR_HIP;
+    }
     ctx->reg_k = k;
     ctx->reg_v = v;
     return PQ_OK;
@@ -97,6 +117,8 @@ void free_ctx(pq_attn_ctx *ctx)
     if (ctx->partials) (void)hipFree(ctx->partials);
     if (ctx->tickets) (void)hipFree(ctx->tickets);
     if (ctx->dev_err) (void)hipFree(ctx->dev_err);
+    if (ctx->stage[0]) (void)hipFree(ctx->stage[0]);
+    if (ctx->stage[1]) (void)hipFree(ctx->stage[1]);
     delete ctx;
 }
 
@@ -111,7 +133,7 @@ int64_t pq_attn_codes_bytes(const pq_attn_config *cfg)
     const int rc = validate(cfg);
     if (rc != PQ_OK)
         return rc;
-    return (int64_t)cfg->batch * cfg->n_kv_heads * padded_capacity(cfg) * cfg->n_subspaces;
+    return (int64_t)cfg->batch * cfg->n_kv_heads * padded_capacity(cfg) * token_bytes(cfg);
 }
 
 int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
@@ -144,7 +166,7 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     ctx->k_skew = pq_config_uses_grouped_kernel(cfg) ? PQ_K_SKEW_QUAD : PQ_K_SKEW_LANE;
     ctx->n_splits = cfg->n_splits > 0 ? cfg->n_splits : choose_splits(cfg, prop.multiProcessorCount);
 
-    const size_t cb_bytes = (size_t)cfg->n_kv_heads * 256 * PQ_HEAD_DIM * ctx->elem_bytes;
+    const size_t cb_bytes = (size_t)cfg->n_kv_heads * cfg->n_centroids * PQ_HEAD_DIM * ctx->elem_bytes;
     const size_t n_bh = (size_t)cfg->batch * cfg->n_q_heads;
     const size_t part_bytes = n_bh * ctx->n_splits * PQ_PART_STRIDE * sizeof(float);
     bool ok = hipMalloc(&ctx->kcb_packed, cb_bytes) == hipSuccess;
@@ -236,8 +258,10 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
     a.S = ctx->n_splits;
     a.max_context = ctx->cfg.max_context;
     a.max_recent = ctx->cfg.max_recent;
-    a.head_stride = ctx->cap_padded * ctx->cfg.n_subspaces;
-    const hipError_t e = ctx->k_skew == PQ_K_SKEW_QUAD ? pq_launch_decode_grouped(ctx, a, s) : pq_launch_decode(ctx, a, s);
+    a.head_stride = ctx->cap_padded * token_bytes(&ctx->cfg);
+    const hipError_t e = pq_config_is_12bit(&ctx->cfg)   ? pq12_launch_decode(ctx, a, s)
+                         : ctx->k_skew == PQ_K_SKEW_QUAD ? pq_launch_decode_grouped(ctx, a, s)
+                                                         : pq_launch_decode(ctx, a, s);
     return e == hipSuccess ? PQ_OK : PQ_ERR_HIP;
 }
 
@@ -271,11 +295,33 @@ int pq_encode_append(pq_attn_ctx *ctx, const void *new_k, const void *new_v, int
     a.n_new = n_new;
     a.max_context = ctx->cfg.max_context;
     a.k_skew = ctx->k_skew;
-    a.head_stride = ctx->cap_padded * ctx->cfg.n_subspaces;
+    a.head_stride = ctx->cap_padded * token_bytes(&ctx->cfg);
+    if (pq_config_is_12bit(&ctx->cfg)) {
+        // codes are staged token-major (uint16) and packed by a second kernel; the staging buffers grow on demand
+        if (n_new > ctx->stage_tokens) {
+            const size_t bytes = (size_t)ctx->cfg.batch * ctx->cfg.n_kv_heads * n_new * PQ12_M * sizeof(uint16_t);
+            if (hipDeviceSynchronize() != hipSuccess)  // earlier appends may still read the old buffers
+                return PQ_ERR_HIP;
+            for (int w = 0; w < 2; ++w) {
+                if (ctx->stage[w]) (void)hipFree(ctx->stage[w]);
+                ctx->stage[w] = nullptr;
+            }
+            ctx->stage_tokens = 0;
+            if (hipMalloc((void **)&ctx->stage[0], bytes) != hipSuccess ||
+                hipMalloc((void **)&ctx->stage[1], bytes) != hipSuccess) {
+                (void)hipGetLastError();
+                return PQ_ERR_ALLOC;
+            }
+            ctx->stage_tokens = n_new;
+        }
+        a.codebook[0] = ctx->kcb_packed;  // the context's own copies (natural layout)
+        a.codebook[1] = ctx->vcb_packed;
+        return pq12_launch_encode_append(ctx, a, ctx_len, ctx->dev_err, s) == hipSuccess ? PQ_OK : PQ_ERR_HIP;
+    }
     return pq_launch_encode(ctx, a, ctx_len, ctx->dev_err, s) == hipSuccess ? PQ_OK : PQ_ERR_HIP;
 }
 
-static int pack_common(pq_attn_ctx *ctx, int32_t kind, const uint8_t *token_major, int32_t n_tokens, uint8_t *packed,
+static int pack_common(pq_attn_ctx *ctx, int32_t kind, const void *token_major, int32_t n_tokens, uint8_t *packed,
                        bool unpack, void *hip_stream)
 {
     if (ctx == nullptr || token_major == nullptr || packed == nullptr)
@@ -289,19 +335,20 @@ static int pack_common(pq_attn_ctx *ctx, int32_t kind, const uint8_t *token_majo
     device_guard guard(ctx->cfg.device);
     if (!guard.ok)
         return PQ_ERR_HIP;
-    return pq_launch_pack_codes(ctx, kind, token_major, n_tokens, packed, unpack, (hipStream_t)hip_stream) ==
-                   hipSuccess
-               ? PQ_OK
-               : PQ_ERR_HIP;
+    const hipError_t e =
+        pq_config_is_12bit(&ctx->cfg)
+            ? pq12_launch_pack_codes(ctx, kind, (const uint16_t *)token_major, n_tokens, packed, unpack, (hipStream_t)hip_stream)
+            : pq_launch_pack_codes(ctx, kind, (const uint8_t *)token_major, n_tokens, packed, unpack, (hipStream_t)hip_stream);
+    return e == hipSuccess ? PQ_OK : PQ_ERR_HIP;
 }
 
-int pq_pack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *token_major, int32_t n_tokens, uint8_t *packed,
+int pq_pack_codes(pq_attn_ctx *ctx, int32_t kind, const void *token_major, int32_t n_tokens, uint8_t *packed,
                   void *hip_stream)
 {
     return pack_common(ctx, kind, token_major, n_tokens, packed, false, hip_stream);
 }
 
-int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32_t n_tokens, uint8_t *token_major,
+int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32_t n_tokens, void *token_major,
                     void *hip_stream)
 {
     return pack_common(ctx, kind, token_major, n_tokens, const_cast<uint8_t *>(packed), true, hip_stream);
@@ -311,7 +358,7 @@ int64_t pq_kmeans_workspace_bytes(const pq_attn_ctx *ctx)
 {
     if (ctx == nullptr)
         return PQ_ERR_NULL;
-    if (ctx->cfg.dtype != PQ_F16)
+    if (ctx->cfg.dtype != PQ_F16 || pq_config_is_12bit(&ctx->cfg))
         return PQ_ERR_UNSUPPORTED;
     return pq_kmeans_accumulator_bytes(ctx);
 }
@@ -321,7 +368,7 @@ int pq_kmeans_fit(pq_attn_ctx *ctx, const void *samples, int32_t n_samples, void
 {
     if (ctx == nullptr || samples == nullptr || codebook == nullptr || workspace == nullptr)
         return PQ_ERR_NULL;
-    if (ctx->cfg.dtype != PQ_F16)
+    if (ctx->cfg.dtype != PQ_F16 || pq_config_is_12bit(&ctx->cfg))
         return PQ_ERR_UNSUPPORTED;
     if (n_samples < 1 || n_iters < 1 || ((uintptr_t)workspace & 7) != 0)
         return PQ_ERR_SHAPE;

@@ -115,6 +115,12 @@ void launch(const pq_encode_args &a, hipStream_t s)
 
 }  // namespace
 
+hipError_t pq_launch_bump_len(int32_t *ctx_len, int B, int n_new, int max_context, unsigned int *dev_err, hipStream_t s)
+{
+    hipLaunchKernelGGL(pq_bump_len_kernel, dim3((B + 255) / 256), dim3(256), 0, s, ctx_len, B, n_new, max_context, dev_err);
+    return hipGetLastError();
+}
+
 hipError_t pq_launch_encode(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len, unsigned int *dev_err,
                             hipStream_t s)
 {
@@ -128,7 +134,5 @@ hipError_t pq_launch_encode(const pq_attn_ctx *ctx, const pq_encode_args &a, int
     if (e != hipSuccess)
         return e;
     // lengths move only after every encode workgroup has read the old ones (stream order)
-    hipLaunchKernelGGL(pq_bump_len_kernel, dim3((a.B + 255) / 256), dim3(256), 0, s, ctx_len, a.B, a.n_new,
-                       a.max_context, dev_err);
-    return hipGetLastError();
+    return pq_launch_bump_len(ctx_len, a.B, a.n_new, a.max_context, dev_err, s);
 }

@@ -42,6 +42,40 @@ __host__ __device__ inline int64_t pq_v_code_offset(int64_t t, int i, int M)
     return (t >> 4) * (16 * (int64_t)M) + (int64_t)i * 16 + (t & 15);
 }
 
+// ---------------------------------------------------------------------------------
+// 12-bit codes (M = 32 subspaces of 4 dims, 4096 centroids): 48 bytes per token and tensor.
+// Every unit below is 12 bytes = eight 12-bit codes, code s of a unit in bits 12 s .. 12 s + 11
+// (little-endian), and a wavefront loads 64 consecutive units (768 bytes) with one 12-byte load
+// per lane.  The decode kernel walks the subspaces in groups (its tables for all 32 do not fit
+// in LDS), so both layouts are group-major inside a block of tokens.
+//
+// K codes: blocks of 64 tokens x 4 groups of 8 subspaces; unit (block, group, lane = token % 64)
+// holds that token's codes of subspaces 8 g .. 8 g + 7 in order.
+//
+// V codes: blocks of 128 tokens x 8 groups of 4 subspaces; unit (block, group, lane) with
+// lane = 4 * (token % 16) + (subspace % 4) holds the codes of that subspace for the 8 tokens
+// token % 16 + 16 k of the block, k = 0 .. 7 (the value pass gives a lane one subspace and every
+// 16th token).
+// The token capacity of a tensor is rounded up to 128 tokens.
+// ---------------------------------------------------------------------------------
+#define PQ12_M 32
+#define PQ12_CENTROIDS 4096
+#define PQ12_TOKEN_BYTES 48
+
+// byte offset of the 12-byte unit and index (0..7) of the code inside it
+__host__ __device__ inline int64_t pq12_k_unit(int64_t t, int i, int *slot)
+{
+    *slot = i & 7;
+    return (((t >> 6) * 4 + (i >> 3)) * 64 + (t & 63)) * 12;
+}
+
+__host__ __device__ inline int64_t pq12_v_unit(int64_t t, int i, int *slot)
+{
+    const int r = (int)(t & 127);
+    *slot = r >> 4;
+    return (((t >> 7) * 8 + (i >> 2)) * 64 + (r & 15) * 4 + (i & 3)) * 12;
+}
+
 // Floats per split partial: [0] running maximum (log2 domain), [1] sum of weights,
 // [2..3] unused, [4..4+d) unnormalised output.
 #define PQ_PART_STRIDE 132
@@ -65,6 +99,9 @@ struct pq_attn_ctx {
     float *partials;      // [B*Hq][n_splits][PQ_PART_STRIDE]
     unsigned int *tickets;  // [B*Hq], zero between calls
     unsigned int *dev_err;  // sticky error word
+    // 12-bit contexts: token-major uint16 staging of an append's codes, grown on demand
+    uint16_t *stage[2];
+    int64_t stage_tokens;   // tokens per (sequence, KV head) the staging buffers hold
 };
 
 struct pq_decode_args {
@@ -100,6 +137,8 @@ hipError_t pq_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args
 bool pq_config_uses_grouped_kernel(const pq_attn_config *cfg);
 hipError_t pq_launch_encode(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len, unsigned int *dev_err,
                             hipStream_t s);
+// lengths += n_new, saturating at max_context (sets the overflow flag)
+hipError_t pq_launch_bump_len(int32_t *ctx_len, int B, int n_new, int max_context, unsigned int *dev_err, hipStream_t s);
 hipError_t pq_launch_pack_codebook(const pq_attn_ctx *ctx, const void *src, void *dst, hipStream_t s);
 hipError_t pq_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint8_t *token_major, int n_tokens,
                                 uint8_t *packed, bool unpack, hipStream_t s);
@@ -109,3 +148,12 @@ hipError_t pq_launch_stream_read(const void *src, int64_t bytes, uint32_t *sink,
 int64_t pq_kmeans_accumulator_bytes(const pq_attn_ctx *ctx);
 hipError_t pq_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n_samples, void *codebook, int n_iters,
                             void *workspace, hipStream_t s);
+
+// 12-bit contexts (n_centroids = 4096): decode, encode into the token-major staging buffers followed by the
+// packing of the staged codes behind the current lengths, and the layout conversions of whole tensors
+bool pq_config_is_12bit(const pq_attn_config *cfg);
+hipError_t pq12_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
+hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len,
+                                     unsigned int *dev_err, hipStream_t s);
+hipError_t pq12_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint16_t *token_major, int n_tokens,
+                                  uint8_t *packed, bool unpack, hipStream_t s);

@@ -18,7 +18,10 @@ from . import binding as B
 def _dev(a: Optional[np.ndarray], device) -> Optional[torch.Tensor]:
     if a is None:
         return None
-    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:          # 12-bit codes: the same bits as int16, a dtype every torch build moves
+        a = a.view(np.int16)
+    return torch.from_numpy(a).to(device)
 
 
 class PQSession:
@@ -36,7 +39,8 @@ class PQSession:
         self.dtype = dtype
         rk = data.get("recent_k")
         self.cfg = B.PQAttnConfig(
-            batch=Bn, n_q_heads=n_q_heads, n_kv_heads=Hkv, head_dim=d, n_subspaces=M, n_centroids=256,
+            batch=Bn, n_q_heads=n_q_heads, n_kv_heads=Hkv, head_dim=d, n_subspaces=M,
+            n_centroids=int(data["k_codebook"].shape[2]),
             max_context=int(max_context if max_context is not None else n_tok),
             max_recent=0 if rk is None else int(rk.shape[2]),
             dtype=B.PQ_F16 if dtype == "f16" else B.PQ_F32, device=device, n_splits=n_splits)
@@ -121,11 +125,14 @@ class PQSession:
                            self.k_codes[copy], self.v_codes[copy], self.ctx_len)
 
     def unpack(self, kind: int, n_tokens: int, copy: int = 0) -> np.ndarray:
-        tm = torch.empty((self.B, self.Hkv, n_tokens, self.M), dtype=torch.uint8, device=self.device)
+        wide = self.cfg.n_centroids > 256                     # 12-bit codes travel token-major as 16-bit words
+        tm = torch.empty((self.B, self.Hkv, n_tokens, self.M), dtype=torch.int16 if wide else torch.uint8,
+                         device=self.device)
         src = self.k_codes[copy] if kind == B.PQ_CODES_K else self.v_codes[copy]
         B.pq_unpack_codes(self.ctx, kind, src, n_tokens, tm)
         torch.cuda.synchronize(self.device)
-        return tm.cpu().numpy()
+        out = tm.cpu().numpy()
+        return out.view(np.uint16) if wide else out
 
     def device_error(self) -> int:
         return B.pq_attn_device_error(self.ctx)

@@ -49,7 +49,10 @@ def good(**kw):
     ({"max_recent": -1}, -2),
     ({"dtype": 7}, -2),
     ({"reserved": 1}, -2),
-    ({"n_centroids": 4096}, -3),                       # 12-bit codes: no kernel
+    ({"n_centroids": 4096, "n_subspaces": 32}, 0),     # the 12-bit setting
+    ({"n_centroids": 4096}, -3),                       # 12-bit codes need M = 32 ...
+    ({"n_centroids": 4096, "n_subspaces": 32, "dtype": P.PQ_F32}, -3),   # ... and fp16
+    ({"n_centroids": 1024, "n_subspaces": 32}, -3),
     ({"n_subspaces": 16}, -3),
     ({"head_dim": 64, "n_subspaces": 32}, -3),
     ({"n_splits": 1000}, -3),
@@ -62,6 +65,8 @@ def test_codes_bytes_rounds_capacity_to_64_token_blocks():
     assert P.pq_attn_codes_bytes(good()) == 32 * 32768 * 64
     assert P.pq_attn_codes_bytes(good(max_context=1000)) == 32 * 1024 * 64
     assert P.pq_attn_codes_bytes(good(max_context=65, n_subspaces=32, batch=3)) == 3 * 32 * 128 * 32
+    # 12-bit codes: 48 bytes per token, capacity in 128-token blocks
+    assert P.pq_attn_codes_bytes(good(max_context=130, n_subspaces=32, n_centroids=4096, batch=2)) == 2 * 32 * 256 * 48
     with pytest.raises(P.PQAttnError):
         P.pq_attn_codes_bytes(good(batch=-1))
 

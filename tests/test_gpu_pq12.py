@@ -1,0 +1,140 @@
+"""GPU parity of the 12-bit setting (M = 32 subspaces, 4096 centroids, 48 bytes per token and tensor):
+layouts bit-exact, decode within max-abs 2e-3 and relative L2 1e-3 of the oracle, encode bit-exact."""
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pq_oracle as O
+from paper_2504_03661_amd import PQ_CODES_K, PQ_CODES_V, binding as B
+from paper_2504_03661_amd.harness import PQSession
+from synth import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2 = 2e-3, 1e-3
+
+
+def check(got, ref, what=""):
+    got = np.asarray(got, dtype=np.float64)
+    assert np.isfinite(got).all(), what
+    err = np.abs(got - ref).max()
+    den = np.linalg.norm(ref)
+    rel = np.linalg.norm(got - ref) / den if den > 0 else np.linalg.norm(got - ref)
+    assert err <= MAX_ABS and rel <= REL_L2, f"{what}: max_abs={err:.3e} rel_l2={rel:.3e}"
+
+
+def workload(name, B_, Hq, Hkv, lens, rcap=0, **kw):
+    return W.Workload(name, B_, Hq, Hkv, 128, 32, max(max(lens), 1) + 5, "f16", recent_cap=rcap, recent_uniform=rcap > 0,
+                      seed=zlib.crc32(name.encode()) % 10000, ctx_lens=tuple(lens), n_centroids=4096, **kw)
+
+
+def oracle_out(w, data, k_codes=None, v_codes=None, ctx_len=None):
+    return O.decode(data["q"], data["k_codes"] if k_codes is None else k_codes,
+                    data["v_codes"] if v_codes is None else v_codes,
+                    data["ctx_len"] if ctx_len is None else ctx_len, data["k_codebook"], data["v_codebook"],
+                    data["recent_k"], data["recent_v"], data["recent_len"], scale=W.attention_scale(w))
+
+
+def unit_bytes(codes8):
+    """Eight 12-bit codes -> the 12 bytes of a unit (code s in bits 12 s .. 12 s + 11, little-endian)."""
+    v = 0
+    for s, c in enumerate(codes8):
+        v |= int(c) << (12 * s)
+    return [(v >> (8 * k)) & 255 for k in range(12)]
+
+
+def test_device_layouts_bit_for_bit_and_roundtrip():
+    w = workload("layout12", 2, 2, 2, (300, 129))
+    data = W.generate(w)
+    n = data["k_codes"].shape[2]
+    with PQSession(data, 2, "f16") as s:
+        assert s.codes_bytes == 2 * 2 * 384 * 48          # capacity 305 -> 384 tokens (128-token blocks)
+        pk = s.k_codes[0].cpu().numpy().reshape(2, 2, -1)
+        pv = s.v_codes[0].cpu().numpy().reshape(2, 2, -1)
+        rng = np.random.default_rng(0)
+        for _ in range(60):
+            b, h, t = rng.integers(0, 2), rng.integers(0, 2), int(rng.integers(0, n))
+            g = int(rng.integers(0, 4))                    # K unit: token t, subspaces 8 g .. 8 g + 7
+            off = (((t >> 6) * 4 + g) * 64 + (t & 63)) * 12
+            assert list(pk[b, h, off:off + 12]) == unit_bytes(data["k_codes"][b, h, t, 8 * g:8 * g + 8])
+            i = int(rng.integers(0, 32))                   # V unit: subspace i, tokens t0 + 16 k of t's 128-block
+            t0 = (t >> 7) * 128 + (t & 15)
+            toks = [t0 + 16 * k for k in range(8)]
+            off = (((t >> 7) * 8 + (i >> 2)) * 64 + (t & 15) * 4 + (i & 3)) * 12
+            got = pv[b, h, off:off + 12]
+            want = unit_bytes([data["v_codes"][b, h, tt, i] if tt < n else 0 for tt in toks])
+            # slots of tokens beyond the packed range hold whatever the buffer held (zeros here)
+            assert list(got) == want
+        assert (s.unpack(PQ_CODES_K, n) == data["k_codes"]).all()
+        assert (s.unpack(PQ_CODES_V, n) == data["v_codes"]).all()
+
+
+CASES = [
+    ("one_chunk", 1, 2, 2, (3000,), 6, 0),
+    ("ragged_two_chunks", 2, 2, 2, (5000, 4097), 9, 1),
+    ("splits_3", 1, 3, 3, (13000,), 5, 3),
+    ("gqa2_splits_2", 2, 4, 2, (9000, 130), 4, 2),
+    ("edges", 6, 1, 1, (0, 1, 127, 128, 129, 0), 8, 2),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_decode_small(case):
+    name, B_, Hq, Hkv, lens, rcap, splits = case
+    w = workload(name, B_, Hq, Hkv, lens, rcap)
+    data = W.generate(w)
+    if name == "edges":
+        data["recent_len"][:] = [0, 0, 3, 0, 7, 5]        # sequence 0: nothing at all; sequence 5: window only
+        fill = np.random.default_rng(7)
+        data["recent_k"][:] = fill.standard_normal(data["recent_k"].shape).astype(np.float16)
+        data["recent_v"][:] = fill.standard_normal(data["recent_v"].shape).astype(np.float16)
+        for b in range(B_):
+            data["recent_k"][b, :, data["recent_len"][b]:] = np.nan
+            data["recent_v"][b, :, data["recent_len"][b]:] = np.nan
+    with PQSession(data, Hq, "f16", n_splits=splits) as s:
+        out = s.decode(W.attention_scale(w))
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+    check(got, oracle_out(w, data), name)
+    if name == "edges":
+        assert (got[0] == 0).all()
+
+
+@pytest.mark.parametrize("n_old,n_new", [(0, 70), (100, 64), (130, 300), (255, 1)])
+def test_encode_append_bit_exact_then_decode(n_old, n_new):
+    w = W.Workload("enc12", 2, 2, 2, 128, 32, n_old + n_new, "f16", n_new=n_new, seed=4000 + n_old, n_centroids=4096)
+    data = W.generate(w)
+    for cb in (data["k_codebook"], data["v_codebook"]):    # duplicated centroids: ties must go to the lowest index
+        cb[:, :, 4000:4010] = cb[:, :, 5:15]
+    want_k = O.encode(data["new_k"], data["k_codebook"])
+    want_v = O.encode(data["new_v"], data["v_codebook"])
+    assert want_k.dtype == np.uint16
+    with PQSession(data, 2, "f16") as s:
+        s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())
+        torch.cuda.synchronize()
+        assert (s.ctx_len.cpu().numpy() == n_old + n_new).all()
+        got_k = s.unpack(PQ_CODES_K, n_old + n_new)
+        got_v = s.unpack(PQ_CODES_V, n_old + n_new)
+        assert (got_k[:, :, n_old:] == want_k).all() and (got_v[:, :, n_old:] == want_v).all()
+        assert (got_k[:, :, :n_old] == data["k_codes"][:, :, :n_old]).all()      # older tokens untouched
+        assert (got_v[:, :, :n_old] == data["v_codes"][:, :, :n_old]).all()
+        out = s.decode(W.attention_scale(w))
+        torch.cuda.synchronize()
+        full_k = np.concatenate([data["k_codes"][:, :, :n_old], want_k], axis=2)
+        full_v = np.concatenate([data["v_codes"][:, :, :n_old], want_v], axis=2)
+        ref = oracle_out(w, data, full_k, full_v, np.full((2,), n_old + n_new, dtype=np.int32))
+        check(out.cpu().numpy(), ref, "after append")
+
+
+def test_llama2_7b_layer_shape_at_32k():
+    """The metric's shape with 12-bit codes: 1 x 32 heads x 32K tokens, 128 recent rows."""
+    w = W.Workload("pq12_llama2_7b_32k", 1, 32, 32, 128, 32, 32768, "f16", recent_cap=128, recent_fixed=128,
+                   seed=W.BASE_SEED + 12, n_centroids=4096)
+    data = W.generate(w)
+    with PQSession(data, 32, "f16") as s:
+        out = s.decode(W.attention_scale(w))
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+    check(got, oracle_out(w, data), "12-bit 32K")
