@@ -4,6 +4,7 @@
     python -m paper_2504_03661_amd.bench_extra prefill   # bulk encode of a 32K-token prompt, all heads, K and V
     python -m paper_2504_03661_amd.bench_extra async     # encode on a second stream while decode runs
     python -m paper_2504_03661_amd.bench_extra train     # offline codebook training (k-means), 64K samples x 32 heads
+    python -m paper_2504_03661_amd.bench_extra pq12      # 12-bit codes: decode at 1 x 32 heads x 32K and 8 x 32 x 32K, 64-token append
 
 prefill: the nearest-centroid encode at prompt shape (Section III-A, "Online Prefill with KV Cache
 Quantization"): vectors per second against the fp64 vector-ALU roofline (2 ds + 3 operations per
@@ -16,6 +17,10 @@ two kernels touch disjoint data; the caller publishes the new lengths between st
 train: Lloyd iterations of the per-subspace k-means (Section III-A, "Offline PQ Codebook Training") on 65 536
 sampled vectors per head, 32 heads, M = 64: time per iteration against the same fp64 vector-ALU roofline (the
 assignment step is the encode's scan), with the oracle timed on a small sample beside it.
+
+pq12: the 12-bit setting (M = 32, 4096 centroids, 48 bytes per token and tensor; Section IV-A).  Decode
+against HBM: algorithmic bytes = codes + recent rows + both codebooks once per KV head (2 MiB per head: at 32K
+tokens they are 40 % of the bytes) + q / out.
 Each mode prints one JSON line.
 """
 import json
@@ -165,6 +170,54 @@ def train():
                                        "sub_vectors_per_s": round(2 * M * 4096 / cpu_s, 1)}}))
 
 
+def pq12():
+    import numpy as np
+    import torch
+    from paper_2504_03661_amd.harness import PQSession
+    from synth import workloads as W
+
+    res = {"mode": "pq12"}
+    for name, Bn in (("1x32x32k", 1), ("8x32x32k", 8)):
+        w = W.Workload("pq12_" + name, Bn, 32, 32, 128, 32, 32768, "f16", recent_cap=128, recent_fixed=128,
+                       seed=W.BASE_SEED + 12, n_centroids=4096)
+        data = W.generate(w)
+        one_copy = 2 * Bn * 32 * 32768 * 48
+        copies = max(2, min(8, -(-(1 << 30) // one_copy)))
+        with PQSession(data, 32, "f16", code_copies=copies) as s:
+            dec = [s.prepared_decode(W.attention_scale(w), copy=c) for c in range(copies)]
+            it = [0]
+
+            def step():
+                dec[it[0] % copies]()
+                it[0] += 1
+            ms = _span_ms(step, 100, warmup=10)
+            n_splits = s.n_splits
+        codes = Bn * 32 * 32768 * 96
+        total = codes + Bn * 32 * 128 * 128 * 2 * 2 + 32 * 2 * 32 * 4096 * 4 * 2 + Bn * 32 * 128 * 6
+        res[name] = {"decode_ms": round(ms, 4), "n_splits": n_splits, "ctx_tokens_per_s": round(Bn * (32768 + 128) / (ms * 1e-3), 1),
+                     "roofline": {"bound": "hbm", "achieved": round(total / (ms * 1e-3) / 1e9, 1), "peak": 8000.0,
+                                  "unit": "GB/s", "frac": round(total / (ms * 1e-3) / 1e9 / 8000.0, 4),
+                                  "algorithmic_bytes": total, "code_bytes": codes}}
+    # append of 64 tokens per head, 16 sequences x 32 heads (the shape of the 8-bit encode workload)
+    w = W.Workload("pq12_append", 16, 32, 32, 128, 32, 4096, "f16", n_new=64, seed=W.BASE_SEED + 13, n_centroids=4096)
+    data = W.generate(w)
+    with PQSession(data, 32, "f16") as s:
+        nk, nv = torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda()
+        base = s.ctx_len.clone()
+        app = s.prepared_append(nk, nv)
+
+        def step2():
+            s.ctx_len.copy_(base)
+            app()
+        ms = _span_ms(step2, 20, warmup=3)
+    ops = 2 * 16 * 32 * 64 * 32 * 4096 * 11
+    res["append_16x32x64"] = {"ms": round(ms, 4), "vectors_per_s": round(2 * 16 * 32 * 64 / (ms * 1e-3), 1),
+                              "alu": {"bound": "alu", "achieved": round(ops / (ms * 1e-3) / 1e12, 2),
+                                      "peak": round(ALU_LANE_OPS_PER_S / 1e12, 1), "unit": "T fp64 vector operations/s",
+                                      "frac": round(ops / (ms * 1e-3) / ALU_LANE_OPS_PER_S, 4)}}
+    print(json.dumps(res))
+
+
 if __name__ == "__main__":
     mode = sys.argv[1] if len(sys.argv) > 1 else ""
     if mode == "prefill":
@@ -173,6 +226,8 @@ if __name__ == "__main__":
         async_encode()
     elif mode == "train":
         train()
+    elif mode == "pq12":
+        pq12()
     else:
         print(__doc__)
         sys.exit(2)

@@ -39,30 +39,38 @@ __device__ inline void unpack8(const uint32_t (&w)[3], uint32_t (&c)[8])
     c[7] = w[2] >> 20;
 }
 
+// One workgroup = (K or V, KV head, subspace) x 4 work items, one per wavefront; a work item is a 64-token
+// chunk of one sequence (the sequences of a batch share the head's codebook, so short appends of many
+// sequences still fill the workgroup).
 __global__ __launch_bounds__(E12_WAVES * 64) void pq12_encode_kernel(const __half *x0, const __half *x1,
                                                                     const __half *cb0, const __half *cb1,
-                                                                    uint16_t *out0, uint16_t *out1, int Hkv, int n_new)
+                                                                    uint16_t *out0, uint16_t *out1, int B, int Hkv,
+                                                                    int n_new, int groups_per_head)
 {
 #pragma clang fp contract(off)
     __shared__ double tile[E12_TILE * 4];
 
     const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
     const int which = blockIdx.z;  // 0: keys, 1: values
     const int i = blockIdx.y;      // subspace
-    const int n_chunks = (n_new + E12_WAVES * 64 - 1) / (E12_WAVES * 64);
-    const int chunk = blockIdx.x % n_chunks;
-    const int head = blockIdx.x / n_chunks;  // b * Hkv + hkv
-    const int hkv = head % Hkv;
+    const int n_chunks = (n_new + 63) >> 6;
+    const int hkv = blockIdx.x / groups_per_head;
+    const int item = (blockIdx.x - hkv * groups_per_head) * E12_WAVES + wave;  // (sequence, chunk) of this wavefront
+    const int b = item / n_chunks;
+    const int chunk = item - b * n_chunks;
+    const int64_t head = (int64_t)b * Hkv + hkv;
     const __half *x = which ? x1 : x0;
     const __half *cb = (which ? cb1 : cb0) + ((int64_t)hkv * PQ12_M + i) * PQ12_CENTROIDS * 4;
     uint16_t *out = which ? out1 : out0;
 
-    const int tok = chunk * (E12_WAVES * 64) + tid;
-    const bool live = tok < n_new;
+    const int tok = chunk * 64 + lane;
+    const bool live = b < B && tok < n_new;
     double xv[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-        xv[j] = live ? (double)__half2float(x[((int64_t)head * n_new + tok) * PQ_HEAD_DIM + i * 4 + j]) : 0.0;
+        xv[j] = live ? (double)__half2float(x[(head * n_new + tok) * PQ_HEAD_DIM + i * 4 + j]) : 0.0;
 
     int best = 0;
     double best_dist = __builtin_huge_val();
@@ -83,7 +91,7 @@ __global__ __launch_bounds__(E12_WAVES * 64) void pq12_encode_kernel(const __hal
         }
     }
     if (live)
-        out[((int64_t)head * n_new + tok) * PQ12_M + i] = (uint16_t)best;
+        out[(head * n_new + tok) * PQ12_M + i] = (uint16_t)best;
 }
 
 // K units: one thread per (head, token j of the source, group of 8 subspaces)
@@ -213,11 +221,12 @@ hipError_t pq12_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint16
 hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len,
                                      unsigned int *dev_err, hipStream_t s)
 {
-    const int n_chunks = (a.n_new + E12_WAVES * 64 - 1) / (E12_WAVES * 64);
-    const dim3 grid((unsigned)(a.B * a.Hkv * n_chunks), PQ12_M, 2);
+    const int n_chunks = (a.n_new + 63) >> 6;
+    const int groups_per_head = (a.B * n_chunks + E12_WAVES - 1) / E12_WAVES;
+    const dim3 grid((unsigned)(a.Hkv * groups_per_head), PQ12_M, 2);
     hipLaunchKernelGGL(pq12_encode_kernel, grid, dim3(E12_WAVES * 64), 0, s, (const __half *)a.x[0],
                        (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
-                       ctx->stage[0], ctx->stage[1], a.Hkv, a.n_new);
+                       ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return e;

@@ -4,23 +4,26 @@
 // Same result as the 8-bit kernels (Eq. 7 = Eq. 6: tables q^i . (C_K^i)^T sampled by the key codes, one
 // softmax shared with the full-precision rows, values aggregated through C_V by the value codes), but
 // the tables no longer fit: 32 x 4096 fp32 table entries are 512 KiB, the fp16 value codebook 1 MiB, the
-// LDS of a compute unit 160 KiB.  So a workgroup takes its context split in chunks of 4096 tokens and
-// walks the SUBSPACES in groups, with one 128 KiB table region in LDS that is refilled per group:
+// LDS of a compute unit 160 KiB.  So a workgroup walks the SUBSPACES in groups, with one 128 KiB table
+// region in LDS that is refilled per group, and keeps what must survive from group to group — the
+// partial scores of its tokens — in registers: a wavefront owns up to 16 blocks of 128 tokens (32
+// scores per lane), a workgroup up to 32K tokens per round.
 //
 //   score passes   4 groups of 8 subspaces: build the group's table [8][4096] fp32 from the key codebook
-//                  (L2) and the query, then every wavefront adds, for its 4 blocks of 64 tokens
-//                  (lane = token, partial scores in registers), the 8 sampled entries per token;
-//   softmax        chunk maximum over the workgroup, running maximum / rescale across chunks, the
-//                  chunk's weights to LDS (16 KiB);
+//                  (L2) and the query, then every wavefront adds, for each of its blocks (lane = token),
+//                  the 8 sampled entries per token to that token's score register;
+//   softmax        all scores of the round are known: maximum over the workgroup, running maximum /
+//                  rescale only between rounds, weights replace the scores in their registers;
 //   value passes   8 groups of 4 subspaces: copy the group's slice of the value codebook (128 KiB) to
-//                  LDS, then lane = (subspace of the group, one of 16 token streams) gathers the 8-byte
-//                  centroid of its subspace for every 16th token and accumulates weight x centroid;
-//                  the 16 streams are summed once, at the end.
+//                  LDS; a wavefront then takes its blocks one by one: the block's 128 weights go to a
+//                  line of LDS that only this wavefront uses, and lane = (subspace of the group, one of
+//                  16 token streams) gathers the 8-byte centroid of its subspace for every 16th token and
+//                  accumulates weight x centroid; the 16 streams are summed once, at the end.
 // The code tensors are group-major (pq_internal.h) so that every pass streams exactly its own bytes:
-// each code byte still comes from HBM once.  What is new against the 8-bit kernels is table traffic:
-// 2 MiB of codebook per 4096-token chunk from L2 against 384 KiB of codes from HBM.
-// Gathers from a [subspace][code] table hit random banks (no layout can avoid that for random
-// codes); the recent rows, the split merge and the ticket protocol are those of the 8-bit kernel.
+// each code byte still comes from HBM once.  Table traffic is 2 MiB of codebook per workgroup and round
+// from L2.  Gathers from a [subspace][code] table hit random banks (no layout can avoid that for
+// random codes): LDS, not HBM, bounds this kernel.  The recent rows, the split merge and the ticket
+// protocol are those of the 8-bit kernel.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -30,10 +33,9 @@
 namespace {
 
 constexpr int NW12 = 16;
-constexpr int CHUNK_VB = 32;                          // 128-token blocks per chunk (4096 tokens)
 constexpr int TAB_OFF = 0;                            // 128 KiB: score table [8][4096] fp32 / value image [4][4096][4] fp16
-constexpr int P_OFF = 131072;                         // float [4096]: weights of the chunk
-constexpr int Q12_OFF = P_OFF + 16384;                // float [128]: query x scale x log2(e)
+constexpr int P_OFF = 131072;                         // float [16][128]: weights of the block a wavefront works on
+constexpr int Q12_OFF = P_OFF + NW12 * 512;           // float [128]: query x scale x log2(e)
 constexpr int WMAX_OFF = Q12_OFF + 512;               // float [16]
 constexpr int PART12_OFF = WMAX_OFF + 64;             // float [16][PQ_PART_STRIDE]
 constexpr int SMEM12_BYTES = PART12_OFF + NW12 * PQ_PART_STRIDE * 4;
@@ -60,8 +62,13 @@ __device__ inline float dot4(const f32x4 &q, uint32_t lo, uint32_t hi)
     return fmaf(q.w, __high2float(b), e);
 }
 
+// WAVE_VB: 128-token blocks per wavefront and round (two score registers per lane each); a workgroup
+// takes 16 WAVE_VB blocks per round.  16 (32K tokens per round) keeps the table refills rare on long
+// splits; short splits use a leaner instantiation.
+template <int WAVE_VB>
 __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_args a)
 {
+    constexpr int ROUND_VB = NW12 * WAVE_VB;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM12_BYTES];
     lds_u8 *lbase = (lds_u8 *)smem;
 
@@ -110,10 +117,33 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
         for (int j = 0; j < 4; ++j)
             acc[g][j] = 0.f;
 
-    for (int vbc = vb0; vbc < vb1; vbc += CHUNK_VB) {
+    const uint32_t *k_units = (const uint32_t *)k_head + lane * 3;
+    const uint32_t *v_units = (const uint32_t *)v_head + lane * 3;
+    lds_f32 *pline = pw + wave * 128;
+
+    for (int sb = vb0; sb < vb1; sb += ROUND_VB) {
+        // wavefront w owns blocks sb + w + 16 jj, jj < n_jj (128 tokens each: two score registers per lane)
+        const int left = vb1 - sb - wave;
+        const int n_jj = left <= 0 ? 0 : (left + NW12 - 1) / NW12 < WAVE_VB ? (left + NW12 - 1) / NW12 : WAVE_VB;
+        const int last_vb = vb1 - 1;  // loads beyond the wavefront's blocks re-read a valid block and are not used
+        float score[2 * WAVE_VB];
+#pragma unroll
+        for (int e = 0; e < 2 * WAVE_VB; ++e)
+            score[e] = 0.f;
+
         // ---------------- score passes: 4 groups of 8 subspaces
-        float score[4] = {0.f, 0.f, 0.f, 0.f};
         for (int g = 0; g < 4; ++g) {
+            // the first block's codes are requested before the table is built
+            uint32_t cur[6], nxt[6];
+            {
+                const int vb = sb + wave < last_vb ? sb + wave : last_vb;
+                const uint32_t *u = k_units + (((int64_t)(2 * vb) * 4 + g) * 64) * 3;
+#pragma unroll
+                for (int e = 0; e < 3; ++e) {
+                    cur[e] = u[e];
+                    cur[3 + e] = u[4 * 64 * 3 + e];  // the second 64-token block of the 128-token block
+                }
+            }
             __syncthreads();  // the table region is free (and, the first time, the query is in LDS)
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -130,32 +160,46 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
             }
             __syncthreads();
 #pragma unroll
-            for (int jb = 0; jb < 4; ++jb) {
-                const int kblk = 2 * vbc + 4 * wave + jb;  // 64-token block of the head
-                if (kblk < 2 * vb1) {
-                    const uint32_t *src = (const uint32_t *)(k_head + (((int64_t)kblk * 4 + g) * 64 + lane) * 12);
+            for (int jj = 0; jj < WAVE_VB; ++jj) {
+                if (jj >= n_jj)
+                    continue;  // wave-uniform; `continue`, not `break`: the loop must unroll (registers are indexed by jj)
+                {
+                    const int want = sb + wave + NW12 * (jj + 1);
+                    const int vb = want < last_vb ? want : last_vb;
+                    const uint32_t *u = k_units + (((int64_t)(2 * vb) * 4 + g) * 64) * 3;
+#pragma unroll
+                    for (int e = 0; e < 3; ++e) {
+                        nxt[e] = u[e];
+                        nxt[3 + e] = u[4 * 64 * 3 + e];
+                    }
+                }
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
                     uint32_t c[8];
-                    unpack8(src[0], src[1], src[2], c);
+                    unpack8(cur[3 * h], cur[3 * h + 1], cur[3 * h + 2], c);
                     float sum = 0.f;
 #pragma unroll
-                    for (int s = 0; s < 8; ++s)
-                        sum += *(lds_f32 *)(lbase + TAB_OFF + (s * PQ12_CENTROIDS + c[s]) * 4);
-                    score[jb] += sum;
+                    for (int s8 = 0; s8 < 8; ++s8)
+                        sum += *(lds_f32 *)(lbase + TAB_OFF + (s8 * PQ12_CENTROIDS + c[s8]) * 4);
+                    score[2 * jj + h] += sum;
                 }
+#pragma unroll
+                for (int e = 0; e < 6; ++e)
+                    cur[e] = nxt[e];
             }
         }
 
-        // ---------------- softmax of the chunk
-        float s4[4];
-        bool valid[4];
+        // ---------------- softmax of the round: the scores become weights
         float mx = NEG_BIG;
 #pragma unroll
-        for (int jb = 0; jb < 4; ++jb) {
-            const int kblk = 2 * vbc + 4 * wave + jb;
-            valid[jb] = kblk < 2 * vb1 && kblk * 64 + lane < N;
-            s4[jb] = valid[jb] ? score[jb] : NEG_BIG;
-            mx = fmaxf(mx, s4[jb]);
-        }
+        for (int jj = 0; jj < WAVE_VB; ++jj)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int tok = (sb + wave + NW12 * jj) * 128 + 64 * h + lane;
+                const bool valid = jj < n_jj && tok < N;
+                score[2 * jj + h] = valid ? score[2 * jj + h] : NEG_BIG;
+                mx = fmaxf(mx, score[2 * jj + h]);
+            }
         mx = wave_max(mx);
         if (lane == 0)
             wmax[wave] = mx;
@@ -169,16 +213,26 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
             for (int j = 0; j < 4; ++j)
                 acc[g][j] *= alpha;
 #pragma unroll
-        for (int jb = 0; jb < 4; ++jb) {
-            const float p = valid[jb] ? __builtin_amdgcn_exp2f(s4[jb] - m_new) : 0.f;
+        for (int e = 0; e < 2 * WAVE_VB; ++e) {
+            // an invalid token carries NEG_BIG; against a finite maximum that is weight 0, and a round whose
+            // maximum is NEG_BIG itself has no valid token at all
+            const float p = score[e] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(score[e] - m_new) : 0.f;
             l_lane += p;
-            pw[(4 * wave + jb) * 64 + lane] = p;
+            score[e] = p;
         }
         m_run = m_new;
 
         // ---------------- value passes: 8 groups of 4 subspaces
         for (int g = 0; g < 8; ++g) {
-            __syncthreads();  // weights written (first group); table region free
+            uint32_t cur[3], nxt[3];
+            {
+                const int vb = sb + wave < last_vb ? sb + wave : last_vb;
+                const uint32_t *u = v_units + (((int64_t)vb * 8 + g) * 64) * 3;
+#pragma unroll
+                for (int e = 0; e < 3; ++e)
+                    cur[e] = u[e];
+            }
+            __syncthreads();  // the table region is free
             {
                 const u32x4 *src = (const u32x4 *)(vcb + (int64_t)(4 * g) * PQ12_CENTROIDS * 4);
 #pragma unroll
@@ -187,24 +241,40 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
             }
             __syncthreads();
 #pragma unroll
-            for (int jv = 0; jv < 2; ++jv) {
-                const int vblk = vbc + 2 * wave + jv;  // 128-token block of the head
-                if (vblk < vb1) {
-                    const uint32_t *src = (const uint32_t *)(v_head + (((int64_t)vblk * 8 + g) * 64 + lane) * 12);
-                    uint32_t c[8];
-                    unpack8(src[0], src[1], src[2], c);
+            for (int jj = 0; jj < WAVE_VB; ++jj) {
+                if (jj >= n_jj)
+                    continue;  // wave-uniform; `continue`, not `break`: the loop must unroll (registers are indexed by jj)
+                {
+                    const int want = sb + wave + NW12 * (jj + 1);
+                    const int vb = want < last_vb ? want : last_vb;
+                    const uint32_t *u = v_units + (((int64_t)vb * 8 + g) * 64) * 3;
 #pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        const float p = pw[(2 * wave + jv) * 128 + (lane >> 2) + 16 * k];
-                        const u32x2 cv = *(lds_u32x2 *)(lbase + TAB_OFF + ((lane & 3) * PQ12_CENTROIDS + c[k]) * 8);
-                        const uint32_t lo = cv.x, hi = cv.y;
-                        const __half2 h0 = *(const __half2 *)&lo, h1 = *(const __half2 *)&hi;
-                        acc[g][0] = fmaf(p, __low2float(h0), acc[g][0]);
-                        acc[g][1] = fmaf(p, __high2float(h0), acc[g][1]);
-                        acc[g][2] = fmaf(p, __low2float(h1), acc[g][2]);
-                        acc[g][3] = fmaf(p, __high2float(h1), acc[g][3]);
-                    }
+                    for (int e = 0; e < 3; ++e)
+                        nxt[e] = u[e];
                 }
+                // this block's 128 weights to the wavefront's own line
+                __builtin_amdgcn_wave_barrier();
+                pline[lane] = score[2 * jj];
+                pline[64 + lane] = score[2 * jj + 1];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                uint32_t c[8];
+                unpack8(cur[0], cur[1], cur[2], c);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float p = pline[(lane >> 2) + 16 * k];
+                    const u32x2 cv = *(lds_u32x2 *)(lbase + TAB_OFF + ((lane & 3) * PQ12_CENTROIDS + c[k]) * 8);
+                    const uint32_t lo = cv.x, hi = cv.y;
+                    const __half2 h0 = *(const __half2 *)&lo, h1 = *(const __half2 *)&hi;
+                    acc[g][0] = fmaf(p, __low2float(h0), acc[g][0]);
+                    acc[g][1] = fmaf(p, __high2float(h0), acc[g][1]);
+                    acc[g][2] = fmaf(p, __low2float(h1), acc[g][2]);
+                    acc[g][3] = fmaf(p, __high2float(h1), acc[g][3]);
+                }
+#pragma unroll
+                for (int e = 0; e < 3; ++e)
+                    cur[e] = nxt[e];
             }
         }
     }
@@ -314,8 +384,14 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
 
 hipError_t pq12_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
 {
-    (void)ctx;
     const int grid = a.B * a.Hq * a.S;
-    hipLaunchKernelGGL(pq12_decode_kernel, dim3(grid), dim3(NW12 * 64), 0, s, a);
+    // blocks of 128 tokens per split at full capacity, per wavefront
+    const int64_t per_wave = (ctx->cap_padded / 128 + (int64_t)a.S * NW12 - 1) / ((int64_t)a.S * NW12);
+    if (per_wave <= 2)
+        hipLaunchKernelGGL(pq12_decode_kernel<2>, dim3(grid), dim3(NW12 * 64), 0, s, a);
+    else if (per_wave <= 6)
+        hipLaunchKernelGGL(pq12_decode_kernel<6>, dim3(grid), dim3(NW12 * 64), 0, s, a);
+    else
+        hipLaunchKernelGGL(pq12_decode_kernel<16>, dim3(grid), dim3(NW12 * 64), 0, s, a);
     return hipGetLastError();
 }
