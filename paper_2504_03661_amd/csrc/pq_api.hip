@@ -70,7 +70,9 @@ int64_t token_bytes(const pq_attn_config *c) { return pq_config_is_12bit(c) ? PQ
 int choose_splits(const pq_attn_config *c, int n_cu)
 {
     // the grouped-query kernel runs one workgroup per (sequence, KV head, split)
-    const int64_t heads = (int64_t)c->batch * (pq_config_uses_grouped_kernel(c) ? c->n_kv_heads : c->n_q_heads);
+    const int g = c->n_q_heads / c->n_kv_heads;
+    const int64_t heads =
+        (int64_t)c->batch * (pq_config_uses_grouped_kernel(c) ? c->n_q_heads / pq_grouped_heads_per_workgroup(g) : c->n_q_heads);
     int64_t s = n_cu / heads;
     const int64_t blocks = padded_capacity(c) / 64;
     // 8-bit kernels: at least a 64-token block per wavefront; 12-bit kernel: at least one 4096-token chunk
@@ -255,6 +257,7 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
     a.Hq = ctx->cfg.n_q_heads;
     a.Hkv = ctx->cfg.n_kv_heads;
     a.G = ctx->group;
+    a.Gs = ctx->k_skew == PQ_K_SKEW_QUAD ? pq_grouped_heads_per_workgroup(ctx->group) : 0;
     a.S = ctx->n_splits;
     a.max_context = ctx->cfg.max_context;
     a.max_recent = ctx->cfg.max_recent;

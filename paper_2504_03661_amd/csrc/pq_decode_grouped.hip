@@ -72,6 +72,10 @@ __device__ inline f16x4 as_f16x4(uint32_t lo, uint32_t hi)
     return __builtin_bit_cast(f16x4, v);
 }
 
+// READ_ONCE: one workgroup per (sequence, KV head, split) reads the head's codes, so they stream with the
+// non-temporal hint; with more than 4 query heads per KV head several workgroups (4 heads each) share the
+// code stream through their XCD's L2 and load normally.
+template <bool READ_ONCE>
 __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_decode_args a)
 {
     constexpr int M = 64;
@@ -82,18 +86,22 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int G = a.G;
+    const int G = a.Gs;  // query heads of this workgroup (2..4)
 
     const uint32_t grid = gridDim.x;
     uint32_t logical = blockIdx.x;
     if ((grid & 7u) == 0)
         logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
     const int S = a.S;
-    const int bkv = (int)(logical / (uint32_t)S);  // b * Hkv + hkv
-    const int split = (int)(logical - (uint32_t)bkv * (uint32_t)S);
+    // workgroups of one KV head are neighbours: (sequence, KV head, sub-group of G query heads, split)
+    const int unit = (int)(logical / (uint32_t)S);
+    const int split = (int)(logical - (uint32_t)unit * (uint32_t)S);
+    const int n_sub = a.G / G;                     // sub-groups per KV head
+    const int bkv = (int)((uint32_t)unit / (uint32_t)n_sub);  // b * Hkv + hkv
+    const int sub_group = unit - bkv * n_sub;
     const int b = (int)((uint32_t)bkv / (uint32_t)a.Hkv);
     const int hkv = bkv - b * a.Hkv;
-    const int bh0 = b * a.Hq + hkv * G;            // first query head of the group
+    const int bh0 = b * a.Hq + hkv * a.G + sub_group * G;  // first query head of this workgroup
     // The lengths are requested first and taken out of their registers only after the table loads
     // below have been issued.  The loads go through lane_zero(), which the compiler cannot see
     // through: a load from a wave-uniform address is otherwise made scalar on the spot, with a full
@@ -145,13 +153,13 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         const int step = live ? 64 : 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            dst[j] = load_codes<true>(kp + j * step);
+            dst[j] = load_codes<READ_ONCE>(kp + j * step);
     };
     auto load_v = [&](int blk_id) {
         const u32x4 *vp = (const u32x4 *)(v_head + (int64_t)blk_id * (64 * M)) + lane;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            vbuf[j] = load_codes<true>(vp + j * 64);
+            vbuf[j] = load_codes<READ_ONCE>(vp + j * 64);
     };
     int blk = blk0 + wave;
     *(lds_u32 *)(lbase + GCTR_OFF) = (uint32_t)(blk0 + NW);
@@ -413,16 +421,32 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
 
 }  // namespace
 
+// Query heads per workgroup for a group of g query heads per KV head: the largest of 4, 3, 2 that divides
+// g (the matrix instruction has 4 rows); 0 if none does or g = 1.
+int pq_grouped_heads_per_workgroup(int g)
+{
+    if (g < 2)
+        return 0;
+    for (int gs = GMAX; gs >= 2; --gs)
+        if (g % gs == 0)
+            return gs;
+    return 0;
+}
+
 bool pq_config_uses_grouped_kernel(const pq_attn_config *cfg)
 {
     const int g = cfg->n_kv_heads > 0 ? cfg->n_q_heads / cfg->n_kv_heads : 0;
-    return cfg->dtype == PQ_F16 && cfg->n_subspaces == 64 && cfg->head_dim == PQ_HEAD_DIM && g >= 2 && g <= GMAX;
+    return cfg->dtype == PQ_F16 && cfg->n_subspaces == 64 && cfg->n_centroids == 256 && cfg->head_dim == PQ_HEAD_DIM &&
+           pq_grouped_heads_per_workgroup(g) > 0;
 }
 
 hipError_t pq_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
 {
     (void)ctx;
-    const int grid = a.B * a.Hkv * a.S;
-    hipLaunchKernelGGL(pq_decode_grouped_kernel, dim3(grid), dim3(GNW * 64), 0, s, a);
+    const int grid = a.B * a.Hkv * (a.G / a.Gs) * a.S;
+    if (a.G == a.Gs)
+        hipLaunchKernelGGL(pq_decode_grouped_kernel<true>, dim3(grid), dim3(GNW * 64), 0, s, a);
+    else
+        hipLaunchKernelGGL(pq_decode_grouped_kernel<false>, dim3(grid), dim3(GNW * 64), 0, s, a);
     return hipGetLastError();
 }

@@ -116,6 +116,7 @@ struct pq_decode_args {
     unsigned int *tickets;
     float scale_log2e;
     int B, Hq, Hkv, G, S;  // G = Hq / Hkv
+    int Gs;                // grouped-query kernel: query heads per workgroup (divides G)
     int max_context, max_recent;
     int64_t head_stride;  // bytes of one (sequence, KV head) in a code tensor
 };
@@ -133,8 +134,10 @@ struct pq_encode_args {
 // launchers (each returns hipGetLastError() after its launches)
 hipError_t pq_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
 hipError_t pq_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
-// true when the grouped-query kernel serves this configuration (fp16, M = 64, 2..4 query heads per KV head)
+// true when the grouped-query kernel serves this configuration (fp16, M = 64, 8-bit codes, Hq / Hkv a multiple of
+// 2, 3 or 4); the kernel takes pq_grouped_heads_per_workgroup(Hq / Hkv) query heads per workgroup
 bool pq_config_uses_grouped_kernel(const pq_attn_config *cfg);
+int pq_grouped_heads_per_workgroup(int g);
 hipError_t pq_launch_encode(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len, unsigned int *dev_err,
                             hipStream_t s);
 // lengths += n_new, saturating at max_context (sets the overflow flag)

@@ -95,7 +95,10 @@ CASES = [
     ("gqa4_m64_f16_s1", 2, 8, 2, 64, "f16", (3001, 640), 33, 1),
     ("gqa2_m64_f16", 3, 4, 2, 64, "f16", (1000, 64, 2085), 40, 0),
     ("gqa3_m64_f16", 1, 6, 2, 64, "f16", (4097,), 7, 5),
-    ("gqa8_m64_f16_per_head", 1, 8, 1, 64, "f16", (1500,), 7, 2),
+    ("gqa8_m64_f16_two_subgroups", 1, 8, 1, 64, "f16", (1500,), 7, 2),
+    ("gqa6_m64_f16_two_subgroups_of_3", 2, 12, 2, 64, "f16", (2100, 777), 9, 3),
+    ("gqa16_m64_f16_four_subgroups", 1, 16, 1, 64, "f16", (3000,), 5, 0),
+    ("gqa5_m64_f16_per_head", 1, 5, 1, 64, "f16", (1300,), 6, 2),
     ("gqa4_m64_f32_per_head", 1, 4, 1, 64, "f32", (700,), 7, 2),
     ("gqa_edges", 6, 8, 2, 64, "f16", (0, 1, 63, 64, 65, 0), 8, 4),
     ("mha_m32_f16", 2, 4, 4, 32, "f16", (777, 4096), 20, 0),
