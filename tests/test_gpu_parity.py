@@ -131,6 +131,30 @@ def test_decode_small(case):
         assert (got[0] == 0).all()                      # empty sequence -> zeros row
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_decode_random_shapes(seed):
+    """Seeded random shapes across every kernel variant: batch, group size (per-head, grouped with 2 / 3 / 4 heads
+    per workgroup, fall-back sizes), M, dtype, ragged lengths including empty sequences, window sizes, splits."""
+    rng = np.random.default_rng(9000 + seed)
+    B_ = int(rng.integers(1, 5))
+    Hkv = int(rng.integers(1, 4))
+    G = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 8]))
+    M = int(rng.choice([64, 64, 32]))
+    dtype = "f32" if seed % 6 == 5 else "f16"
+    lens = tuple(int(x) for x in rng.choice([0, 1, 63, 64, 65, 500, 2047, 4096, 6001], size=B_))
+    rcap = int(rng.choice([0, 1, 17, 64]))
+    splits = int(rng.integers(0, 8))
+    w = W.Workload(f"rand{seed}", B_, Hkv * G, Hkv, 128, M, max(lens) + int(rng.integers(1, 70)), dtype, recent_cap=rcap,
+                   recent_uniform=rcap > 0, seed=9000 + seed, ctx_lens=lens)
+    data = W.generate(w)
+    got = gpu_decode(w, data, n_splits=splits)
+    ref = oracle_out(w, data)
+    check(got, ref, f"B={B_} Hkv={Hkv} G={G} M={M} {dtype} lens={lens} rcap={rcap} splits={splits}")
+    for b in range(B_):
+        if lens[b] + int(data["recent_len"][b]) == 0:
+            assert (got[b] == 0).all()
+
+
 def test_decode_no_recent_tensors_and_codebooks_passed_per_call():
     w = W.Workload("nr", 2, 4, 4, 128, 64, 1500, "f16", seed=31, ctx_lens=(1500, 700))
     data = W.generate(w)
