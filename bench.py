@@ -217,10 +217,19 @@ def main():
             best = dt if best is None else min(best, dt)
             spent += dt
             reps += 1
+        # the same oracle on one thread, two rows
+        threads = pq_oracle.num_threads()
+        pq_oracle.set_num_threads(1)
+        t = time.perf_counter()
+        pq_oracle.decode(data["q"], data["k_codes"], data["v_codes"], ctx_len, data["k_codebook"], data["v_codebook"],
+                         data["recent_k"], data["recent_v"], data["recent_len"], scale=scale, pairs=all_pairs[:2])
+        one_thread = time.perf_counter() - t
+        pq_oracle.set_num_threads(threads)
         frac_rows = len(pairs) / len(all_pairs)
         cpu_tokens = tokens_per_step * frac_rows
         cpu = {"value": round(cpu_tokens / best, 1), "unit": "context tokens/s", "cores": pq_oracle.num_threads(),
                "kind": "oracle", "seconds": round(best, 4),
+               "value_one_thread": round(tokens_per_step * min(2, len(all_pairs)) / len(all_pairs) / one_thread, 1),
                "sample": f"{len(pairs)} of {len(all_pairs)} (sequence, head) rows of {w.name}, best of {reps}; "
                          "tokens counted pro rata"}
         if w.n_new == 0:

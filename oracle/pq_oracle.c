@@ -237,3 +237,13 @@ int PQ_NAME(oracle_num_threads)(void)
 #endif
     return n;
 }
+
+/* Limits the threads later calls use (n <= 0: back to the default of the OpenMP runtime's environment). */
+void PQ_NAME(oracle_set_num_threads)(int n)
+{
+#ifdef _OPENMP
+    omp_set_num_threads(n > 0 ? n : omp_get_num_procs());
+#else
+    (void)n;
+#endif
+}

@@ -36,6 +36,8 @@ def lib():
         L.oracle_dense_attention.restype = None
         L.oracle_dense_attention.argtypes = [vp, vp, vp, i64, i32, dbl, vp, vp]
         L.oracle_num_threads.restype = ctypes.c_int
+        L.oracle_set_num_threads.restype = None
+        L.oracle_set_num_threads.argtypes = [i32]
         # the same routines for 16-bit centroid indices (more than 256 centroids per subspace)
         for name in ("oracle_pq_decode", "oracle_pq_encode", "oracle_pq_dequantize"):
             wide = getattr(L, name + "_u16")
@@ -61,6 +63,11 @@ def _ptr(a: Optional[np.ndarray]):
 
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads for later calls (timing the oracle on one core); n <= 0 restores one thread per processor."""
+    lib().oracle_set_num_threads(int(n))
 
 
 def dequantize(codes: np.ndarray, codebook: np.ndarray) -> np.ndarray:
