@@ -362,6 +362,7 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if (ticket != (unsigned int)(S - 1))
         return;
+    asm volatile("" ::: "memory");  // the loads below stay behind the ticket in the instruction stream
     const float *ps = a.partials + (int64_t)bh * S * PQ_PART_STRIDE;
     const float2 ml = lane < S ? fetch(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
     mx = wave_max(ml.x);

@@ -418,6 +418,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if (ticket != (unsigned int)(S - 1))
         return;
+    asm volatile("" ::: "memory");  // the loads below stay behind the ticket in the instruction stream
     // the other splits' partials: device-scope loads, issued after the ticket has returned
     const float *ps = a.partials + (int64_t)bh * S * PQ_PART_STRIDE;
     // Lane s holds (maximum, weight sum) of split s.  The first eight splits' output loads are issued

@@ -392,6 +392,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     __syncthreads();
     if (!*last_flag || g >= G)
         return;
+    asm volatile("" ::: "memory");  // the loads below stay behind the ticket in the instruction stream
     {
         // the other workgroups' partials, by device-scope loads issued after the ticket has returned
         const float *ps = a.partials + (int64_t)(bh0 + g) * S * PQ_PART_STRIDE;
