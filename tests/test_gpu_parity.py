@@ -167,6 +167,23 @@ def test_decode_outlier_codebooks_gqa():
     check(gpu_decode(w, data), oracle_out(w, data), "outliers")
 
 
+@pytest.mark.parametrize("Hq,Hkv,M", [(2, 2, 64), (4, 1, 64), (2, 2, 32)])
+def test_lengths_outside_their_range_are_clamped(Hq, Hkv, M):
+    """Device lengths below zero count as 0, lengths above the capacities as the capacities (header contract)."""
+    w = W.Workload("clamp", 3, Hq, Hkv, 128, M, 700, "f16", recent_cap=12, recent_fixed=12, seed=61)
+    data = W.generate(w)
+    ref_data = dict(data)
+    ref_data["ctx_len"] = np.array([0, 700, 350], dtype=np.int32)
+    ref_data["recent_len"] = np.array([12, 0, 12], dtype=np.int32)
+    ref = oracle_out(w, ref_data)
+    with PQSession(data, Hq, "f16") as s:
+        s.ctx_len.copy_(torch.tensor([-7, 700 + 1000, 350], dtype=torch.int32))
+        s.recent_len.copy_(torch.tensor([12 + 99, -1, 12], dtype=torch.int32))
+        out = s.decode(W.attention_scale(w))
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), ref, "clamped lengths")
+
+
 def test_repeated_calls_reuse_tickets_and_scratch():
     w = W.Workload("rep", 2, 4, 4, 128, 64, 3000, "f16", recent_cap=16, recent_fixed=16, seed=8)
     data = W.generate(w)
