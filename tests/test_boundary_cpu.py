@@ -78,6 +78,14 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.pq_attn_decode(None, None, None, None, None, None, None, None, None, None, 1.0, None, None) == -1
     assert lib.pq_encode_append(None, None, None, 1, None, None, None, None, None, None) == -1
     assert lib.pq_attn_validate_config(None) == -1
+    assert lib.pq_pack_codes(None, 0, None, 1, None, None) == -1
+    assert lib.pq_unpack_codes(None, 0, None, 1, None, None) == -1
+    assert lib.pq_attn_set_codebooks(None, None, None, None) == -1
+    assert lib.pq_kmeans_workspace_bytes(None) == -1
+    assert lib.pq_kmeans_fit(None, None, 1, None, 1, None, 0, None) == -1
+    assert lib.pq_stream_read_probe(None, None, 16, None) == -1
+    assert lib.pq_attn_device_error(None, None) == -1
+    assert lib.pq_attn_n_splits(None) == -1
     out = ctypes.c_void_p()
     # bad config is reported before any HIP call
     assert lib.pq_attn_create(ctypes.byref(good(batch=0).c_struct()), ctypes.byref(out)) == -2
