@@ -157,11 +157,11 @@ int pq_unpack_codes(pq_attn_ctx *ctx, int32_t kind, const uint8_t *packed, int32
  * value.  The result does not depend on the order in which samples are processed.
  *
  *   samples    device [Hkv][n_samples][d] fp16 (finite), 1 <= n_samples <= 2^20 (else PQ_ERR_CAPACITY)
- *   codebook   device [Hkv][M][256][ds] fp16: initial centroids in, trained centroids out (in place)
+ *   codebook   device [Hkv][M][C][ds] fp16: initial centroids in, trained centroids out (in place)
  *   workspace  device, 8-byte aligned, at least pq_kmeans_workspace_bytes(ctx) bytes (else PQ_ERR_CAPACITY);
  *              contents need not be initialised and are garbage afterwards
  *
- * fp16 contexts with 8-bit codes only (PQ_ERR_UNSUPPORTED otherwise).  Asynchronous on the stream.  Training a codebook that
+ * fp16 contexts only (PQ_ERR_UNSUPPORTED otherwise); with 12-bit codes the codebook is [Hkv][32][4096][4].  Asynchronous on the stream.  Training a codebook that
  * is registered with the context in place requires pq_attn_set_codebooks afterwards. */
 int64_t pq_kmeans_workspace_bytes(const pq_attn_ctx *ctx);
 int pq_kmeans_fit(pq_attn_ctx *ctx, const void *samples /* device */, int32_t n_samples, void *codebook /* device */,

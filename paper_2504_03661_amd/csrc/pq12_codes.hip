@@ -41,11 +41,12 @@ __device__ inline void unpack8(const uint32_t (&w)[3], uint32_t (&c)[8])
 
 // One workgroup = (K or V, KV head, subspace) x 4 work items, one per wavefront; a work item is a 64-token
 // chunk of one sequence (the sequences of a batch share the head's codebook, so short appends of many
-// sequences still fill the workgroup).
+// sequences still fill the workgroup).  x is [B][Hkv][x_head_stride >= n_new][d]; the codes of its first
+// n_new rows go to out [B][Hkv][n_new][32].
 __global__ __launch_bounds__(E12_WAVES * 64) void pq12_encode_kernel(const __half *x0, const __half *x1,
                                                                     const __half *cb0, const __half *cb1,
                                                                     uint16_t *out0, uint16_t *out1, int B, int Hkv,
-                                                                    int n_new, int groups_per_head)
+                                                                    int n_new, int groups_per_head, int64_t x_head_stride)
 {
 #pragma clang fp contract(off)
     __shared__ double tile[E12_TILE * 4];
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(E12_WAVES * 64) void pq12_encode_kernel(const __hal
     double xv[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-        xv[j] = live ? (double)__half2float(x[(head * n_new + tok) * PQ_HEAD_DIM + i * 4 + j]) : 0.0;
+        xv[j] = live ? (double)__half2float(x[(head * x_head_stride + tok) * PQ_HEAD_DIM + i * 4 + j]) : 0.0;
 
     int best = 0;
     double best_dist = __builtin_huge_val();
@@ -226,7 +227,7 @@ hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_arg
     const dim3 grid((unsigned)(a.Hkv * groups_per_head), PQ12_M, 2);
     hipLaunchKernelGGL(pq12_encode_kernel, grid, dim3(E12_WAVES * 64), 0, s, (const __half *)a.x[0],
                        (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
-                       ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head);
+                       ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, (int64_t)a.n_new);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return e;
@@ -238,4 +239,75 @@ hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_arg
         return e;
     // the lengths move only after both packing kernels have read the old ones (stream order)
     return pq_launch_bump_len(ctx_len, a.B, a.n_new, a.max_context, dev_err, s);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Offline codebook training for 4096 centroids: the Lloyd iteration of pq_kmeans.hip with the assignment done
+// by the encode kernel above (chunks of the samples, codes staged in the workspace) and the exact 64-bit
+// integer member sums added straight to memory (a subspace has 4096 x 4 sums: they do not fit in LDS, and
+// with that many addresses the atomics hardly collide).
+// ---------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int KM12_CHUNK = 8192;  // samples per head and assignment launch
+
+// one thread per (head, sample of the chunk, subspace)
+__global__ void pq12_kmeans_accumulate_kernel(const __half *samples, const uint16_t *codes, unsigned long long *sums,
+                                              unsigned int *counts, int64_t head_stride, int nc, int64_t total)
+{
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= total)
+        return;
+    const int i = (int)(x & (PQ12_M - 1));
+    const int64_t tok = (x >> 5) % nc;
+    const int64_t head = (x >> 5) / nc;
+    const uint32_t c = codes[x] & 0xfffu;
+    const __half *v = samples + (head * head_stride + tok) * PQ_HEAD_DIM + i * 4;
+    const int64_t e = (head * PQ12_M + i) * PQ12_CENTROIDS + c;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        // exact: an fp16 value times 2^24 is an integer below 2^41 in magnitude
+        const long long fixed = (long long)(__half2float(v[j]) * 16777216.0f);
+        atomicAdd(&sums[e * 4 + j], (unsigned long long)fixed);
+    }
+    atomicAdd(&counts[e], 1u);
+}
+
+}  // namespace
+
+int64_t pq12_kmeans_workspace_bytes(const pq_attn_ctx *ctx)
+{
+    const int64_t n = (int64_t)ctx->cfg.n_kv_heads * PQ12_M * PQ12_CENTROIDS;
+    return n * 4 * 8 + n * 4 + (int64_t)ctx->cfg.n_kv_heads * KM12_CHUNK * PQ12_M * 2;
+}
+
+hipError_t pq12_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n_samples, void *codebook, int n_iters,
+                              void *workspace, hipStream_t s)
+{
+    const int Hkv = ctx->cfg.n_kv_heads;
+    const int64_t n = (int64_t)Hkv * PQ12_M * PQ12_CENTROIDS;
+    unsigned long long *sums = (unsigned long long *)workspace;
+    unsigned int *counts = (unsigned int *)(sums + n * 4);
+    uint16_t *codes = (uint16_t *)(counts + n);
+    hipError_t e = pq_launch_clear_words(workspace, (n * 4 * 8 + n * 4) / 4, s);
+    if (e != hipSuccess)
+        return e;
+    for (int it = 0; it < n_iters; ++it) {
+        for (int c0 = 0; c0 < n_samples; c0 += KM12_CHUNK) {
+            const int nc = n_samples - c0 < KM12_CHUNK ? n_samples - c0 : KM12_CHUNK;
+            const __half *x = (const __half *)samples + (int64_t)c0 * PQ_HEAD_DIM;
+            const int n_chunks = (nc + 63) >> 6;
+            const int groups_per_head = (n_chunks + E12_WAVES - 1) / E12_WAVES;
+            hipLaunchKernelGGL(pq12_encode_kernel, dim3((unsigned)(Hkv * groups_per_head), PQ12_M, 1), dim3(E12_WAVES * 64), 0,
+                               s, x, x, (const __half *)codebook, (const __half *)codebook, codes, codes, 1, Hkv, nc,
+                               groups_per_head, (int64_t)n_samples);
+            const int64_t total = (int64_t)Hkv * nc * PQ12_M;
+            hipLaunchKernelGGL(pq12_kmeans_accumulate_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x, codes,
+                               sums, counts, (int64_t)n_samples, nc, total);
+        }
+        e = pq_launch_kmeans_update(codebook, sums, counts, n, 4, s);
+        if (e != hipSuccess)
+            return e;
+    }
+    return hipGetLastError();
 }

@@ -361,7 +361,7 @@ int64_t pq_kmeans_workspace_bytes(const pq_attn_ctx *ctx)
 {
     if (ctx == nullptr)
         return PQ_ERR_NULL;
-    if (ctx->cfg.dtype != PQ_F16 || pq_config_is_12bit(&ctx->cfg))
+    if (ctx->cfg.dtype != PQ_F16)
         return PQ_ERR_UNSUPPORTED;
     return pq_kmeans_accumulator_bytes(ctx);
 }
@@ -371,7 +371,7 @@ int pq_kmeans_fit(pq_attn_ctx *ctx, const void *samples, int32_t n_samples, void
 {
     if (ctx == nullptr || samples == nullptr || codebook == nullptr || workspace == nullptr)
         return PQ_ERR_NULL;
-    if (ctx->cfg.dtype != PQ_F16 || pq_config_is_12bit(&ctx->cfg))
+    if (ctx->cfg.dtype != PQ_F16)
         return PQ_ERR_UNSUPPORTED;
     if (n_samples < 1 || n_iters < 1 || ((uintptr_t)workspace & 7) != 0)
         return PQ_ERR_SHAPE;

@@ -160,3 +160,10 @@ hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_arg
                                      unsigned int *dev_err, hipStream_t s);
 hipError_t pq12_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint16_t *token_major, int n_tokens,
                                   uint8_t *packed, bool unpack, hipStream_t s);
+// pieces of the training shared by the 8-bit and the 12-bit path
+hipError_t pq_launch_clear_words(void *p, int64_t words, hipStream_t s);
+hipError_t pq_launch_kmeans_update(void *codebook, unsigned long long *sums, unsigned int *counts, int64_t n, int ds,
+                                   hipStream_t s);
+int64_t pq12_kmeans_workspace_bytes(const pq_attn_ctx *ctx);
+hipError_t pq12_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n_samples, void *codebook, int n_iters,
+                              void *workspace, hipStream_t s);

@@ -127,8 +127,27 @@ __global__ void pq_clear_words_kernel(uint32_t *p, int64_t n)
 
 }  // namespace
 
+hipError_t pq_launch_clear_words(void *p, int64_t words, hipStream_t s)
+{
+    hipLaunchKernelGGL(pq_clear_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, s, (uint32_t *)p, words);
+    return hipGetLastError();
+}
+
+hipError_t pq_launch_kmeans_update(void *codebook, unsigned long long *sums, unsigned int *counts, int64_t n, int ds,
+                                   hipStream_t s)
+{
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (ds == 2)
+        hipLaunchKernelGGL(pq_kmeans_update_kernel<2>, grid, block, 0, s, (__half *)codebook, sums, counts, n);
+    else
+        hipLaunchKernelGGL(pq_kmeans_update_kernel<4>, grid, block, 0, s, (__half *)codebook, sums, counts, n);
+    return hipGetLastError();
+}
+
 int64_t pq_kmeans_accumulator_bytes(const pq_attn_ctx *ctx)
 {
+    if (pq_config_is_12bit(&ctx->cfg))
+        return pq12_kmeans_workspace_bytes(ctx);
     const int64_t n = (int64_t)ctx->cfg.n_kv_heads * ctx->cfg.n_subspaces * 256;
     return n * ctx->ds * 8 + n * 4;
 }
@@ -136,6 +155,8 @@ int64_t pq_kmeans_accumulator_bytes(const pq_attn_ctx *ctx)
 hipError_t pq_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n_samples, void *codebook, int n_iters,
                             void *workspace, hipStream_t s)
 {
+    if (pq_config_is_12bit(&ctx->cfg))
+        return pq12_launch_kmeans(ctx, samples, n_samples, codebook, n_iters, workspace, s);
     const int Hkv = ctx->cfg.n_kv_heads, M = ctx->cfg.n_subspaces, DS = ctx->ds;
     const int64_t n = (int64_t)Hkv * M * 256;
     unsigned long long *sums = (unsigned long long *)workspace;

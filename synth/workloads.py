@@ -167,24 +167,25 @@ def attention_scale(w: Workload) -> np.float32:
 
 
 def training_samples(n_kv_heads: int, n_samples: int, head_dim: int = 128, n_subspaces: int = 64, seed: int = 0,
-                     duplicate_init: int = 0) -> Dict[str, np.ndarray]:
+                     duplicate_init: int = 0, n_centroids: int = N_CENTROIDS) -> Dict[str, np.ndarray]:
     """Stand-in for the sampled K (or V) activations that the offline codebook training clusters
     (Section III-A, "Offline PQ Codebook Training"): per head, `n_samples` fp16 vectors ~ N(0, 1) times a
     per-channel factor drawn log-uniformly in [0.5, 4] (a few channels much larger than the rest, the
     shape the paper's Fig. 2-3 describe).  The initial codebook is the sub-vectors of the head's first
-    256 samples (centroid c of subspace i = sample c's i-th sub-vector); with `duplicate_init` = k the
-    last k initial centroids of every subspace repeat the first k, so that some clusters stay empty.
+    C = n_centroids samples (centroid c of subspace i = sample c's i-th sub-vector); with `duplicate_init`
+    = k the last k initial centroids of every subspace repeat the first k, so that some clusters stay
+    empty.
 
         samples   [Hkv, n_samples, d]      float16
-        init      [Hkv, M, 256, ds]        float16
+        init      [Hkv, M, C, ds]          float16
     """
-    assert n_samples >= N_CENTROIDS
+    assert n_samples >= n_centroids
     rng = np.random.Generator(np.random.Philox(key=BASE_SEED + 7919 * (seed + 1)))
     ds = head_dim // n_subspaces
     chan = np.exp(rng.uniform(np.log(0.5), np.log(4.0), size=(n_kv_heads, 1, head_dim)))
     x = (rng.standard_normal((n_kv_heads, n_samples, head_dim)) * chan).astype(np.float32).astype(np.float16)
     init = np.ascontiguousarray(
-        x[:, :N_CENTROIDS].reshape(n_kv_heads, N_CENTROIDS, n_subspaces, ds).transpose(0, 2, 1, 3))
+        x[:, :n_centroids].reshape(n_kv_heads, n_centroids, n_subspaces, ds).transpose(0, 2, 1, 3))
     if duplicate_init > 0:
-        init[:, :, N_CENTROIDS - duplicate_init:] = init[:, :, :duplicate_init]
+        init[:, :, n_centroids - duplicate_init:] = init[:, :, :duplicate_init]
     return {"samples": x, "init": init}

@@ -12,8 +12,8 @@ from synth import workloads as W
 pytestmark = pytest.mark.gpu
 
 
-def make_ctx(Hkv, M, dtype=B.PQ_F16):
-    cfg = PQAttnConfig(batch=1, n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=128, n_subspaces=M, n_centroids=256,
+def make_ctx(Hkv, M, dtype=B.PQ_F16, n_centroids=256):
+    cfg = PQAttnConfig(batch=1, n_q_heads=Hkv, n_kv_heads=Hkv, head_dim=128, n_subspaces=M, n_centroids=n_centroids,
                        max_context=64, max_recent=0, dtype=dtype, device=0, n_splits=0)
     return B.pq_attn_create(cfg)
 
@@ -43,6 +43,20 @@ def test_trained_codebook_is_bit_identical_to_the_oracle(Hkv, M, n, iters, dup):
     assert not diff.any(), f"{int(diff.sum())} of {diff.size} centroid coordinates differ"
     if dup and iters == 1:
         assert (got[:, :, 256 - dup:].view(np.uint16) == d["init"][:, :, 256 - dup:].view(np.uint16)).all()
+
+
+@pytest.mark.parametrize("n,iters,dup", [(5000, 2, 0), (8192 + 77, 1, 9)])
+def test_trained_12bit_codebook_is_bit_identical_to_the_oracle(n, iters, dup):
+    """4096 centroids per subspace (M = 32): assignment in chunks of 8192 samples, sums added straight to memory."""
+    d = W.training_samples(2, n, 128, 32, seed=n, duplicate_init=dup, n_centroids=4096)
+    want, _ = K.kmeans_lloyd(d["samples"], d["init"], iters)
+    ctx = make_ctx(2, 32, n_centroids=4096)
+    try:
+        got = gpu_fit(ctx, d["samples"], d["init"], iters)
+    finally:
+        B.pq_attn_destroy(ctx)
+    diff = got.view(np.uint16) != want.view(np.uint16)
+    assert not diff.any(), f"{int(diff.sum())} of {diff.size} centroid coordinates differ"
 
 
 def test_training_lowers_the_quantization_error_and_the_codebook_serves_encode():
