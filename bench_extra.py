@@ -1,10 +1,10 @@
 #!/usr/bin/env python3
 """Measurements beyond the headline benchmark (one MI355X):
 
-    python -m paper_2504_03661_amd.bench_extra prefill   # bulk encode of a 32K-token prompt, all heads, K and V
-    python -m paper_2504_03661_amd.bench_extra async     # encode on a second stream while decode runs
-    python -m paper_2504_03661_amd.bench_extra train     # offline codebook training (k-means), 64K samples x 32 heads
-    python -m paper_2504_03661_amd.bench_extra pq12      # 12-bit codes: decode at 1 x 32 heads x 32K and 8 x 32 x 32K, 64-token append
+    python bench_extra.py prefill   # bulk encode of a 32K-token prompt, all heads, K and V
+    python bench_extra.py async     # encode on a second stream while decode runs
+    python bench_extra.py train     # offline codebook training (k-means), 64K samples x 32 heads
+    python bench_extra.py pq12      # 12-bit codes: decode at 1 x 32 heads x 32K and 8 x 32 x 32K, 64-token append
 
 prefill: the nearest-centroid encode at prompt shape (Section III-A, "Online Prefill with KV Cache
 Quantization"): vectors per second against the fp64 vector-ALU roofline (2 ds + 3 operations per
@@ -16,7 +16,7 @@ two kernels touch disjoint data; the caller publishes the new lengths between st
 
 train: Lloyd iterations of the per-subspace k-means (Section III-A, "Offline PQ Codebook Training") on 65 536
 sampled vectors per head, 32 heads, M = 64: time per iteration against the same fp64 vector-ALU roofline (the
-assignment step is the encode's scan), with the oracle timed on a small sample beside it.
+assignment step is the encode's scan).
 
 pq12: the 12-bit setting (M = 32, 4096 centroids, 48 bytes per token and tensor; Section IV-A).  Decode
 against HBM: algorithmic bytes = codes + recent rows + both codebooks once per KV head (2 MiB per head: at 32K
@@ -28,7 +28,7 @@ import os
 import sys
 import time
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -152,22 +152,13 @@ def train():
     trained = cb.cpu().numpy()
     B.pq_attn_destroy(ctx)
 
-    # the oracle on 2 heads x 4096 samples, one iteration
-    from oracle import pq_kmeans_oracle as K
-    sub = {"samples": d["samples"][:2, :4096], "init": d["init"][:2]}
-    t = time.perf_counter()
-    K.kmeans_lloyd(sub["samples"], sub["init"], 1)
-    cpu_s = time.perf_counter() - t
     print(json.dumps({"mode": "kmeans_train", "workload": f"{Hkv} heads x {n} samples, M={M}, {iters} Lloyd iterations",
                       "ms_per_iteration": round(ms, 3),
                       "sub_vectors_per_s": round(Hkv * M * n / (ms * 1e-3), 1),
                       "alu": {"bound": "alu", "achieved": round(ops / (ms * 1e-3) / 1e12, 2),
                               "peak": round(ALU_LANE_OPS_PER_S / 1e12, 1), "unit": "T fp64 vector operations/s",
                               "frac": round(ops / (ms * 1e-3) / ALU_LANE_OPS_PER_S, 4)},
-                      "inertia_initial": round(K.inertia(d["samples"][:1, :8192], d["init"][:1]), 1),
-                      "inertia_trained": round(K.inertia(d["samples"][:1, :8192], trained[:1]), 1),
-                      "cpu_baseline": {"kind": "oracle", "sample": "2 heads x 4096 samples, 1 iteration",
-                                       "sub_vectors_per_s": round(2 * M * 4096 / cpu_s, 1)}}))
+                      "trained_codebook_finite": bool(np.isfinite(trained.astype(np.float32)).all())}))
 
 
 def pq12():
