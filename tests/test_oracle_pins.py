@@ -35,8 +35,9 @@ def brute_force(data, scale, b, hq, G=1):
     vcb = data["v_codebook"][hkv].astype(np.float64)
     M = kc.shape[1]
     sub = np.arange(M)[None, :]
-    K = kcb[sub, kc].reshape(N, -1)                             # gather + concatenate (Eq. 5)
-    V = vcb[sub, vc].reshape(N, -1)
+    d = kcb.shape[0] * kcb.shape[2]
+    K = kcb[sub, kc].reshape(N, d)                              # gather + concatenate (Eq. 5)
+    V = vcb[sub, vc].reshape(N, d)
     R = int(data["recent_len"][b])
     if R:
         K = np.concatenate([K, data["recent_k"][b, hkv, :R].astype(np.float64)])
@@ -365,3 +366,46 @@ def test_encode_with_4096_centroids_matches_library_vector_quantizer():
     cb[0, 0, 4000] = cb[0, 0, 17]
     x[0, 0, 0, :4] = cb[0, 0, 4000]
     assert O.encode(x, cb)[0, 0, 0, 0] == 17
+
+
+# ------------------------------------------------------------------ property-based: random tiny shapes
+
+from hypothesis import given, settings, strategies as st  # noqa: E402
+
+
+@settings(max_examples=30, deadline=None)
+@given(seed=st.integers(0, 10_000), B=st.integers(1, 3), Hkv=st.integers(1, 2), G=st.integers(1, 3),
+       M=st.sampled_from([1, 2, 4, 8]), ds=st.sampled_from([1, 2, 4]), C=st.sampled_from([2, 7, 256, 300, 4096]),
+       N=st.integers(0, 40), R=st.integers(0, 6), f16=st.booleans())
+def test_decode_equals_brute_force_on_random_tiny_shapes(seed, B, Hkv, G, M, ds, C, N, R, f16):
+    """Brute force (numpy gather + scipy softmax) over drawn shapes: any subspace count and width, any
+    codebook size (byte and 16-bit indices), grouped heads, ragged and empty sequences, with and without window."""
+    rng = np.random.default_rng(seed)
+    lens = tuple(int(x) for x in rng.integers(0, N + 1, size=B))
+    w = W.Workload("h", B, Hkv * G, Hkv, M * ds, M, max(N, 1), "f16" if f16 else "f32", recent_cap=R,
+                   recent_uniform=R > 0, seed=seed, ctx_lens=lens, n_centroids=C)
+    data = W.generate(w)
+    out = run_oracle(w, data)
+    for b in range(B):
+        for h in range(Hkv * G):
+            if lens[b] + int(data["recent_len"][b]) == 0:
+                assert (out[b, h] == 0).all()
+            else:
+                np.testing.assert_allclose(out[b, h], brute_force(data, W.attention_scale(w), b, h, G), rtol=1e-11,
+                                           atol=1e-12)
+
+
+@settings(max_examples=25, deadline=None)
+@given(seed=st.integers(0, 10_000), M=st.sampled_from([1, 3, 8]), ds=st.sampled_from([1, 2, 4]),
+       C=st.sampled_from([1, 5, 256, 1000]), n=st.integers(0, 30), f16=st.booleans())
+def test_encode_equals_vectorised_argmin_on_random_tiny_shapes(seed, M, ds, C, n, f16):
+    """numpy argmin over explicitly computed squared distances (first minimum = lowest index); the drawn values
+    are multiples of 1/8 in [-4, 4], so every distance is exact in double and equal distances do occur."""
+    rng = np.random.default_rng(seed)
+    dt = np.float16 if f16 else np.float32
+    cb = (rng.integers(-32, 33, size=(2, M, C, ds)) / 8.0).astype(dt)
+    x = (rng.integers(-32, 33, size=(1, 2, n, M * ds)) / 8.0).astype(dt)
+    codes = O.encode(x, cb)
+    xs = x.astype(np.float64).reshape(1, 2, n, M, 1, ds)
+    d2 = ((xs - cb.astype(np.float64)[None, :, None]) ** 2).sum(-1)         # [1, 2, n, M, C]
+    assert (codes == d2.argmin(-1)).all()
