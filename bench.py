@@ -50,8 +50,10 @@ def algorithmic_bytes(w, data):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
+    # Defaults: the first 10-20 ms of back-to-back launches after an idle period run about 8 % slower than the
+    # steady state (clocks ramping up), so the warm-up is longer than that and the timed region a few times longer.
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=1000)
     ap.add_argument("--config", type=int, default=1, help="workload index 0..4 (default 1: the metric's workload)")
     ap.add_argument("--copies", type=int, default=0, help="distinct code-tensor copies to rotate (0 = 1 GiB worth)")
     ap.add_argument("--splits", type=int, default=0)
