@@ -207,16 +207,12 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     }
     __syncthreads();
 
-    // column bytes of the score pass: byte k of idx[r] = 4 * ((4r + k + lane) % 64)
+    // column bytes of the score pass: byte k of idx[r] = 4 * ((4r + k + lane) % 64), the four bytes at once
+    // (no byte of any intermediate exceeds 255, so nothing carries from byte to byte)
     uint32_t idx[M / 4];
 #pragma unroll
-    for (int r = 0; r < M / 4; ++r) {
-        uint32_t v = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            v |= (uint32_t)(((4 * r + k + lane) & 63) << 2) << (8 * k);
-        idx[r] = v;
-    }
+    for (int r = 0; r < M / 4; ++r)
+        idx[r] = (((uint32_t)(4 * r + lane) * 0x01010101u + 0x03020100u) & 0x3f3f3f3fu) << 2;
     // value pass: byte 0 = this lane's column offset in a 256-byte codebook row,
     // byte 1 = bits 16..23 of the codebook image's LDS address
     const uint32_t vcol = (uint32_t)(sub * (2 * DS)) | ((VCB_OFF >> 16) << 8);

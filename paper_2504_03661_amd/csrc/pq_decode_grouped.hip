@@ -181,16 +181,11 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
 
     const int quad = lane >> 2;  // the 4x4x4 block of this lane
     const int row = lane & 3;    // its row: query head as an A operand, token / dim as a B operand
-    // score pass: column bytes, byte k of idx[r] = 4 * ((4r + k + 4 quad) % 64)
+    // score pass: column bytes, byte k of idx[r] = 4 * ((4r + k + 4 quad) % 64) = 16 * ((r + quad) % 16) + 4 k
     uint32_t idx[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        uint32_t v = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            v |= (uint32_t)(((4 * r + k + 4 * quad) & 63) << 2) << (8 * k);
-        idx[r] = v;
-    }
+    for (int r = 0; r < 16; ++r)
+        idx[r] = 0x0c080400u + 0x10101010u * (uint32_t)((r + quad) & 15);
     // gather r of a step: this lane's byte (r + 2 * (row / 2)) % 4 -> address = code << 8 | column
     uint32_t ksel[4];
 #pragma unroll
