@@ -246,14 +246,34 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         const float s = valid ? (s4[0] + s4[1]) + (s4[2] + s4[3]) : NEG_BIG;
 
         // ---------------- running softmax
-        const float m_new = fmaxf(m_run, wave_max(s));
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        const float p = valid ? __builtin_amdgcn_exp2f(s - m_new) : 0.f;
-        l_lane = fmaf(l_lane, alpha, p);
+        float p;
+        if constexpr (M == 32) {
+            // M = 32 is close to the vector-ALU issue limit, so here the reference maximum moves only when a
+            // score of the block exceeds it by more than 8 (a factor 2^8 in weight; a wave-wide vote): the
+            // weights stay below 2^8, far inside the range of the fp32 sums, and nearly every block after the
+            // first few skips the wave-wide maximum and the rescaling (16 x 32 heads x 64K: 350 -> 335 us).
+            // At M = 64 the extra branch costs more than it saves (it makes the wait counts conservative).
+            if (__builtin_amdgcn_ballot_w64(s > m_run + 8.0f) != 0) {  // wave-uniform
+                const float m_new = fmaxf(m_run, wave_max(s));
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                l_lane *= alpha;
 #pragma unroll
-        for (int j = 0; j < DS; ++j)
-            acc[j] *= alpha;
-        m_run = m_new;
+                for (int j = 0; j < DS; ++j)
+                    acc[j] *= alpha;
+                m_run = m_new;
+            }
+            p = valid ? __builtin_amdgcn_exp2f(s - m_run) : 0.f;
+            l_lane += p;
+        } else {
+            const float m_new = fmaxf(m_run, wave_max(s));
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            p = valid ? __builtin_amdgcn_exp2f(s - m_new) : 0.f;
+            l_lane = fmaf(l_lane, alpha, p);
+#pragma unroll
+            for (int j = 0; j < DS; ++j)
+                acc[j] *= alpha;
+            m_run = m_new;
+        }
         *(lds_f32 *)(pline + lane * 4) = p;
         __builtin_amdgcn_wave_barrier();
 
