@@ -102,6 +102,27 @@ def test_decode_small(case):
         assert (got[0] == 0).all()
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_decode_random_shapes(seed):
+    """Seeded random shapes: batch, grouped heads, ragged lengths around the 128-token block and the 4096-token
+    chunk boundaries, window sizes, split counts (all three instantiations of the kernel)."""
+    rng = np.random.default_rng(7000 + seed)
+    B_ = int(rng.integers(1, 4))
+    Hkv = int(rng.integers(1, 3))
+    G = int(rng.choice([1, 1, 2, 4]))
+    lens = tuple(int(x) for x in rng.choice([0, 1, 127, 128, 129, 2000, 4095, 4097, 9000, 20000], size=B_))
+    rcap = int(rng.choice([0, 3, 33]))
+    splits = int(rng.choice([0, 1, 2, 5]))
+    w = W.Workload(f"rand12_{seed}", B_, Hkv * G, Hkv, 128, 32, max(max(lens), 1) + int(rng.integers(0, 200)), "f16",
+                   recent_cap=rcap, recent_uniform=rcap > 0, seed=7000 + seed, ctx_lens=lens, n_centroids=4096)
+    data = W.generate(w)
+    with PQSession(data, Hkv * G, "f16", n_splits=splits) as s:
+        out = s.decode(W.attention_scale(w))
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+    check(got, oracle_out(w, data), f"B={B_} Hkv={Hkv} G={G} lens={lens} rcap={rcap} splits={splits}")
+
+
 @pytest.mark.parametrize("n_old,n_new", [(0, 70), (100, 64), (130, 300), (255, 1)])
 def test_encode_append_bit_exact_then_decode(n_old, n_new):
     w = W.Workload("enc12", 2, 2, 2, 128, 32, n_old + n_new, "f16", n_new=n_new, seed=4000 + n_old, n_centroids=4096)
