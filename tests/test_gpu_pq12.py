@@ -77,6 +77,8 @@ CASES = [
     ("splits_3", 1, 3, 3, (13000,), 5, 3),
     ("gqa2_splits_2", 2, 4, 2, (9000, 130), 4, 2),
     ("edges", 6, 1, 1, (0, 1, 127, 128, 129, 0), 8, 2),
+    ("three_rounds_of_32k", 1, 2, 2, (70000,), 5, 1),          # a split longer than the 32K tokens a round holds
+    ("two_rounds_ragged", 2, 1, 1, (40000, 33000), 0, 1),
 ]
 
 
