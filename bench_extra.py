@@ -20,7 +20,8 @@ assignment step is the encode's scan).
 
 pq12: the 12-bit setting (M = 32, 4096 centroids, 48 bytes per token and tensor; Section IV-A).  Decode
 against HBM: algorithmic bytes = codes + recent rows + both codebooks once per KV head (2 MiB per head: at 32K
-tokens they are 40 % of the bytes) + q / out.
+tokens they are 40 % of the bytes) + q / out.  With few (sequence, head) pairs the decode runs in two passes
+(partial scores per subspace group, then softmax and values): "n_passes" in the output.
 Each mode prints one JSON line.
 """
 import json
@@ -183,10 +184,10 @@ def pq12():
                 it[0] += 1
             # warm-up past the clock ramp that follows an idle period (the first 10-20 ms run slower)
             ms = _span_ms(step, 400, warmup=max(100, int(30e-3 / (70e-6 * Bn))))
-            n_splits = s.n_splits
+            n_splits, n_passes = s.n_splits, s.n_passes
         codes = Bn * 32 * 32768 * 96
         total = codes + Bn * 32 * 128 * 128 * 2 * 2 + 32 * 2 * 32 * 4096 * 4 * 2 + Bn * 32 * 128 * 6
-        res[name] = {"decode_ms": round(ms, 4), "n_splits": n_splits, "ctx_tokens_per_s": round(Bn * (32768 + 128) / (ms * 1e-3), 1),
+        res[name] = {"decode_ms": round(ms, 4), "n_passes": n_passes, "n_splits": n_splits, "ctx_tokens_per_s": round(Bn * (32768 + 128) / (ms * 1e-3), 1),
                      "roofline": {"bound": "hbm", "achieved": round(total / (ms * 1e-3) / 1e9, 1), "peak": 8000.0,
                                   "unit": "GB/s", "frac": round(total / (ms * 1e-3) / 1e9 / 8000.0, 4),
                                   "algorithmic_bytes": total, "code_bytes": codes}}

@@ -53,13 +53,16 @@ typedef struct {
     int32_t n_kv_heads;   /* Hkv, Hq % Hkv == 0                                             */
     int32_t head_dim;     /* d; supported: 128                                              */
     int32_t n_subspaces;  /* M; supported: 64 (ds = 2, 4 bits/dim) and 32 (ds = 4, 2 bits/dim) */
-    int32_t n_centroids;  /* C; supported: 256 (nbits = 8)                                  */
+    int32_t n_centroids;  /* C; supported: 256 (nbits = 8), and 4096 (nbits = 12) with M = 32, fp16 */
     int32_t max_context;  /* token capacity of the code tensors per (sequence, KV head),    */
                           /* 1 .. 2^24                                                      */
     int32_t max_recent;   /* row capacity of the recent window tensors (0: no window), <= 2^24 */
     int32_t dtype;        /* pq_dtype of q, codebooks, recent K/V and new K/V               */
     int32_t device;       /* HIP device ordinal                                             */
-    int32_t n_splits;     /* context splits per (sequence, query head); 0 = choose          */
+    int32_t n_splits;     /* context splits per (sequence, query head); 0 = choose.         */
+                          /* 4096-centroid contexts only: -k asks for the two-pass decode   */
+                          /* (split by subspace group) with k token ranges; "0 = choose"    */
+                          /* takes it by itself when (sequence, head) pairs are few         */
     int32_t reserved;     /* must be 0                                                      */
 } pq_attn_config;
 
@@ -80,6 +83,11 @@ int pq_attn_destroy(pq_attn_ctx *ctx);
 
 /* Number of context splits the decode kernel uses (after "0 = choose"). */
 int pq_attn_n_splits(const pq_attn_ctx *ctx);
+
+/* Kernels one pq_attn_decode call launches: 1 (fused), or 2 for a 4096-centroid
+ * context that decodes in two passes (partial scores per subspace group, then
+ * softmax and values). */
+int pq_attn_n_passes(const pq_attn_ctx *ctx);
 
 /* Registers the codebooks trained offline (Section III-A, "Offline PQ Codebook
  * Training"): C_K, C_V as [Hkv][M][C][ds] in the context dtype, device memory.

@@ -81,10 +81,14 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
     if ((grid & 7u) == 0)
         logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
     const int S = a.S;
-    const int bh = (int)(logical / (uint32_t)S);
-    const int split = (int)(logical - (uint32_t)bh * (uint32_t)S);
-    const int b = (int)((uint32_t)bh / (uint32_t)a.Hq);
-    const int hq = bh - b * a.Hq;
+    // Neighbouring workgroups (one XCD): the splits of a (sequence, head), then the same head of the other
+    // sequences — they refill their table region from the same 2 MiB of codebooks, which then come from the
+    // XCD's L2 instead of once per sequence from memory.
+    const int unit = (int)(logical / (uint32_t)S);
+    const int split = (int)(logical - (uint32_t)unit * (uint32_t)S);
+    const int hq = (int)((uint32_t)unit / (uint32_t)a.B);
+    const int b = unit - hq * a.B;
+    const int bh = b * a.Hq + hq;
     const int hkv = (int)((uint32_t)hq / (uint32_t)a.G);
 
     int N = a.ctx_len[b];
@@ -381,10 +385,371 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
         a.tickets[bh] = 0u;
 }
 
+
+// ---------------------------------------------------------------------------------
+// Two-pass path for few (sequence, query head) pairs.
+//
+// The fused kernel above splits a head's TOKENS over workgroups, and every workgroup streams all of the
+// head's tables (1.5 MiB) through its LDS: with few heads and therefore many splits per head the table
+// refills, not the codes, are most of the bytes a compute unit moves (1 x 32 heads x 32K: 1.5 MiB of tables
+// against 0.4 MB of codes per workgroup).  Here the SUBSPACES are split instead, so that a workgroup loads
+// one table region once and keeps it:
+//   pass 1  one workgroup per (sequence, query head, group of 8 subspaces, token range): builds the
+//           group's score table [8][4096] from the key codebook and the query, streams the group's key
+//           units and writes, per token, the sum of its 8 sampled entries — a partial score — to memory
+//           (4 floats per token and query head);
+//   pass 2  one workgroup per (sequence, query head, group of 4 subspaces, token range): keeps the group's
+//           slice of the value codebook in LDS, adds the 4 partial scores of a token, runs the running
+//           softmax (every group of a head computes the same maximum and weight sum) and accumulates the
+//           16 output dims of its subspaces.  With one token range per head the row is written directly;
+//           otherwise the ranges are merged as in the fused kernel, behind one ticket per head.
+// Each code byte still comes from HBM once; the partial scores cost 16 bytes per token and query head
+// written and read back (pass 2 finds them in the memory-side cache).
+// ---------------------------------------------------------------------------------
+constexpr int W2_OFF = 131072;                 // pass 2: float [16][128] weights of the block a wavefront works on
+constexpr int Q2_OFF = W2_OFF + NW12 * 512;    // float [128]: query x scale x log2(e)
+constexpr int PART2_OFF = Q2_OFF + 512;        // pass 2: float [16][24]: maximum, weight sum, 2 unused, 16 dims
+constexpr int PART2_STRIDE = 24;
+constexpr int SMEM2_BYTES = PART2_OFF + NW12 * PART2_STRIDE * 4;
+constexpr int PF2 = 1;                         // 128-token blocks a wavefront requests ahead (3 measured slower: 46 against 44 us)
+static_assert(SMEM2_BYTES <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+
+__device__ inline uint32_t undeal(uint32_t id, uint32_t grid)
+{
+    // consecutive logical ids on one XCD (workgroups are dealt to the 8 XCDs round-robin)
+    return (grid & 7u) == 0 ? (id & 7u) * (grid >> 3) + (id >> 3) : id;
+}
+
+__global__ __launch_bounds__(NW12 * 64) void pq12_scores_kernel(const pq_decode_args a, float *scores, const int TS)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM2_BYTES];
+    lds_u8 *lbase = (lds_u8 *)smem;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const uint32_t logical = undeal(blockIdx.x, gridDim.x);
+    const int bh = (int)(logical / (uint32_t)(4 * TS));
+    const int rem = (int)(logical - (uint32_t)bh * (uint32_t)(4 * TS));
+    const int g = rem / TS;
+    const int ts = rem - g * TS;
+    const int b = (int)((uint32_t)bh / (uint32_t)a.Hq);
+    const int hq = bh - b * a.Hq;
+    const int hkv = (int)((uint32_t)hq / (uint32_t)a.G);
+
+    int N = a.ctx_len[b];
+    N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
+    const uint32_t nvb = (uint32_t)(N + 127) >> 7;
+    const int vb0 = (int)(nvb * (uint32_t)ts / (uint32_t)TS);
+    const int vb1 = (int)(nvb * (uint32_t)(ts + 1) / (uint32_t)TS);
+    if (vb0 >= vb1)
+        return;  // workgroup-uniform
+
+    const uint8_t *k_head = a.k_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
+    const __half *kcb = (const __half *)a.kcb_packed + (int64_t)hkv * PQ12_M * PQ12_CENTROIDS * 4;
+    const uint32_t *k_units = (const uint32_t *)k_head + lane * 3;
+    const int64_t cap = a.head_stride / PQ12_TOKEN_BYTES;  // tokens per row of partial scores
+    float *row = scores + ((int64_t)bh * 4 + g) * cap;
+
+    // the first blocks' codes are requested before the table is built; PF2 blocks per wavefront stay in flight
+    const int last_vb = vb1 - 1;
+    uint32_t un[PF2][6];
+    auto load_units = [&](uint32_t (&dst)[6], int vb) {
+        const uint32_t *u = k_units + (((int64_t)(2 * (vb < last_vb ? vb : last_vb)) * 4 + g) * 64) * 3;
+#pragma unroll
+        for (int e = 0; e < 3; ++e) {
+            dst[e] = u[e];
+            dst[3 + e] = u[4 * 64 * 3 + e];  // the second 64-token block of the 128-token block
+        }
+    };
+#pragma unroll
+    for (int d = 0; d < PF2; ++d)
+        load_units(un[d], vb0 + wave + NW12 * d);
+
+    if (tid < PQ_HEAD_DIM)
+        *(lds_f32 *)(lbase + Q2_OFF + tid * 4) =
+            __half2float(((const __half *)a.q)[(int64_t)bh * PQ_HEAD_DIM + tid]) * a.scale_log2e;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int sub = 8 * g + i;
+        const u32x4 *src = (const u32x4 *)(kcb + ((int64_t)sub * PQ12_CENTROIDS + 4 * tid) * 4);
+        const u32x4 c01 = src[0], c23 = src[1];  // centroids 4 tid .. 4 tid + 3, four fp16 each
+        const f32x4 q4 = *(lds_f32x4 *)(lbase + Q2_OFF + sub * 16);
+        f32x4 ent;
+        ent.x = dot4(q4, c01.x, c01.y);
+        ent.y = dot4(q4, c01.z, c01.w);
+        ent.z = dot4(q4, c23.x, c23.y);
+        ent.w = dot4(q4, c23.z, c23.w);
+        *(lds_f32x4 *)(lbase + TAB_OFF + (i * PQ12_CENTROIDS + 4 * tid) * 4) = ent;
+    }
+    __syncthreads();
+
+    for (int vb = vb0 + wave; vb < vb1;) {
+#pragma unroll
+        for (int d = 0; d < PF2; ++d) {
+            if (vb < vb1) {  // wave-uniform
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    uint32_t c[8];
+                    unpack8(un[d][3 * h], un[d][3 * h + 1], un[d][3 * h + 2], c);
+                    float t[8];
+#pragma unroll
+                    for (int s8 = 0; s8 < 8; ++s8)
+                        t[s8] = *(lds_f32 *)(lbase + TAB_OFF + (s8 * PQ12_CENTROIDS + c[s8]) * 4);
+                    row[(int64_t)vb * 128 + 64 * h + lane] =
+                        ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+                }
+                load_units(un[d], vb + NW12 * PF2);
+                vb += NW12;
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(NW12 * 64) void pq12_values_kernel(const pq_decode_args a, const float *scores, const int TS)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM2_BYTES];
+    lds_u8 *lbase = (lds_u8 *)smem;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const uint32_t logical = undeal(blockIdx.x, gridDim.x);
+    const int bh = (int)(logical / (uint32_t)(8 * TS));
+    const int rem = (int)(logical - (uint32_t)bh * (uint32_t)(8 * TS));
+    const int g = rem / TS;
+    const int ts = rem - g * TS;
+    const int b = (int)((uint32_t)bh / (uint32_t)a.Hq);
+    const int hq = bh - b * a.Hq;
+    const int hkv = (int)((uint32_t)hq / (uint32_t)a.G);
+
+    int N = a.ctx_len[b];
+    int R = (a.recent_k != nullptr && a.recent_len != nullptr) ? a.recent_len[b] : 0;
+    N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
+    R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
+    const uint32_t nvb = (uint32_t)(N + 127) >> 7;
+    const int vb0 = (int)(nvb * (uint32_t)ts / (uint32_t)TS);
+    const int vb1 = (int)(nvb * (uint32_t)(ts + 1) / (uint32_t)TS);
+    const int r0 = (int)((uint32_t)R * (uint32_t)ts / (uint32_t)TS);
+    const int r1 = (int)((uint32_t)R * (uint32_t)(ts + 1) / (uint32_t)TS);
+
+    const uint8_t *v_head = a.v_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
+    const __half *vcb = (const __half *)a.vcb_packed + (int64_t)hkv * PQ12_M * PQ12_CENTROIDS * 4;
+    const uint32_t *v_units = (const uint32_t *)v_head + lane * 3;
+    const int64_t cap = a.head_stride / PQ12_TOKEN_BYTES;
+    const float *rows = scores + (int64_t)bh * 4 * cap;
+
+    // the first blocks' partial scores and codes are requested before the table is copied
+    const int last_vb = vb1 > vb0 ? vb1 - 1 : 0;
+    float sc[PF2][8];
+    uint32_t un[PF2][3];
+    auto load_block = [&](float (&scd)[8], uint32_t (&und)[3], int vb_want) {
+        const int vb = vb_want < last_vb ? vb_want : last_vb;
+#pragma unroll
+        for (int kg = 0; kg < 4; ++kg) {
+            scd[2 * kg] = rows[kg * cap + (int64_t)vb * 128 + lane];
+            scd[2 * kg + 1] = rows[kg * cap + (int64_t)vb * 128 + 64 + lane];
+        }
+        const uint32_t *u = v_units + (((int64_t)vb * 8 + g) * 64) * 3;
+#pragma unroll
+        for (int e = 0; e < 3; ++e)
+            und[e] = u[e];
+    };
+    if (vb1 > vb0) {
+#pragma unroll
+        for (int d = 0; d < PF2; ++d)
+            load_block(sc[d], un[d], vb0 + wave + NW12 * d);
+    }
+
+    if (tid < PQ_HEAD_DIM)
+        *(lds_f32 *)(lbase + Q2_OFF + tid * 4) =
+            __half2float(((const __half *)a.q)[(int64_t)bh * PQ_HEAD_DIM + tid]) * a.scale_log2e;
+    {
+        const u32x4 *src = (const u32x4 *)(vcb + (int64_t)(4 * g) * PQ12_CENTROIDS * 4);
+        u32x4 raw[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            raw[k] = src[tid + k * (NW12 * 64)];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            *(lds_u32x4 *)(lbase + TAB_OFF + (tid + k * (NW12 * 64)) * 16) = raw[k];
+    }
+    __syncthreads();
+
+    float m_run = NEG_BIG;  // this wavefront's reference maximum
+    float l_lane = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    lds_f32 *pline = (lds_f32 *)(lbase + W2_OFF) + wave * 128;
+    for (int vb = vb0 + wave; vb < vb1;) {
+#pragma unroll
+        for (int d = 0; d < PF2; ++d) {
+            if (vb < vb1) {  // wave-uniform
+                float s[2], p[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const bool valid = vb * 128 + 64 * h + lane < N;
+                    s[h] = valid ? (sc[d][h] + sc[d][2 + h]) + (sc[d][4 + h] + sc[d][6 + h]) : NEG_BIG;
+                }
+                // the reference maximum moves only when a score exceeds it by more than 8 (2^8 in weight)
+                const float smax = fmaxf(s[0], s[1]);
+                if (__builtin_amdgcn_ballot_w64(smax > m_run + 8.0f) != 0) {  // wave-uniform
+                    const float m_new = fmaxf(m_run, wave_max(smax));
+                    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                    l_lane *= alpha;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[j] *= alpha;
+                    m_run = m_new;
+                }
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    p[h] = s[h] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(s[h] - m_run) : 0.f;
+                    l_lane += p[h];
+                }
+                __builtin_amdgcn_wave_barrier();
+                pline[lane] = p[0];
+                pline[64 + lane] = p[1];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                uint32_t c[8];
+                unpack8(un[d][0], un[d][1], un[d][2], c);
+                load_block(sc[d], un[d], vb + NW12 * PF2);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const float pk = pline[(lane >> 2) + 16 * k];
+                    const u32x2 cv = *(lds_u32x2 *)(lbase + TAB_OFF + ((lane & 3) * PQ12_CENTROIDS + c[k]) * 8);
+                    const uint32_t lo = cv.x, hi = cv.y;
+                    const __half2 h0 = *(const __half2 *)&lo, h1 = *(const __half2 *)&hi;
+                    acc[0] = fmaf(pk, __low2float(h0), acc[0]);
+                    acc[1] = fmaf(pk, __high2float(h0), acc[1]);
+                    acc[2] = fmaf(pk, __low2float(h1), acc[2]);
+                    acc[3] = fmaf(pk, __high2float(h1), acc[3]);
+                }
+                vb += NW12;
+            }
+        }
+    }
+
+    // ---------------- sum the 16 token streams (lanes with equal lane % 4); then lane l < 16 owns dim 16 g + l
+    lds_f32 *part = (lds_f32 *)(lbase + PART2_OFF) + wave * PART2_STRIDE;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float v = acc[j];
+        v += __shfl_xor(v, 4);
+        v += __shfl_xor(v, 8);
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        if (lane < 4)
+            part[4 + lane * 4 + j] = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    float o = lane < 16 ? part[4 + lane] : 0.f;
+
+    // ---------------- recent full-precision rows of this token range: every group scores them, each adds its dims
+    {
+        const float q0 = *(lds_f32 *)(lbase + Q2_OFF + lane * 8), q1 = *(lds_f32 *)(lbase + Q2_OFF + lane * 8 + 4);
+        const int64_t rbase = ((int64_t)b * a.Hkv + hkv) * a.max_recent;
+        for (int r = r0 + wave; r < r1; r += NW12) {
+            const __half2 kk = *((const __half2 *)((const __half *)a.recent_k + (rbase + r) * PQ_HEAD_DIM) + lane);
+            const float vv =
+                lane < 16 ? __half2float(((const __half *)a.recent_v)[(rbase + r) * PQ_HEAD_DIM + 16 * g + lane]) : 0.f;
+            const float sr = wave_sum(fmaf(q0, __low2float(kk), q1 * __high2float(kk)));
+            const float m_new = fmaxf(m_run, sr);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            const float pr = __builtin_amdgcn_exp2f(sr - m_new);
+            l_lane = fmaf(l_lane, alpha, lane == 0 ? pr : 0.f);
+            o = fmaf(o, alpha, pr * vv);
+            m_run = m_new;
+        }
+    }
+    {
+        const float l_w = wave_sum(l_lane);
+        if (lane == 0) {
+            part[0] = m_run;
+            part[1] = l_w;
+        }
+        if (lane < 16)
+            part[4 + lane] = o;
+    }
+    __syncthreads();
+    if (wave != 0)
+        return;
+
+    // ---------------- wavefront 0 merges the workgroup: lane l < 8 takes dims 16 g + 2 l, + 1
+    const lds_f32 *parts = (const lds_f32 *)(lbase + PART2_OFF);
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int w = 0; w < NW12; ++w)
+        mx = fmaxf(mx, parts[w * PART2_STRIDE]);
+    float l = 0.f, o0 = 0.f, o1 = 0.f;
+    const int dl = lane < 8 ? lane : 0;
+#pragma unroll
+    for (int w = 0; w < NW12; ++w) {
+        const float f = __builtin_amdgcn_exp2f(parts[w * PART2_STRIDE] - mx);
+        o0 = fmaf(parts[w * PART2_STRIDE + 4 + 2 * dl], f, o0);
+        o1 = fmaf(parts[w * PART2_STRIDE + 5 + 2 * dl], f, o1);
+        l = fmaf(parts[w * PART2_STRIDE + 1], f, l);
+    }
+    float *orow = a.out + (int64_t)bh * PQ_HEAD_DIM;
+    if (TS == 1) {
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        if (lane < 8)
+            *(float2 *)(orow + 16 * g + 2 * lane) = make_float2(o0 * inv, o1 * inv);
+        return;
+    }
+    // Several token ranges: publish this range's 16 dims (and, from group 0, its maximum and weight sum, which
+    // every group of the range computes alike), then one ticket per head counts the 8 TS workgroups; the last
+    // one merges the ranges.  Device-scope stores complete before the ticket, device-scope loads follow it.
+    float *gpart = a.partials + ((int64_t)bh * TS + ts) * PQ_PART_STRIDE;
+    if (lane < 8)
+        publish(gpart + 4 + 16 * g + 2 * lane, o0, o1);
+    if (g == 0 && lane == 0)
+        publish(gpart, mx, l);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    unsigned int ticket = 0;
+    if (lane == 0)
+        ticket = __hip_atomic_fetch_add(a.tickets + bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    ticket = __builtin_amdgcn_readfirstlane(ticket);
+    if (ticket != (unsigned int)(8 * TS - 1))
+        return;
+    asm volatile("" ::: "memory");  // the loads below stay behind the ticket in the instruction stream
+    const float *ps = a.partials + (int64_t)bh * TS * PQ_PART_STRIDE;
+    const float2 ml = lane < TS ? fetch(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
+    mx = wave_max(ml.x);
+    const float f_lane = __builtin_amdgcn_exp2f(ml.x - mx);
+    l = wave_sum(ml.y * f_lane);
+    o0 = o1 = 0.f;
+    for (int s = 0; s < TS; ++s) {
+        const float2 os = fetch(ps + s * PQ_PART_STRIDE + 4 + 2 * lane);
+        const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), s & 63));
+        o0 = fmaf(os.x, f, o0);
+        o1 = fmaf(os.y, f, o1);
+    }
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    *(float2 *)(orow + 2 * lane) = make_float2(o0 * inv, o1 * inv);
+    if (lane == 0)
+        a.tickets[bh] = 0u;
+}
+
 }  // namespace
 
 hipError_t pq12_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
 {
+    if (ctx->scores12 != nullptr) {
+        // two passes: a.S is the number of token ranges of pass 2; pass 1 has half as many workgroups per
+        // range (4 groups against 8), so it takes twice the ranges where the context is long enough
+        const int64_t nvb = ctx->cap_padded / 128;
+        int ts1 = 2 * a.S;
+        if ((int64_t)ts1 * 16 > nvb)
+            ts1 = a.S;
+        hipLaunchKernelGGL(pq12_scores_kernel, dim3(a.B * a.Hq * 4 * ts1), dim3(NW12 * 64), 0, s, a, ctx->scores12, ts1);
+        hipLaunchKernelGGL(pq12_values_kernel, dim3(a.B * a.Hq * 8 * a.S), dim3(NW12 * 64), 0, s, a, ctx->scores12, a.S);
+        return hipGetLastError();
+    }
     const int grid = a.B * a.Hq * a.S;
     // blocks of 128 tokens per split at full capacity, per wavefront
     const int64_t per_wave = (ctx->cap_padded / 128 + (int64_t)a.S * NW12 - 1) / ((int64_t)a.S * NW12);

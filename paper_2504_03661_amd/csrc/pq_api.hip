@@ -33,8 +33,10 @@ int validate(const pq_attn_config *c)
     if (c == nullptr)
         return PQ_ERR_NULL;
     if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->n_subspaces <= 0 ||
-        c->n_centroids <= 0 || c->max_context <= 0 || c->max_recent < 0 || c->device < 0 || c->n_splits < 0 ||
-        c->reserved != 0)
+        c->n_centroids <= 0 || c->max_context <= 0 || c->max_recent < 0 || c->device < 0 || c->reserved != 0)
+        return PQ_ERR_SHAPE;
+    // a negative split count is the 12-bit contexts' request for the two-pass decode with that many token ranges
+    if (c->n_splits < 0 && c->n_centroids != PQ12_CENTROIDS)
         return PQ_ERR_SHAPE;
     if (c->n_q_heads % c->n_kv_heads != 0 || c->head_dim % c->n_subspaces != 0)
         return PQ_ERR_SHAPE;
@@ -45,7 +47,7 @@ int validate(const pq_attn_config *c)
     // 8-bit codes, or the 12-bit setting: 32 subspaces x 4096 centroids, fp16
     if (c->n_centroids != 256 && !(c->n_centroids == PQ12_CENTROIDS && c->n_subspaces == PQ12_M && c->dtype == PQ_F16))
         return PQ_ERR_UNSUPPORTED;
-    if (c->n_splits > PQ_MAX_SPLITS || c->max_context > PQ_MAX_TOKENS || c->max_recent > PQ_MAX_TOKENS)
+    if (c->n_splits > PQ_MAX_SPLITS || c->n_splits < -PQ_MAX_SPLITS || c->max_context > PQ_MAX_TOKENS || c->max_recent > PQ_MAX_TOKENS)
         return PQ_ERR_UNSUPPORTED;
     if ((int64_t)c->batch * c->n_q_heads * PQ_MAX_SPLITS > (int64_t)1 << 30)
         return PQ_ERR_UNSUPPORTED;
@@ -119,6 +121,7 @@ void free_ctx(pq_attn_ctx *ctx)
     if (ctx->partials) (void)hipFree(ctx->partials);
     if (ctx->tickets) (void)hipFree(ctx->tickets);
     if (ctx->dev_err) (void)hipFree(ctx->dev_err);
+    if (ctx->scores12) (void)hipFree(ctx->scores12);
     if (ctx->stage[0]) (void)hipFree(ctx->stage[0]);
     if (ctx->stage[1]) (void)hipFree(ctx->stage[1]);
     delete ctx;
@@ -167,6 +170,19 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     ctx->elem_bytes = cfg->dtype == PQ_F16 ? 2 : 4;
     ctx->k_skew = pq_config_uses_grouped_kernel(cfg) ? PQ_K_SKEW_QUAD : PQ_K_SKEW_LANE;
     ctx->n_splits = cfg->n_splits > 0 ? cfg->n_splits : choose_splits(cfg, prop.multiProcessorCount);
+    // 12-bit contexts with few (sequence, query head) pairs decode in two passes (split by subspace group, see
+    // pq12_decode.hip): chosen when the fused kernel would need 5 or more token splits per head (measured at 32 heads x 32K: one
+    // sequence 44 against 64 us, two sequences 87 against 84 us, four 182 against 164 us), or on request
+    bool two_pass = false;
+    if (pq_config_is_12bit(cfg) && (cfg->n_splits < 0 || (cfg->n_splits == 0 && ctx->n_splits >= 5))) {
+        two_pass = true;
+        const int64_t n_bh8 = (int64_t)cfg->batch * cfg->n_q_heads * 8;
+        int64_t ts = cfg->n_splits < 0 ? -cfg->n_splits : prop.multiProcessorCount / n_bh8;
+        const int64_t by_work = ctx->cap_padded / 128 / 16;  // at least one 128-token block per wavefront
+        if (cfg->n_splits == 0 && ts > by_work)
+            ts = by_work;
+        ctx->n_splits = (int)(ts < 1 ? 1 : (ts > PQ_MAX_SPLITS ? PQ_MAX_SPLITS : ts));
+    }
 
     const size_t cb_bytes = (size_t)cfg->n_kv_heads * cfg->n_centroids * PQ_HEAD_DIM * ctx->elem_bytes;
     const size_t n_bh = (size_t)cfg->batch * cfg->n_q_heads;
@@ -176,6 +192,8 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     ok = ok && hipMalloc((void **)&ctx->partials, part_bytes) == hipSuccess;
     ok = ok && hipMalloc((void **)&ctx->tickets, n_bh * sizeof(unsigned int)) == hipSuccess;
     ok = ok && hipMalloc((void **)&ctx->dev_err, 2 * sizeof(unsigned int)) == hipSuccess;  // [1]: probe sink
+    if (two_pass)  // partial scores [B*Hq][4 groups][capacity]
+        ok = ok && hipMalloc((void **)&ctx->scores12, n_bh * 4 * (size_t)ctx->cap_padded * sizeof(float)) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
         free_ctx(ctx);
@@ -207,6 +225,8 @@ int pq_attn_destroy(pq_attn_ctx *ctx)
 }
 
 int pq_attn_n_splits(const pq_attn_ctx *ctx) { return ctx ? ctx->n_splits : PQ_ERR_NULL; }
+
+int pq_attn_n_passes(const pq_attn_ctx *ctx) { return ctx ? (ctx->scores12 ? 2 : 1) : PQ_ERR_NULL; }
 
 int pq_attn_set_codebooks(pq_attn_ctx *ctx, const void *k_codebook, const void *v_codebook, void *hip_stream)
 {

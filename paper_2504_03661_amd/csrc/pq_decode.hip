@@ -67,11 +67,16 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     if ((grid & 7u) == 0)
         logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
     const int S = a.S;
-    const int bh = (int)(logical / (uint32_t)S);
-    const int split = (int)(logical - (uint32_t)bh * (uint32_t)S);
-    const int b = (int)((uint32_t)bh / (uint32_t)a.Hq);
-    const int hq = bh - b * a.Hq;
-    const int hkv = (int)((uint32_t)hq / (uint32_t)a.G);
+    // neighbours: the splits of a (sequence, query head), the query heads of its KV group, then the same
+    // KV head of the other sequences (they load the same codebooks: once per XCD instead of once per sequence)
+    const uint32_t unit = logical / (uint32_t)S;
+    const int split = (int)(logical - unit * (uint32_t)S);
+    const uint32_t bkv = unit / (uint32_t)a.G;          // hkv * B + b
+    const int gq = (int)(unit - bkv * (uint32_t)a.G);
+    const int hkv = (int)(bkv / (uint32_t)a.B);
+    const int b = (int)(bkv - (uint32_t)hkv * (uint32_t)a.B);
+    const int hq = hkv * a.G + gq;
+    const int bh = b * a.Hq + hq;
 
     // The lengths are requested first and taken out of their registers only after the table loads
     // below have been issued.  The loads go through lane_zero(), which the compiler cannot see

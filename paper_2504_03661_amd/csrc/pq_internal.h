@@ -102,6 +102,9 @@ struct pq_attn_ctx {
     // 12-bit contexts: token-major uint16 staging of an append's codes, grown on demand
     uint16_t *stage[2];
     int64_t stage_tokens;   // tokens per (sequence, KV head) the staging buffers hold
+    // 12-bit contexts that decode in two passes: partial scores [B*Hq][4][cap_padded]; n_splits then counts the
+    // token ranges of the second pass
+    float *scores12;
 };
 
 struct pq_decode_args {

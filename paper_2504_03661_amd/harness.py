@@ -46,6 +46,7 @@ class PQSession:
             dtype=B.PQ_F16 if dtype == "f16" else B.PQ_F32, device=device, n_splits=n_splits)
         self.ctx = B.pq_attn_create(self.cfg)
         self.n_splits = B.pq_attn_n_splits(self.ctx)
+        self.n_passes = B.pq_attn_n_passes(self.ctx)
         self.codes_bytes = B.pq_attn_codes_bytes(self.cfg)
 
         self.q = _dev(data["q"], self.device)

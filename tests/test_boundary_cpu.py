@@ -56,6 +56,9 @@ def good(**kw):
     ({"n_subspaces": 16}, -3),
     ({"head_dim": 64, "n_subspaces": 32}, -3),
     ({"n_splits": 1000}, -3),
+    ({"n_splits": -1}, -2),                            # a negative split count is the 12-bit contexts' alone:
+    ({"n_centroids": 4096, "n_subspaces": 32, "n_splits": -3}, 0),      # two-pass decode with 3 token ranges
+    ({"n_centroids": 4096, "n_subspaces": 32, "n_splits": -65}, -3),
 ])
 def test_validate_config(changes, status):
     assert P.pq_attn_validate_config(good(**changes)) == status
@@ -86,6 +89,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.pq_stream_read_probe(None, None, 16, None) == -1
     assert lib.pq_attn_device_error(None, None) == -1
     assert lib.pq_attn_n_splits(None) == -1
+    assert lib.pq_attn_n_passes(None) == -1
     out = ctypes.c_void_p()
     # bad config is reported before any HIP call
     assert lib.pq_attn_create(ctypes.byref(good(batch=0).c_struct()), ctypes.byref(out)) == -2

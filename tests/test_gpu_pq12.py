@@ -104,6 +104,52 @@ def test_decode_small(case):
         assert (got[0] == 0).all()
 
 
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("ranges", [1, 3])
+def test_decode_small_two_pass(case, ranges):
+    """The same cases through the two-pass path (split by subspace group), forced by a negative split count."""
+    name, B_, Hq, Hkv, lens, rcap, _ = case
+    w = workload(name, B_, Hq, Hkv, lens, rcap)
+    data = W.generate(w)
+    if name == "edges":
+        data["recent_len"][:] = [0, 0, 3, 0, 7, 5]
+        fill = np.random.default_rng(7)
+        data["recent_k"][:] = fill.standard_normal(data["recent_k"].shape).astype(np.float16)
+        data["recent_v"][:] = fill.standard_normal(data["recent_v"].shape).astype(np.float16)
+        for b in range(B_):
+            data["recent_k"][b, :, data["recent_len"][b]:] = np.nan
+            data["recent_v"][b, :, data["recent_len"][b]:] = np.nan
+    with PQSession(data, Hq, "f16", n_splits=-ranges) as s:
+        assert s.n_passes == 2 and s.n_splits == ranges
+        for _ in range(2):                                  # twice: the tickets must be back at zero
+            out = s.decode(W.attention_scale(w))
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            check(got, oracle_out(w, data), f"{name} two-pass x{ranges}")
+    if name == "edges":
+        assert (got[0] == 0).all()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_decode_random_shapes_two_pass(seed):
+    rng = np.random.default_rng(7100 + seed)
+    B_ = int(rng.integers(1, 4))
+    Hkv = int(rng.integers(1, 3))
+    G = int(rng.choice([1, 1, 2, 4]))
+    lens = tuple(int(x) for x in rng.choice([0, 1, 127, 128, 129, 2000, 4095, 4097, 9000, 20000], size=B_))
+    rcap = int(rng.choice([0, 3, 33]))
+    ranges = int(rng.choice([1, 2, 5, 8]))
+    w = W.Workload(f"rand12tp_{seed}", B_, Hkv * G, Hkv, 128, 32, max(max(lens), 1) + int(rng.integers(0, 200)), "f16",
+                   recent_cap=rcap, recent_uniform=rcap > 0, seed=7100 + seed, ctx_lens=lens, n_centroids=4096)
+    data = W.generate(w)
+    with PQSession(data, Hkv * G, "f16", n_splits=-ranges) as s:
+        assert s.n_passes == 2
+        out = s.decode(W.attention_scale(w))
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+    check(got, oracle_out(w, data), f"B={B_} Hkv={Hkv} G={G} lens={lens} rcap={rcap} ranges={ranges}")
+
+
 @pytest.mark.parametrize("seed", range(10))
 def test_decode_random_shapes(seed):
     """Seeded random shapes: batch, grouped heads, ragged lengths around the 128-token block and the 4096-token
@@ -156,8 +202,16 @@ def test_llama2_7b_layer_shape_at_32k():
     w = W.Workload("pq12_llama2_7b_32k", 1, 32, 32, 128, 32, 32768, "f16", recent_cap=128, recent_fixed=128,
                    seed=W.BASE_SEED + 12, n_centroids=4096)
     data = W.generate(w)
+    ref = oracle_out(w, data)
     with PQSession(data, 32, "f16") as s:
+        assert s.n_passes == 2                              # few (sequence, head) pairs: split by subspace group
         out = s.decode(W.attention_scale(w))
         torch.cuda.synchronize()
         got = out.cpu().numpy()
-    check(got, oracle_out(w, data), "12-bit 32K")
+    check(got, ref, "12-bit 32K")
+    with PQSession(data, 32, "f16", n_splits=8) as s:       # the fused kernel on the same shape
+        assert s.n_passes == 1
+        out = s.decode(W.attention_scale(w))
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+    check(got, ref, "12-bit 32K, fused kernel")
