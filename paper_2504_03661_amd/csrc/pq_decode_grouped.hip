@@ -98,10 +98,12 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const int unit = (int)(logical / (uint32_t)S);
     const int split = (int)(logical - (uint32_t)unit * (uint32_t)S);
     const int n_sub = a.G / G;                     // sub-groups per KV head
-    const int bkv = (int)((uint32_t)unit / (uint32_t)n_sub);  // b * Hkv + hkv
-    const int sub_group = unit - bkv * n_sub;
-    const int b = (int)((uint32_t)bkv / (uint32_t)a.Hkv);
-    const int hkv = bkv - b * a.Hkv;
+    // ... then the same KV head of the other sequences (same codebook images: once per XCD from memory)
+    const int hb = (int)((uint32_t)unit / (uint32_t)n_sub);  // hkv * B + b
+    const int sub_group = unit - hb * n_sub;
+    const int hkv = (int)((uint32_t)hb / (uint32_t)a.B);
+    const int b = hb - hkv * a.B;
+    const int bkv = b * a.Hkv + hkv;
     const int bh0 = b * a.Hq + hkv * a.G + sub_group * G;  // first query head of this workgroup
     // The lengths are requested first and taken out of their registers only after the table loads
     // below have been issued.  The loads go through lane_zero(), which the compiler cannot see
