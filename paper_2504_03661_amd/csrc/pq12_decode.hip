@@ -33,6 +33,7 @@
 namespace {
 
 constexpr int NW12 = 16;
+constexpr int RB12 = 4;                               // recent rows a wavefront loads together
 constexpr int TAB_OFF = 0;                            // 128 KiB: score table [8][4096] fp32 / value image [4][4096][4] fp16
 constexpr int P_OFF = 131072;                         // float [16][128]: weights of the block a wavefront works on
 constexpr int Q12_OFF = P_OFF + NW12 * 512;           // float [128]: query x scale x log2(e)
@@ -307,17 +308,29 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
     {
         const float q0 = qs[2 * lane], q1 = qs[2 * lane + 1];
         const int64_t rbase = ((int64_t)b * a.Hkv + hkv) * a.max_recent;
-        for (int r = r0 + wave; r < r1; r += NW12) {
-            const __half2 kk = *((const __half2 *)((const __half *)a.recent_k + (rbase + r) * PQ_HEAD_DIM) + lane);
-            const __half2 vv = *((const __half2 *)((const __half *)a.recent_v + (rbase + r) * PQ_HEAD_DIM) + lane);
-            const float s = wave_sum(fmaf(q0, __low2float(kk), q1 * __high2float(kk)));
-            const float m_new = fmaxf(m_run, s);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            const float p = __builtin_amdgcn_exp2f(s - m_new);
-            l_lane = fmaf(l_lane, alpha, lane == 0 ? p : 0.f);
-            o0 = fmaf(o0, alpha, p * __low2float(vv));
-            o1 = fmaf(o1, alpha, p * __high2float(vv));
-            m_run = m_new;
+        // RB12 rows per trip, their loads issued together (one memory round trip per trip, not per row); rows
+        // beyond the range re-read the trip's first row and are skipped
+        for (int r = r0 + wave; r < r1; r += NW12 * RB12) {
+            __half2 kk[RB12], vv[RB12];
+#pragma unroll
+            for (int u = 0; u < RB12; ++u) {
+                const int rr = r + u * NW12 < r1 ? r + u * NW12 : r;
+                kk[u] = *((const __half2 *)((const __half *)a.recent_k + (rbase + rr) * PQ_HEAD_DIM) + lane);
+                vv[u] = *((const __half2 *)((const __half *)a.recent_v + (rbase + rr) * PQ_HEAD_DIM) + lane);
+            }
+#pragma unroll
+            for (int u = 0; u < RB12; ++u) {
+                if (r + u * NW12 < r1) {  // wave-uniform
+                    const float s = wave_sum(fmaf(q0, __low2float(kk[u]), q1 * __high2float(kk[u])));
+                    const float m_new = fmaxf(m_run, s);
+                    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                    const float p = __builtin_amdgcn_exp2f(s - m_new);
+                    l_lane = fmaf(l_lane, alpha, lane == 0 ? p : 0.f);
+                    o0 = fmaf(o0, alpha, p * __low2float(vv[u]));
+                    o1 = fmaf(o1, alpha, p * __high2float(vv[u]));
+                    m_run = m_new;
+                }
+            }
         }
     }
 
@@ -406,8 +419,9 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
 // Each code byte still comes from HBM once; the partial scores cost 16 bytes per token and query head
 // written and read back (pass 2 finds them in the memory-side cache).
 // ---------------------------------------------------------------------------------
-constexpr int W2_OFF = 131072;                 // pass 2: float [16][128] weights of the block a wavefront works on
-constexpr int Q2_OFF = W2_OFF + NW12 * 512;    // float [128]: query x scale x log2(e)
+constexpr int W2_OFF = 131072;                 // pass 2: float [16][NB2][128] weights of the blocks a wavefront works on
+constexpr int NB2 = 2;                         // pass 2: 128-token blocks a wavefront works on together
+constexpr int Q2_OFF = W2_OFF + NW12 * NB2 * 512;  // float [128]: query x scale x log2(e)
 constexpr int PART2_OFF = Q2_OFF + 512;        // pass 2: float [16][24]: maximum, weight sum, 2 unused, 16 dims
 constexpr int PART2_STRIDE = 24;
 constexpr int SMEM2_BYTES = PART2_OFF + NW12 * PART2_STRIDE * 4;
@@ -437,7 +451,38 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_scores_kernel(const pq_decode_
     const int hq = bh - b * a.Hq;
     const int hkv = (int)((uint32_t)hq / (uint32_t)a.G);
 
-    int N = a.ctx_len[b];
+    // Order of the prologue (as in the 8-bit kernels): everything that needs only the head index is requested
+    // first — the length (through an index the compiler cannot prove uniform, so that the load stays in flight
+    // instead of becoming a scalar load with a wait on the spot), the query, the first half of the codebook
+    // slice — then the length is taken out of its register, the range is cut and the first codes are requested.
+    const int zero = lane_zero();
+    const int n_vec = a.ctx_len[b + zero];
+    const __half *kcb = (const __half *)a.kcb_packed + (int64_t)hkv * PQ12_M * PQ12_CENTROIDS * 4;
+    const float q_mine = tid < PQ_HEAD_DIM ? __half2float(((const __half *)a.q)[(int64_t)bh * PQ_HEAD_DIM + tid]) : 0.f;
+    u32x4 craw[4][2];  // centroids 4 tid .. 4 tid + 3 of four subspaces, four fp16 each
+    auto load_centroids = [&](int i0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const u32x4 *src = (const u32x4 *)(kcb + ((int64_t)(8 * g + i0 + i) * PQ12_CENTROIDS + 4 * tid) * 4);
+            craw[i][0] = src[0];
+            craw[i][1] = src[1];
+        }
+    };
+    auto build_rows = [&](int i0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f32x4 q4 = *(lds_f32x4 *)(lbase + Q2_OFF + (8 * g + i0 + i) * 16);
+            f32x4 ent;
+            ent.x = dot4(q4, craw[i][0].x, craw[i][0].y);
+            ent.y = dot4(q4, craw[i][0].z, craw[i][0].w);
+            ent.z = dot4(q4, craw[i][1].x, craw[i][1].y);
+            ent.w = dot4(q4, craw[i][1].z, craw[i][1].w);
+            *(lds_f32x4 *)(lbase + TAB_OFF + ((i0 + i) * PQ12_CENTROIDS + 4 * tid) * 4) = ent;
+        }
+    };
+    load_centroids(0);
+
+    int N = __builtin_amdgcn_readfirstlane(n_vec);
     N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
     const uint32_t nvb = (uint32_t)(N + 127) >> 7;
     const int vb0 = (int)(nvb * (uint32_t)ts / (uint32_t)TS);
@@ -446,7 +491,6 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_scores_kernel(const pq_decode_
         return;  // workgroup-uniform
 
     const uint8_t *k_head = a.k_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
-    const __half *kcb = (const __half *)a.kcb_packed + (int64_t)hkv * PQ12_M * PQ12_CENTROIDS * 4;
     const uint32_t *k_units = (const uint32_t *)k_head + lane * 3;
     const int64_t cap = a.head_stride / PQ12_TOKEN_BYTES;  // tokens per row of partial scores
     float *row = scores + ((int64_t)bh * 4 + g) * cap;
@@ -467,22 +511,11 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_scores_kernel(const pq_decode_
         load_units(un[d], vb0 + wave + NW12 * d);
 
     if (tid < PQ_HEAD_DIM)
-        *(lds_f32 *)(lbase + Q2_OFF + tid * 4) =
-            __half2float(((const __half *)a.q)[(int64_t)bh * PQ_HEAD_DIM + tid]) * a.scale_log2e;
+        *(lds_f32 *)(lbase + Q2_OFF + tid * 4) = q_mine * a.scale_log2e;
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int sub = 8 * g + i;
-        const u32x4 *src = (const u32x4 *)(kcb + ((int64_t)sub * PQ12_CENTROIDS + 4 * tid) * 4);
-        const u32x4 c01 = src[0], c23 = src[1];  // centroids 4 tid .. 4 tid + 3, four fp16 each
-        const f32x4 q4 = *(lds_f32x4 *)(lbase + Q2_OFF + sub * 16);
-        f32x4 ent;
-        ent.x = dot4(q4, c01.x, c01.y);
-        ent.y = dot4(q4, c01.z, c01.w);
-        ent.z = dot4(q4, c23.x, c23.y);
-        ent.w = dot4(q4, c23.z, c23.w);
-        *(lds_f32x4 *)(lbase + TAB_OFF + (i * PQ12_CENTROIDS + 4 * tid) * 4) = ent;
-    }
+    build_rows(0);
+    load_centroids(4);
+    build_rows(4);
     __syncthreads();
 
     for (int vb = vb0 + wave; vb < vb1;) {
@@ -524,8 +557,24 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_values_kernel(const pq_decode_
     const int hq = bh - b * a.Hq;
     const int hkv = (int)((uint32_t)hq / (uint32_t)a.G);
 
-    int N = a.ctx_len[b];
-    int R = (a.recent_k != nullptr && a.recent_len != nullptr) ? a.recent_len[b] : 0;
+    // Order of the prologue: lengths (kept in flight, see pass 1), the table slice and the query are requested
+    // first; then the range is cut, and this wavefront's first recent rows and code blocks are requested.
+    const int zero = lane_zero();
+    const bool has_recent = a.recent_k != nullptr && a.recent_len != nullptr;
+    const int n_vec = a.ctx_len[b + zero];
+    const int r_vec = (has_recent ? a.recent_len : a.ctx_len)[b + zero];
+    const __half *vcb = (const __half *)a.vcb_packed + (int64_t)hkv * PQ12_M * PQ12_CENTROIDS * 4;
+    u32x4 raw[8];
+    {
+        const u32x4 *src = (const u32x4 *)(vcb + (int64_t)(4 * g) * PQ12_CENTROIDS * 4);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            raw[k] = src[tid + k * (NW12 * 64)];
+    }
+    const float q_mine = tid < PQ_HEAD_DIM ? __half2float(((const __half *)a.q)[(int64_t)bh * PQ_HEAD_DIM + tid]) : 0.f;
+
+    int N = __builtin_amdgcn_readfirstlane(n_vec);
+    int R = has_recent ? __builtin_amdgcn_readfirstlane(r_vec) : 0;
     N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
     R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
     const uint32_t nvb = (uint32_t)(N + 127) >> 7;
@@ -535,15 +584,30 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_values_kernel(const pq_decode_
     const int r1 = (int)((uint32_t)R * (uint32_t)(ts + 1) / (uint32_t)TS);
 
     const uint8_t *v_head = a.v_codes + ((int64_t)b * a.Hkv + hkv) * a.head_stride;
-    const __half *vcb = (const __half *)a.vcb_packed + (int64_t)hkv * PQ12_M * PQ12_CENTROIDS * 4;
     const uint32_t *v_units = (const uint32_t *)v_head + lane * 3;
     const int64_t cap = a.head_stride / PQ12_TOKEN_BYTES;
     const float *rows = scores + (int64_t)bh * 4 * cap;
+    const int64_t rbase = ((int64_t)b * a.Hkv + hkv) * a.max_recent;
 
-    // the first blocks' partial scores and codes are requested before the table is copied
+    // recent rows of this wavefront: RB12 per trip, their loads issued together; rows beyond the range re-read
+    // the trip's first row and are skipped.  The first trip's rows are requested here, behind the table.
+    __half2 kk[RB12];
+    float vv[RB12];
+    auto load_recent = [&](int r) {
+#pragma unroll
+        for (int u = 0; u < RB12; ++u) {
+            const int rr = r + u * NW12 < r1 ? r + u * NW12 : r;
+            kk[u] = *((const __half2 *)((const __half *)a.recent_k + (rbase + rr) * PQ_HEAD_DIM) + lane);
+            vv[u] = lane < 16 ? __half2float(((const __half *)a.recent_v)[(rbase + rr) * PQ_HEAD_DIM + 16 * g + lane]) : 0.f;
+        }
+    };
+    if (r0 + wave < r1)
+        load_recent(r0 + wave);
+
+    // the first blocks' partial scores and codes
     const int last_vb = vb1 > vb0 ? vb1 - 1 : 0;
-    float sc[PF2][8];
-    uint32_t un[PF2][3];
+    float sc[NB2][8];
+    uint32_t un[NB2][3];
     auto load_block = [&](float (&scd)[8], uint32_t (&und)[3], int vb_want) {
         const int vb = vb_want < last_vb ? vb_want : last_vb;
 #pragma unroll
@@ -558,85 +622,122 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_values_kernel(const pq_decode_
     };
     if (vb1 > vb0) {
 #pragma unroll
-        for (int d = 0; d < PF2; ++d)
-            load_block(sc[d], un[d], vb0 + wave + NW12 * d);
+        for (int e = 0; e < NB2; ++e)
+            load_block(sc[e], un[e], vb0 + wave + NW12 * e);
     }
 
     if (tid < PQ_HEAD_DIM)
-        *(lds_f32 *)(lbase + Q2_OFF + tid * 4) =
-            __half2float(((const __half *)a.q)[(int64_t)bh * PQ_HEAD_DIM + tid]) * a.scale_log2e;
-    {
-        const u32x4 *src = (const u32x4 *)(vcb + (int64_t)(4 * g) * PQ12_CENTROIDS * 4);
-        u32x4 raw[8];
+        *(lds_f32 *)(lbase + Q2_OFF + tid * 4) = q_mine * a.scale_log2e;
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-            raw[k] = src[tid + k * (NW12 * 64)];
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            *(lds_u32x4 *)(lbase + TAB_OFF + (tid + k * (NW12 * 64)) * 16) = raw[k];
-    }
+    for (int k = 0; k < 8; ++k)
+        *(lds_u32x4 *)(lbase + TAB_OFF + (tid + k * (NW12 * 64)) * 16) = raw[k];
     __syncthreads();
 
     float m_run = NEG_BIG;  // this wavefront's reference maximum
     float l_lane = 0.f;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    lds_f32 *pline = (lds_f32 *)(lbase + W2_OFF) + wave * 128;
-    for (int vb = vb0 + wave; vb < vb1;) {
+    // ---------------- recent full-precision rows of this token range first (their data arrived with the table):
+    // every group scores them, each adds its own dims; lane l < 16 owns dim 16 g + l
+    float o_rec = 0.f;
+    {
+        const float q0 = *(lds_f32 *)(lbase + Q2_OFF + lane * 8), q1 = *(lds_f32 *)(lbase + Q2_OFF + lane * 8 + 4);
+        for (int r = r0 + wave; r < r1; r += NW12 * RB12) {
 #pragma unroll
-        for (int d = 0; d < PF2; ++d) {
-            if (vb < vb1) {  // wave-uniform
-                float s[2], p[2];
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const bool valid = vb * 128 + 64 * h + lane < N;
-                    s[h] = valid ? (sc[d][h] + sc[d][2 + h]) + (sc[d][4 + h] + sc[d][6 + h]) : NEG_BIG;
-                }
-                // the reference maximum moves only when a score exceeds it by more than 8 (2^8 in weight)
-                const float smax = fmaxf(s[0], s[1]);
-                if (__builtin_amdgcn_ballot_w64(smax > m_run + 8.0f) != 0) {  // wave-uniform
-                    const float m_new = fmaxf(m_run, wave_max(smax));
+            for (int u = 0; u < RB12; ++u) {
+                if (r + u * NW12 < r1) {  // wave-uniform
+                    const float sr = wave_sum(fmaf(q0, __low2float(kk[u]), q1 * __high2float(kk[u])));
+                    const float m_new = fmaxf(m_run, sr);
                     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-                    l_lane *= alpha;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[j] *= alpha;
+                    const float pr = __builtin_amdgcn_exp2f(sr - m_new);
+                    l_lane = fmaf(l_lane, alpha, lane == 0 ? pr : 0.f);
+                    o_rec = fmaf(o_rec, alpha, pr * vv[u]);
                     m_run = m_new;
                 }
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    p[h] = s[h] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(s[h] - m_run) : 0.f;
-                    l_lane += p[h];
-                }
-                __builtin_amdgcn_wave_barrier();
-                pline[lane] = p[0];
-                pline[64 + lane] = p[1];
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                uint32_t c[8];
-                unpack8(un[d][0], un[d][1], un[d][2], c);
-                load_block(sc[d], un[d], vb + NW12 * PF2);
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    const float pk = pline[(lane >> 2) + 16 * k];
-                    const u32x2 cv = *(lds_u32x2 *)(lbase + TAB_OFF + ((lane & 3) * PQ12_CENTROIDS + c[k]) * 8);
-                    const uint32_t lo = cv.x, hi = cv.y;
-                    const __half2 h0 = *(const __half2 *)&lo, h1 = *(const __half2 *)&hi;
-                    acc[0] = fmaf(pk, __low2float(h0), acc[0]);
-                    acc[1] = fmaf(pk, __high2float(h0), acc[1]);
-                    acc[2] = fmaf(pk, __low2float(h1), acc[2]);
-                    acc[3] = fmaf(pk, __high2float(h1), acc[3]);
-                }
-                vb += NW12;
             }
+            if (r + NW12 * RB12 < r1)
+                load_recent(r + NW12 * RB12);
         }
+    }
+    float acc[NB2][4];
+#pragma unroll
+    for (int e = 0; e < NB2; ++e)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[e][j] = 0.f;
+    lds_f32 *pline = (lds_f32 *)(lbase + W2_OFF) + wave * (NB2 * 128);
+    // A wavefront takes NB2 blocks per trip (vb, vb + 16, ...) and works on them together: their gathers and
+    // multiply-adds are independent, which hides the LDS latency that one block at a time leaves exposed.  A
+    // block beyond the range counts as empty (its loads re-read the last block).
+    for (int vb = vb0 + wave; vb < vb1; vb += NW12 * NB2) {
+        float s[NB2][2], p[NB2][2];
+        float smax = NEG_BIG;
+#pragma unroll
+        for (int e = 0; e < NB2; ++e)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int vbe = vb + NW12 * e;
+                const bool valid = vbe < vb1 && vbe * 128 + 64 * h + lane < N;
+                s[e][h] = valid ? (sc[e][h] + sc[e][2 + h]) + (sc[e][4 + h] + sc[e][6 + h]) : NEG_BIG;
+                smax = fmaxf(smax, s[e][h]);
+            }
+        // the registers of this trip's loads are free again: request the next trip's blocks now, a whole trip ahead
+        uint32_t c[NB2][8];
+#pragma unroll
+        for (int e = 0; e < NB2; ++e) {
+            unpack8(un[e][0], un[e][1], un[e][2], c[e]);
+            load_block(sc[e], un[e], vb + NW12 * (NB2 + e));
+        }
+        // the reference maximum moves only when a score exceeds it by more than 8 (2^8 in weight)
+        if (__builtin_amdgcn_ballot_w64(smax > m_run + 8.0f) != 0) {  // wave-uniform
+            const float m_new = fmaxf(m_run, wave_max(smax));
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            l_lane *= alpha;
+            o_rec *= alpha;
+#pragma unroll
+            for (int e = 0; e < NB2; ++e)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[e][j] *= alpha;
+            m_run = m_new;
+        }
+#pragma unroll
+        for (int e = 0; e < NB2; ++e)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                p[e][h] = s[e][h] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(s[e][h] - m_run) : 0.f;
+                l_lane += p[e][h];
+            }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int e = 0; e < NB2; ++e) {
+            pline[e * 128 + lane] = p[e][0];
+            pline[e * 128 + 64 + lane] = p[e][1];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+#pragma unroll
+            for (int e = 0; e < NB2; ++e) {
+                const float pk = pline[e * 128 + (lane >> 2) + 16 * k];
+                const u32x2 cv = *(lds_u32x2 *)(lbase + TAB_OFF + ((lane & 3) * PQ12_CENTROIDS + c[e][k]) * 8);
+                const uint32_t lo = cv.x, hi = cv.y;
+                const __half2 h0 = *(const __half2 *)&lo, h1 = *(const __half2 *)&hi;
+                acc[e][0] = fmaf(pk, __low2float(h0), acc[e][0]);
+                acc[e][1] = fmaf(pk, __high2float(h0), acc[e][1]);
+                acc[e][2] = fmaf(pk, __low2float(h1), acc[e][2]);
+                acc[e][3] = fmaf(pk, __high2float(h1), acc[e][3]);
+            }
     }
 
     // ---------------- sum the 16 token streams (lanes with equal lane % 4); then lane l < 16 owns dim 16 g + l
     lds_f32 *part = (lds_f32 *)(lbase + PART2_OFF) + wave * PART2_STRIDE;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        float v = acc[j];
+        float v = acc[0][j];
+#pragma unroll
+        for (int e = 1; e < NB2; ++e)
+            v += acc[e][j];
         v += __shfl_xor(v, 4);
         v += __shfl_xor(v, 8);
         v += __shfl_xor(v, 16);
@@ -647,25 +748,7 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_values_kernel(const pq_decode_
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    float o = lane < 16 ? part[4 + lane] : 0.f;
-
-    // ---------------- recent full-precision rows of this token range: every group scores them, each adds its dims
-    {
-        const float q0 = *(lds_f32 *)(lbase + Q2_OFF + lane * 8), q1 = *(lds_f32 *)(lbase + Q2_OFF + lane * 8 + 4);
-        const int64_t rbase = ((int64_t)b * a.Hkv + hkv) * a.max_recent;
-        for (int r = r0 + wave; r < r1; r += NW12) {
-            const __half2 kk = *((const __half2 *)((const __half *)a.recent_k + (rbase + r) * PQ_HEAD_DIM) + lane);
-            const float vv =
-                lane < 16 ? __half2float(((const __half *)a.recent_v)[(rbase + r) * PQ_HEAD_DIM + 16 * g + lane]) : 0.f;
-            const float sr = wave_sum(fmaf(q0, __low2float(kk), q1 * __high2float(kk)));
-            const float m_new = fmaxf(m_run, sr);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            const float pr = __builtin_amdgcn_exp2f(sr - m_new);
-            l_lane = fmaf(l_lane, alpha, lane == 0 ? pr : 0.f);
-            o = fmaf(o, alpha, pr * vv);
-            m_run = m_new;
-        }
-    }
+    const float o = (lane < 16 ? part[4 + lane] : 0.f) + o_rec;
     {
         const float l_w = wave_sum(l_lane);
         if (lane == 0) {

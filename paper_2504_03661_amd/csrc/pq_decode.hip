@@ -357,24 +357,39 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         // token stream of the value pass and are merged below)
         const bool owner = (M == 64) || lane < 32;
         const int64_t rbase = ((int64_t)b * a.Hkv + hkv) * a.max_recent;
-        for (int r = r0 + wave; r < r1; r += NW) {
-            float kv[DS], vv[DS];
-            float dot = 0.f;
+        // RB rows per trip: their loads go out together, so a wavefront with many rows (one split per head,
+        // a few hundred recent rows) pays one memory round trip per RB rows instead of one per row.  Rows
+        // beyond the range re-read the trip's first row and are skipped.
+        constexpr int RB = 4;
+        for (int r = r0 + wave; r < r1; r += NW * RB) {
+            float kv[RB][DS], vv[RB][DS];
 #pragma unroll
-            for (int j = 0; j < DS; ++j) {
-                kv[j] = owner ? elem<T>::ld(a.recent_k, (rbase + r) * PQ_HEAD_DIM + sub * DS + j) : 0.f;
-                vv[j] = owner ? elem<T>::ld(a.recent_v, (rbase + r) * PQ_HEAD_DIM + sub * DS + j) : 0.f;
-                dot = fmaf(qs[j], kv[j], dot);
+            for (int u = 0; u < RB; ++u) {
+                const int rr = r + u * NW < r1 ? r + u * NW : r;
+#pragma unroll
+                for (int j = 0; j < DS; ++j) {
+                    kv[u][j] = owner ? elem<T>::ld(a.recent_k, (rbase + rr) * PQ_HEAD_DIM + sub * DS + j) : 0.f;
+                    vv[u][j] = owner ? elem<T>::ld(a.recent_v, (rbase + rr) * PQ_HEAD_DIM + sub * DS + j) : 0.f;
+                }
             }
-            const float s = wave_sum(dot);
-            const float m_new = fmaxf(m_run, s);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            const float p = __builtin_amdgcn_exp2f(s - m_new);
-            l_lane = fmaf(l_lane, alpha, lane == 0 ? p : 0.f);
 #pragma unroll
-            for (int j = 0; j < DS; ++j)
-                acc[j] = fmaf(acc[j], alpha, p * vv[j]);
-            m_run = m_new;
+            for (int u = 0; u < RB; ++u) {
+                if (r + u * NW < r1) {  // wave-uniform
+                    float dot = 0.f;
+#pragma unroll
+                    for (int j = 0; j < DS; ++j)
+                        dot = fmaf(qs[j], kv[u][j], dot);
+                    const float s = wave_sum(dot);
+                    const float m_new = fmaxf(m_run, s);
+                    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                    const float p = __builtin_amdgcn_exp2f(s - m_new);
+                    l_lane = fmaf(l_lane, alpha, lane == 0 ? p : 0.f);
+#pragma unroll
+                    for (int j = 0; j < DS; ++j)
+                        acc[j] = fmaf(acc[j], alpha, p * vv[u][j]);
+                    m_run = m_new;
+                }
+            }
         }
     }
 

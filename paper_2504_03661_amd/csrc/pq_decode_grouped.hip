@@ -306,24 +306,37 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     // ---------------- recent full-precision rows of this split, all heads of the group
     {
         const int64_t rbase = (int64_t)bkv * a.max_recent;
-        for (int r = r0 + wave; r < r1; r += NW) {
-            const uint32_t kw = *((const uint32_t *)((const __half *)a.recent_k + (rbase + r) * PQ_HEAD_DIM) + lane);
-            const uint32_t vw = *((const uint32_t *)((const __half *)a.recent_v + (rbase + r) * PQ_HEAD_DIM) + lane);
-            const __half2 kh = *(const __half2 *)&kw, vh = *(const __half2 *)&vw;
-            const float k0 = __low2float(kh), k1 = __high2float(kh), v0 = __low2float(vh), v1 = __high2float(vh);
+        // RBG rows per trip, their loads issued together (one memory round trip per trip, not per row); rows
+        // beyond the range re-read the trip's first row and are skipped
+        constexpr int RBG = 4;
+        for (int r = r0 + wave; r < r1; r += NW * RBG) {
+            uint32_t kw[RBG], vw[RBG];
 #pragma unroll
-            for (int g = 0; g < GMAX; ++g) {
-                // this lane's dims (2 lane, 2 lane + 1) of head g's query
-                const uint32_t qw = *(lds_u32 *)(lbase + Q_OFF + q_row(g) + lane * 4);
-                const __half2 qh = *(const __half2 *)&qw;
-                const float s = wave_sum(fmaf(__low2float(qh), k0, __high2float(qh) * k1)) * a.scale_log2e;
-                const float m_new = fmaxf(m_run[g], s);
-                const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_new);
-                const float p = __builtin_amdgcn_exp2f(s - m_new);
-                l_lane[g] = fmaf(l_lane[g], alpha, lane == 0 ? p : 0.f);
-                accx[g] = fmaf(accx[g], alpha, p * v0);
-                accy[g] = fmaf(accy[g], alpha, p * v1);
-                m_run[g] = m_new;
+            for (int u = 0; u < RBG; ++u) {
+                const int rr = r + u * NW < r1 ? r + u * NW : r;
+                kw[u] = *((const uint32_t *)((const __half *)a.recent_k + (rbase + rr) * PQ_HEAD_DIM) + lane);
+                vw[u] = *((const uint32_t *)((const __half *)a.recent_v + (rbase + rr) * PQ_HEAD_DIM) + lane);
+            }
+#pragma unroll
+            for (int u = 0; u < RBG; ++u) {
+                if (r + u * NW < r1) {  // wave-uniform
+                    const __half2 kh = *(const __half2 *)&kw[u], vh = *(const __half2 *)&vw[u];
+                    const float k0 = __low2float(kh), k1 = __high2float(kh), v0 = __low2float(vh), v1 = __high2float(vh);
+#pragma unroll
+                    for (int g = 0; g < GMAX; ++g) {
+                        // this lane's dims (2 lane, 2 lane + 1) of head g's query
+                        const uint32_t qw = *(lds_u32 *)(lbase + Q_OFF + q_row(g) + lane * 4);
+                        const __half2 qh = *(const __half2 *)&qw;
+                        const float s = wave_sum(fmaf(__low2float(qh), k0, __high2float(qh) * k1)) * a.scale_log2e;
+                        const float m_new = fmaxf(m_run[g], s);
+                        const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_new);
+                        const float p = __builtin_amdgcn_exp2f(s - m_new);
+                        l_lane[g] = fmaf(l_lane[g], alpha, lane == 0 ? p : 0.f);
+                        accx[g] = fmaf(accx[g], alpha, p * v0);
+                        accy[g] = fmaf(accy[g], alpha, p * v1);
+                        m_run[g] = m_new;
+                    }
+                }
             }
         }
     }
