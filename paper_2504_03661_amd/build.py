@@ -12,9 +12,11 @@ HEADERS = [os.path.join(CSRC, "pq_internal.h"), os.path.join(CSRC, "pq_device_ut
            os.path.join(ROOT, "include", "pq_attn.h")]
 
 # packed-fp32 instructions are switched off for all device code; -ffp-contract=off keeps
-# the encode distances as separately rounded IEEE operations.
+# the encode distances as separately rounded IEEE operations; matrix instructions write their
+# results to ordinary vector registers (the kernels consume them with vector instructions at once:
+# accumulation registers would cost one move per value).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form",
          "-Wall", "-Wno-unused-result", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 

@@ -90,6 +90,257 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void pq_encode_kernel(const pq_enco
     }
 }
 
+// ---------------------------------------------------------------------------------
+// fp16 inputs: the same codes, found with the matrix cores as a filter.
+//
+// With q(c) = n(c)/2 - x . c (n = |c|^2) the distance is |x|^2 + 2 q, so the nearest centroid minimises q.
+// For fp16 inputs every product x_j c_j is exact in fp32, and v_mfma_f32_4x4x4_16B_f16 evaluates
+// v(c) = q(c) + off for 4 centroids (rows of A, from LDS) x 64 tokens (columns of B, one per lane) per
+// instruction, to within a bound e that follows from the magnitudes (below); off >= |x|^2/2 + e is a
+// per-token constant in the C operand that makes every computed value positive, so that values compare
+// as integers (v_min3_i32: half a vector operation per value, no NaN quieting).  That is a filter, not the
+// decision:
+//   pass 1  best = min over all 256 centroids of the computed v;
+//   pass 2  the same products again; a group of 4 centroids is a candidate when its smallest computed v is
+//           <= best + tau; count the candidate groups, remember the first and the last;
+//   refine  one or two candidate groups (nearly always): the true minimiser is among their centroids — the
+//           distances of those 4 or 8 are evaluated in the defining fp64 arithmetic (see the top of this file),
+//           ascending, and the smallest, lowest index first, is the code.  Otherwise (three or more groups
+//           within tau: duplicated centroids, near-ties; subnormal or out-of-range inputs) the 64-token chunk
+//           runs the full fp64 scan.
+// Either way the code is decided by the fp64 expression, so it is bit-exact by construction; the filter only
+// has to be SAFE: every centroid outside the candidate groups must have a strictly larger true distance.  With
+// |computed - true| <= e for every centroid and c^ the minimiser of the computed values, a centroid c outside
+// the candidate groups has true v(c) > best + tau - e and true v(c^) <= best + e: tau >= 2 e suffices.
+// Bound on e: A row = (c_0 .. c_{ds-1}, h, l) with h + l = n/2 split into two fp16 (n summed in fp32 from
+// exact squares: <= 2^-21.2 n/2 in all), B column = (-x_0 .. -x_{ds-1}, 1, 1); fp32 accumulation of at most 7
+// terms, even if every one of the 6 adds truncates, <= 6 x 2^-23 T with T = N + X C + off >= the sum of the
+// terms' magnitudes (N = max n/2, C = max |c_j|, X = sum_j |x_j|).  So e <= 2^-19.7 T, and
+// tau = 2^-18.3 T + 2^-22 leaves a factor 1.3 beyond the worst case (2.6 if the adds round to nearest), which
+// is many orders above the rounding of the fp64 distances themselves.
+// The matrix instruction takes fp16 subnormals as they are (no flush: measured, and the default mode of a HIP
+// kernel); n/2 beyond the fp16 range does not split into h + l: such a codebook takes the full scan.
+// Cost per (sub-vector, centroid): about 2 vector operations instead of 2 ds + 3 in fp64.
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4e __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2e __attribute__((ext_vector_type(2)));
+
+__device__ inline float wave_max_f(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+
+__device__ inline int min4_bits(const f32x4e d)
+{
+    const int a = __float_as_int(d[0]), b = __float_as_int(d[1]), c = __float_as_int(d[2]), e = __float_as_int(d[3]);
+    const int ab = a < b ? a : b, ce = c < e ? c : e;
+    return ab < ce ? ab : ce;
+}
+
+template <int M, int DS, int NQ>
+__global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args a)
+{
+#pragma clang fp contract(off)
+    constexpr int ROW = DS == 2 ? 8 : 16;  // bytes of an A row: ds centroid coordinates, h, l (, 0, 0)
+    __shared__ __attribute__((aligned(16))) unsigned char arow[256 * ROW];
+    __shared__ double cb[256 * DS];
+
+    const int lane = threadIdx.x;
+    const int which = blockIdx.z;  // 0: keys, 1: values
+    const int i = blockIdx.y;      // subspace
+    const int n_tok = a.B * a.n_new;  // tokens of one KV head over all sequences: they share its codebook
+    const int n_chunks = (n_tok + 64 * NQ - 1) / (64 * NQ);
+    const int hkv = blockIdx.x / n_chunks;
+    const int chunk = blockIdx.x - hkv * n_chunks;
+
+    // ---- codebook of this subspace: fp64 copy for the exact evaluations, A rows for the filter
+    const __half *src = (const __half *)a.codebook[which] + ((int64_t)hkv * M + i) * 256 * DS;
+    float n_max = 0.f, c_max = 0.f;
+    bool cb_bad = false;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int c = lane + 64 * r;
+        float n = 0.f;
+        _Float16 row[ROW / 2];
+#pragma unroll
+        for (int j = 0; j < DS; ++j) {
+            const _Float16 v = __builtin_bit_cast(_Float16, src[c * DS + j]);
+            const float f = (float)v;
+            cb[c * DS + j] = (double)f;
+            row[j] = v;
+            n += f * f;  // exact squares; the sum is rounded (covered by the bound)
+            c_max = fmaxf(c_max, fabsf(f));
+        }
+        const float h = 0.5f * n;
+        const _Float16 hh = (_Float16)h;
+        const _Float16 hl = (_Float16)(h - (float)hh);
+        row[DS] = hh;
+        row[DS + 1] = hl;
+        if (DS == 4)
+            row[6] = row[7] = (_Float16)0.f;
+        cb_bad |= !(h < 60000.f);
+        n_max = fmaxf(n_max, h);
+        __builtin_memcpy(arow + c * ROW, row, ROW);
+    }
+    n_max = wave_max_f(n_max);
+    c_max = wave_max_f(c_max);
+    cb_bad = __builtin_amdgcn_ballot_w64(cb_bad) != 0;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+    // ---- this lane's tokens: one per 64-token sub-chunk
+    bool live[NQ], bad[NQ];
+    int bq[NQ], tq[NQ];
+    double xd[NQ][DS];
+    f16x4 bop[NQ];
+    f32x4e off4[NQ];
+    float tau[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int u = (chunk * NQ + q) * 64 + lane;
+        live[q] = u < n_tok;
+        const int uu = live[q] ? u : 0;
+        bq[q] = uu / a.n_new;
+        tq[q] = uu - bq[q] * a.n_new;
+        const __half *xp =
+            (const __half *)a.x[which] + (((int64_t)bq[q] * a.Hkv + hkv) * a.n_new + tq[q]) * PQ_HEAD_DIM + i * DS;
+        float x1 = 0.f, x2 = 0.f;
+        bad[q] = cb_bad;
+        _Float16 xv[4] = {(_Float16)1.f, (_Float16)1.f, (_Float16)1.f, (_Float16)1.f};
+#pragma unroll
+        for (int j = 0; j < DS; ++j) {
+            const _Float16 v = __builtin_bit_cast(_Float16, xp[j]);
+            const float f = (float)v;
+            xd[q][j] = (double)f;
+            xv[j] = -v;
+            x1 += fabsf(f);
+            x2 += f * f;
+        }
+        bop[q] = f16x4{xv[0], xv[1], xv[2], xv[3]};
+        {
+            // keep the negated operand in its registers (the compiler otherwise redoes the negation per use)
+            u32x2e w = __builtin_bit_cast(u32x2e, bop[q]);
+            asm volatile("" : "+v"(w));
+            bop[q] = __builtin_bit_cast(f16x4, w);
+        }
+        // off: |x|^2/2 with half a per cent on top, plus the same again as tau and a floor, so that every
+        // computed value stays above zero; T = N + X C + off; tau = 2^-18.3 T + 2^-22
+        const float t0 = n_max + x1 * c_max + 0.5025f * x2;
+        float off = 0.5025f * x2 + 2.0f * (3.1e-06f * (2.0f * t0) + 2.4e-07f);
+        tau[q] = 3.1e-06f * (t0 + off) + 2.4e-07f;
+        off += tau[q];
+        off4[q] = f32x4e{off, off, off, off};
+        bad[q] |= !(off < 1.0e30f);
+    }
+    const f16x4 ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)0.f, (_Float16)0.f};
+    const unsigned char *my_row = arow + (lane & 3) * ROW;
+    auto values = [&](int m, int q) -> f32x4e {
+        if (DS == 2) {
+            const f16x4 A = *(const f16x4 *)(my_row + m * (4 * ROW));
+            return __builtin_amdgcn_mfma_f32_4x4x4f16(A, bop[q], off4[q], 0, 0, 0);
+        }
+        const f16x4 A1 = *(const f16x4 *)(my_row + m * (4 * ROW));
+        const f16x4 A2 = *(const f16x4 *)(my_row + m * (4 * ROW) + 8);
+        return __builtin_amdgcn_mfma_f32_4x4x4f16(A2, ones, __builtin_amdgcn_mfma_f32_4x4x4f16(A1, bop[q], off4[q], 0, 0, 0), 0, 0, 0);
+    };
+
+    // ---- pass 1: smallest computed value per token (positive floats order like their bit patterns)
+    int best[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+        best[q] = 0x7f800000;
+    for (int m = 0; m < 64; ++m) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const f32x4e d = values(m, q);
+            best[q] = min(min(best[q], __float_as_int(d[0])), __float_as_int(d[1]));
+            best[q] = min(min(best[q], __float_as_int(d[2])), __float_as_int(d[3]));
+        }
+    }
+    // ---- pass 2: candidate groups, one bit per group
+    uint32_t cand_lo[NQ], cand_hi[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const float b = __int_as_float(best[q]);
+        bad[q] |= !(b > 0.f && b < 1.0e30f);                   // the offset did not keep the values positive and finite
+        best[q] = __float_as_int(b + tau[q]);
+        cand_lo[q] = 0u;
+        cand_hi[q] = 0u;
+    }
+#pragma unroll 4
+    for (int m = 0; m < 32; ++m) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const f32x4e d = values(m, q);
+            const int m4 = min(min(__float_as_int(d[0]), __float_as_int(d[1])), min(__float_as_int(d[2]), __float_as_int(d[3])));
+            cand_lo[q] |= m4 <= best[q] ? 1u << m : 0u;
+        }
+    }
+#pragma unroll 4
+    for (int m = 0; m < 32; ++m) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const f32x4e d = values(m + 32, q);
+            const int m4 = min(min(__float_as_int(d[0]), __float_as_int(d[1])), min(__float_as_int(d[2]), __float_as_int(d[3])));
+            cand_hi[q] |= m4 <= best[q] ? 1u << m : 0u;
+        }
+    }
+    int cnt[NQ], first[NQ], last[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const uint64_t cand = ((uint64_t)cand_hi[q] << 32) | cand_lo[q];
+        cnt[q] = __builtin_popcountll(cand);
+        first[q] = cand ? __builtin_ctzll(cand) : 0;
+        last[q] = cand ? 63 - __builtin_clzll(cand) : 0;
+    }
+
+    // ---- refine / full scan, store
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        int code = 0;
+        double bd = __builtin_huge_val();
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {  // ascending centroid index: first group, then last group (the same if one)
+            const int c = 4 * (k < 4 ? first[q] : last[q]) + (k & 3);
+            double dist = 0.0;
+#pragma unroll
+            for (int j = 0; j < DS; ++j) {
+                const double diff = xd[q][j] - cb[c * DS + j];
+                dist = __builtin_fma(diff, diff, dist);
+            }
+            code = dist < bd ? c : code;  // strict: the lowest index among equal distances stays
+            bd = __builtin_fmin(bd, dist);
+        }
+        const bool unsure = live[q] && (bad[q] || cnt[q] < 1 || cnt[q] > 2);
+        if (__builtin_amdgcn_ballot_w64(unsure) != 0) {  // wave-uniform: the defining scan for this sub-chunk
+            code = 0;
+            bd = __builtin_huge_val();
+            for (int c = 0; c < 256; ++c) {
+                double dist = 0.0;
+#pragma unroll
+                for (int j = 0; j < DS; ++j) {
+                    const double diff = xd[q][j] - cb[c * DS + j];
+                    dist = __builtin_fma(diff, diff, dist);
+                }
+                code = dist < bd ? c : code;
+                bd = __builtin_fmin(bd, dist);
+            }
+        }
+        int n_old = a.ctx_len[bq[q]];
+        n_old = n_old < 0 ? 0 : n_old;
+        const int64_t pos = (int64_t)n_old + tq[q];
+        if (live[q] && pos < a.max_context) {
+            uint8_t *dst = a.codes[which] + ((int64_t)bq[q] * a.Hkv + hkv) * a.head_stride;
+            const int64_t off = which == 0 ? pq_k_code_offset(pos, i, M, a.k_skew) : pq_v_code_offset(pos, i, M);
+            dst[off] = (uint8_t)code;
+        }
+    }
+}
+
 __global__ void pq_bump_len_kernel(int32_t *ctx_len, int B, int n_new, int max_context, unsigned int *dev_err)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -121,14 +372,32 @@ hipError_t pq_launch_bump_len(int32_t *ctx_len, int B, int n_new, int max_contex
     return hipGetLastError();
 }
 
+template <int M, int DS>
+void launch_fast(const pq_encode_args &a, hipStream_t s)
+{
+    const int n_tok = a.B * a.n_new;
+    if (n_tok > 128) {
+        dim3 grid(a.Hkv * ((n_tok + 255) / 256), M, 2);
+        hipLaunchKernelGGL((pq_encode_fast_kernel<M, DS, 4>), grid, dim3(64), 0, s, a);
+    } else if (n_tok > 64) {
+        dim3 grid(a.Hkv, M, 2);
+        hipLaunchKernelGGL((pq_encode_fast_kernel<M, DS, 2>), grid, dim3(64), 0, s, a);
+    } else {
+        dim3 grid(a.Hkv, M, 2);
+        hipLaunchKernelGGL((pq_encode_fast_kernel<M, DS, 1>), grid, dim3(64), 0, s, a);
+    }
+}
+
 hipError_t pq_launch_encode(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len, unsigned int *dev_err,
                             hipStream_t s)
 {
     const bool f16 = ctx->cfg.dtype == PQ_F16;
+    // the filter kernel indexes the tokens of a head over all sequences with 32 bits
+    const bool fast = f16 && (int64_t)a.B * a.n_new < ((int64_t)1 << 30);
     if (ctx->cfg.n_subspaces == 64) {
-        if (f16) launch<64, 2, __half>(a, s); else launch<64, 2, float>(a, s);
+        if (fast) launch_fast<64, 2>(a, s); else if (f16) launch<64, 2, __half>(a, s); else launch<64, 2, float>(a, s);
     } else {
-        if (f16) launch<32, 4, __half>(a, s); else launch<32, 4, float>(a, s);
+        if (fast) launch_fast<32, 4>(a, s); else if (f16) launch<32, 4, __half>(a, s); else launch<32, 4, float>(a, s);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)

@@ -297,6 +297,59 @@ def test_bulk_encode_at_prefill_shape_is_bit_exact():
             np.testing.assert_array_equal(s.unpack(PQ_CODES_V, 3000), O.encode(data["new_v"], data["v_codebook"]))
 
 
+@pytest.mark.parametrize("M", [64, 32])
+@pytest.mark.parametrize("B_,n_new", [(1, 1), (3, 20), (2, 50), (2, 200), (5, 333)])
+def test_encode_filter_paths_are_bit_exact(M, B_, n_new):
+    """fp16 encode = matrix-core filter + fp64 decision: every way through it gives the oracle's codes — ties inside
+    one group of 4 centroids, across two groups, across three and more (full scan), clusters of near-ties far
+    below the filter's resolution, subnormal and zero inputs, a codebook whose norms leave the fp16 range (full
+    scan), tokens that are far outliers; token counts per head that take the 1-, 2- and 4-chunk instantiations."""
+    ds = 128 // M
+    w = W.Workload("filt", B_, 4, 2, 128, M, n_new + 3, "f16", n_new=n_new, seed=900 + M + n_new)
+    data = W.generate(w)
+    rng = np.random.default_rng(17 + M + n_new)
+    for cb in (data["k_codebook"], data["v_codebook"]):
+        cb[:, 0, 1] = cb[:, 0, 0]                          # subspace 0: a tie inside group 0
+        cb[:, 1, 130] = cb[:, 1, 7]                        # subspace 1: a tie across two groups
+        cb[:, 2, [9, 77, 140, 201, 255]] = cb[:, 2, 3][:, None]     # subspace 2: the same centroid in six groups
+        base = cb[:, 3, 0].astype(np.float32)              # subspace 3: 256 near-ties, a few fp16 steps apart
+        steps = rng.integers(-3, 4, size=(cb.shape[0], 256, ds)).astype(np.float32)
+        cb[:, 3] = (base[:, None, :] + steps * np.abs(np.spacing(base.astype(np.float16)))[:, None, :].astype(np.float32)).astype(np.float16)
+        cb[:, 4] = (cb[:, 4].astype(np.float32) * 1e-6).astype(np.float16)      # subspace 4: subnormals and zeros
+        cb[:, 5] = (cb[:, 5].astype(np.float32) * 150.0).astype(np.float16)     # subspace 5: |c|^2 / 2 beyond fp16
+        cb[:, 6, ::2] = 0                                  # subspace 6: half the centroids at the origin
+        # subspace 8: pairs of close centroids in different groups (k, k + 128), 0.02 .. 0.1 apart
+        d = rng.standard_normal((cb.shape[0], 128, ds)).astype(np.float32)
+        d *= (rng.uniform(0.02, 0.1, size=(cb.shape[0], 128, 1)) / np.linalg.norm(d, axis=-1, keepdims=True)).astype(np.float32)
+        cb[:, 8, 128:] = (cb[:, 8, :128].astype(np.float32) + d).astype(np.float16)
+    for x in (data["new_k"], data["new_v"]):
+        x[..., 0:ds] = data["k_codebook"][:, 0, 0][None, :, None, :]            # exactly on the tied centroids
+        x[..., ds:2 * ds] = data["k_codebook"][:, 1, 7][None, :, None, :]
+        x[..., 2 * ds:3 * ds] = data["k_codebook"][:, 2, 3][None, :, None, :]
+        x[..., 3 * ds:4 * ds] = data["k_codebook"][:, 3, 0][None, :, None, :]
+        x[..., 4 * ds:5 * ds] = (x[..., 4 * ds:5 * ds].astype(np.float32) * 1e-6).astype(np.float16)
+        x[..., 6 * ds:7 * ds] = 0
+        x[:, :, ::5, 7 * ds:8 * ds] = (x[:, :, ::5, 7 * ds:8 * ds].astype(np.float32) * 300.0).astype(np.float16)
+        # subspace 8: tokens within a few fp16 steps of the midpoint of a close pair (distance gaps around the
+        # filter's threshold; exact ties across two groups where the midpoint is representable)
+        pair = rng.integers(0, 128, size=x.shape[:3])
+        cb8 = data["k_codebook"][:, 8].astype(np.float32)
+        hk = np.arange(x.shape[1])[None, :, None]
+        mid = 0.5 * (cb8[hk, pair] + cb8[hk, pair + 128])
+        jit = rng.integers(-2, 3, size=mid.shape).astype(np.float32) * np.abs(np.spacing(mid.astype(np.float16))).astype(np.float32)
+        x[..., 8 * ds:9 * ds] = (mid + jit).astype(np.float16)
+    with PQSession(data, 4, "f16") as s:
+        s.ctx_len.zero_()
+        s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())
+        torch.cuda.synchronize()
+        got_k, got_v = s.unpack(PQ_CODES_K, n_new), s.unpack(PQ_CODES_V, n_new)
+    exp_k = O.encode(data["new_k"], data["k_codebook"])
+    exp_v = O.encode(data["new_v"], data["v_codebook"])
+    np.testing.assert_array_equal(got_k, exp_k)
+    np.testing.assert_array_equal(got_v, exp_v)
+    assert (exp_k[..., 0] == 0).all() and (exp_k[..., 1] == 7).all() and (exp_k[..., 2] == 3).all()
+
+
 def test_encode_on_a_second_stream_while_decode_runs():
     """Asynchronous quantization (Section III-B) with two default-priority streams: decode attends over the
     visible lengths while encode appends behind them through a second length array."""
