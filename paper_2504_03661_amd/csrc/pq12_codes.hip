@@ -95,6 +95,242 @@ __global__ __launch_bounds__(E12_WAVES * 64) void pq12_encode_kernel(const __hal
         out[(head * n_new + tok) * PQ12_M + i] = (uint16_t)best;
 }
 
+// ---------------------------------------------------------------------------------------------------
+// The same codes with the matrix cores as a filter (see the 8-bit encode for the argument and the error bound;
+// here ds = 4, so an A row is (c_0 .. c_3) and (h, l, 0, 0), two matrix instructions per value quad, 6 fp32
+// adds).  A workgroup keeps the 4096 A rows of its (K or V, KV head, subspace) in LDS (64 KiB) and each of its 8
+// wavefronts takes up to NQ 64-token sub-chunks of the head's tokens over all sequences.  Pass 1: the minimum
+// of the 4096 computed values per token.  Pass 2: one bit per block of 16 centroids whose smallest value is
+// within tau of it (256 bits per token).  One or two marked blocks: their 16 or 32 centroids are evaluated in
+// the defining fp64 arithmetic, ascending, lowest index first.  More, or a codebook whose |c|^2 / 2 leaves the
+// fp16 range: the sub-chunk runs the full fp64 scan.  About 1.5 vector instructions per (sub-vector, centroid)
+// instead of 11.
+// ---------------------------------------------------------------------------------------------------
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4e __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2e __attribute__((ext_vector_type(2)));
+
+__device__ inline int min4_bits(const f32x4e d)
+{
+    const int a = __float_as_int(d[0]), b = __float_as_int(d[1]), c = __float_as_int(d[2]), e = __float_as_int(d[3]);
+    return min(min(a, b), min(c, e));
+}
+
+constexpr int F12_WAVES = 8;  // wavefronts that share one set of A rows
+
+template <int NQ>
+__global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void pq12_encode_fast_kernel(const __half *x0, const __half *x1,
+                                                                         const __half *cb0, const __half *cb1,
+                                                                         uint16_t *out0, uint16_t *out1, int B, int Hkv,
+                                                                         int n_new, int groups_per_head, int64_t x_head_stride)
+{
+#pragma clang fp contract(off)
+    __shared__ __attribute__((aligned(16))) unsigned char arow[PQ12_CENTROIDS * 16];
+    __shared__ float red[2 * F12_WAVES + 1];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int which = blockIdx.z;  // 0: keys, 1: values
+    const int i = blockIdx.y;      // subspace
+    const int n_tok = B * n_new;   // tokens of one KV head over all sequences
+    const int hkv = blockIdx.x / groups_per_head;
+    const int chunk = (blockIdx.x - hkv * groups_per_head) * F12_WAVES + wave;  // of 64 NQ tokens
+    const __half *x = which ? x1 : x0;
+    const __half *cb = (which ? cb1 : cb0) + ((int64_t)hkv * PQ12_M + i) * PQ12_CENTROIDS * 4;
+    uint16_t *out = which ? out1 : out0;
+
+    // ---- A rows of the 4096 centroids, their largest |c|^2 / 2 and coordinate
+    float n_max = 0.f, c_max = 0.f;
+    bool cb_bad = false;
+    for (int c = tid; c < PQ12_CENTROIDS; c += F12_WAVES * 64) {
+        const u32x2e raw = *(const u32x2e *)(cb + c * 4);
+        const f16x4 v = __builtin_bit_cast(f16x4, raw);
+        float n = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float f = (float)v[j];
+            n += f * f;  // exact squares; the sum is rounded (covered by the bound)
+            c_max = fmaxf(c_max, fabsf(f));
+        }
+        const float h = 0.5f * n;
+        const _Float16 hh = (_Float16)h;
+        const _Float16 hl = (_Float16)(h - (float)hh);
+        cb_bad |= !(h < 60000.f);
+        n_max = fmaxf(n_max, h);
+        const f16x4 tail = {hh, hl, (_Float16)0.f, (_Float16)0.f};
+        *(f16x4 *)(arow + c * 16) = v;
+        *(f16x4 *)(arow + c * 16 + 8) = tail;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        n_max = fmaxf(n_max, __shfl_xor(n_max, o));
+        c_max = fmaxf(c_max, __shfl_xor(c_max, o));
+    }
+    if (lane == 0) {
+        red[wave] = n_max;
+        red[F12_WAVES + wave] = __builtin_amdgcn_ballot_w64(cb_bad) != 0 ? -1.f : c_max;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < F12_WAVES; ++w) {
+        n_max = fmaxf(n_max, red[w]);
+        const float cw = red[F12_WAVES + w];
+        cb_bad |= cw < 0.f;
+        c_max = fmaxf(c_max, cw);
+    }
+    cb_bad = __builtin_amdgcn_ballot_w64(cb_bad) != 0;
+    if (cb_bad)
+        c_max = 0.f;  // unused: every sub-chunk takes the full scan
+
+    // ---- this lane's tokens
+    bool live[NQ], bad[NQ];
+    f16x4 bop[NQ];
+    f32x4e off4[NQ];
+    float tau[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int u = (chunk * NQ + q) * 64 + lane;
+        live[q] = u < n_tok;
+        const int uu = live[q] ? u : 0;
+        const int b = uu / n_new;
+        const int t = uu - b * n_new;
+        // x is [B][Hkv][x_head_stride >= n_new][d]
+        const u32x2e raw = *(const u32x2e *)(x + ((((int64_t)b * Hkv + hkv) * x_head_stride + t) * PQ_HEAD_DIM + i * 4));
+        const f16x4 v = __builtin_bit_cast(f16x4, raw);
+        float x1s = 0.f, x2s = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float f = (float)v[j];
+            x1s += fabsf(f);
+            x2s += f * f;
+        }
+        u32x2e neg = raw ^ 0x80008000u;
+        asm volatile("" : "+v"(neg));  // keep the negated operand in its registers
+        bop[q] = __builtin_bit_cast(f16x4, neg);
+        const float t0 = n_max + x1s * c_max + 0.5025f * x2s;
+        float off = 0.5025f * x2s + 2.0f * (3.1e-06f * (2.0f * t0) + 2.4e-07f);
+        tau[q] = 3.1e-06f * (t0 + off) + 2.4e-07f;
+        off += tau[q];
+        off4[q] = f32x4e{off, off, off, off};
+        bad[q] = cb_bad || !(off < 1.0e30f);
+    }
+    const f16x4 ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)0.f, (_Float16)0.f};
+    const unsigned char *my_row = arow + (lane & 3) * 16;
+    auto values = [&](int m, int q) -> f32x4e {
+        const f16x4 A1 = *(const f16x4 *)(my_row + m * 64);
+        const f16x4 A2 = *(const f16x4 *)(my_row + m * 64 + 8);
+        return __builtin_amdgcn_mfma_f32_4x4x4f16(A2, ones, __builtin_amdgcn_mfma_f32_4x4x4f16(A1, bop[q], off4[q], 0, 0, 0), 0, 0, 0);
+    };
+
+    // ---- pass 1: smallest computed value per token (positive floats order like their bit patterns)
+    int best[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+        best[q] = 0x7f800000;
+#pragma unroll 2
+    for (int m = 0; m < PQ12_CENTROIDS / 4; ++m) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const f32x4e d = values(m, q);
+            best[q] = min(min(best[q], __float_as_int(d[0])), __float_as_int(d[1]));
+            best[q] = min(min(best[q], __float_as_int(d[2])), __float_as_int(d[3]));
+        }
+    }
+    // ---- pass 2: one bit per block of 16 centroids within tau of the minimum
+    uint32_t cand[NQ][8];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const float b = __int_as_float(best[q]);
+        bad[q] |= !(b > 0.f && b < 1.0e30f);
+        best[q] = __float_as_int(b + tau[q]);
+    }
+#pragma unroll
+    for (int wd = 0; wd < 8; ++wd) {
+        uint32_t bits[NQ];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+            bits[q] = 0u;
+#pragma unroll 1
+        for (int k = 0; k < 32; ++k) {  // block 32 wd + k: groups 4 (32 wd + k) .. + 3
+            int bmin[NQ];
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+                bmin[q] = 0x7f800000;
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+                    bmin[q] = min(bmin[q], min4_bits(values(4 * (32 * wd + k) + g4, q)));
+            }
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+                bits[q] |= bmin[q] <= best[q] ? 1u << k : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+            cand[q][wd] = bits[q];
+    }
+
+    // ---- refine / full scan, store
+    double xd[4];
+    auto exact = [&](int c, int &code, double &bd) {
+        const f16x4 v = *(const f16x4 *)(arow + c * 16);
+        double dist = 0.0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const double diff = xd[j] - (double)(float)v[j];
+            dist = __builtin_fma(diff, diff, dist);
+        }
+        code = dist < bd ? c : code;  // ascending callers, strict "<": the lowest index among equal distances stays
+        bd = __builtin_fmin(bd, dist);
+    };
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        // the token again (its registers were given up during the passes)
+        const int u = (chunk * NQ + q) * 64 + lane;
+        const int uu = live[q] ? u : 0;
+        const int b = uu / n_new;
+        const int t = uu - b * n_new;
+        {
+            const u32x2e raw = *(const u32x2e *)(x + ((((int64_t)b * Hkv + hkv) * x_head_stride + t) * PQ_HEAD_DIM + i * 4));
+            const f16x4 v = __builtin_bit_cast(f16x4, raw);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                xd[j] = (double)(float)v[j];
+        }
+        int cnt = 0, first = 0, last = 0;
+#pragma unroll
+        for (int wd = 7; wd >= 0; --wd) {
+            const uint32_t wbits = cand[q][wd];
+            cnt += __builtin_popcount(wbits);
+            first = wbits ? 32 * wd + __builtin_ctz(wbits) : first;
+        }
+#pragma unroll
+        for (int wd = 0; wd < 8; ++wd) {
+            const uint32_t wbits = cand[q][wd];
+            last = wbits ? 32 * wd + 31 - __builtin_clz(wbits) : last;
+        }
+        int code = 0;
+        double bd = __builtin_huge_val();
+        for (int k = 0; k < 16; ++k)
+            exact(16 * first + k, code, bd);
+        if (__builtin_amdgcn_ballot_w64(live[q] && cnt == 2) != 0) {  // wave-uniform; lanes with one block repeat it
+            for (int k = 0; k < 16; ++k)
+                exact(16 * last + k, code, bd);
+        }
+        const bool unsure = live[q] && (bad[q] || cnt < 1 || cnt > 2);
+        if (__builtin_amdgcn_ballot_w64(unsure) != 0) {  // wave-uniform: the defining scan for this sub-chunk
+            code = 0;
+            bd = __builtin_huge_val();
+            for (int c = 0; c < PQ12_CENTROIDS; ++c)
+                exact(c, code, bd);
+        }
+        if (live[q])
+            out[((((int64_t)b * Hkv + hkv) * n_new + t)) * PQ12_M + i] = (uint16_t)code;
+    }
+}
+
 // K units: one thread per (head, token j of the source, group of 8 subspaces)
 __global__ void pq12_pack_k_kernel(const uint16_t *src, uint8_t *dst, const int32_t *pos0, int n, int Hkv, int max_context,
                                    int64_t head_stride, int64_t total)
@@ -222,12 +458,28 @@ hipError_t pq12_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint16
 hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len,
                                      unsigned int *dev_err, hipStream_t s)
 {
-    const int n_chunks = (a.n_new + 63) >> 6;
-    const int groups_per_head = (a.B * n_chunks + E12_WAVES - 1) / E12_WAVES;
-    const dim3 grid((unsigned)(a.Hkv * groups_per_head), PQ12_M, 2);
-    hipLaunchKernelGGL(pq12_encode_kernel, grid, dim3(E12_WAVES * 64), 0, s, (const __half *)a.x[0],
-                       (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
-                       ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, (int64_t)a.n_new);
+    const int64_t n_tok = (int64_t)a.B * a.n_new;  // tokens of a head over all sequences
+    if (n_tok < ((int64_t)1 << 30)) {
+        // matrix-core filter: 8 wavefronts per workgroup, each takes 64 NQ tokens of the head
+        const int nq = n_tok > 64 * F12_WAVES ? 2 : 1;
+        const int groups_per_head = (int)((n_tok + 64 * nq * F12_WAVES - 1) / (64 * nq * F12_WAVES));
+        const dim3 grid((unsigned)(a.Hkv * groups_per_head), PQ12_M, 2);
+        if (nq == 2)
+            hipLaunchKernelGGL(pq12_encode_fast_kernel<2>, grid, dim3(F12_WAVES * 64), 0, s, (const __half *)a.x[0],
+                               (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
+                               ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, (int64_t)a.n_new);
+        else
+            hipLaunchKernelGGL(pq12_encode_fast_kernel<1>, grid, dim3(F12_WAVES * 64), 0, s, (const __half *)a.x[0],
+                               (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
+                               ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, (int64_t)a.n_new);
+    } else {
+        const int n_chunks = (a.n_new + 63) >> 6;
+        const int groups_per_head = (a.B * n_chunks + E12_WAVES - 1) / E12_WAVES;
+        const dim3 grid((unsigned)(a.Hkv * groups_per_head), PQ12_M, 2);
+        hipLaunchKernelGGL(pq12_encode_kernel, grid, dim3(E12_WAVES * 64), 0, s, (const __half *)a.x[0],
+                           (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
+                           ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, (int64_t)a.n_new);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)
         return e;
@@ -296,11 +548,11 @@ hipError_t pq12_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n
         for (int c0 = 0; c0 < n_samples; c0 += KM12_CHUNK) {
             const int nc = n_samples - c0 < KM12_CHUNK ? n_samples - c0 : KM12_CHUNK;
             const __half *x = (const __half *)samples + (int64_t)c0 * PQ_HEAD_DIM;
-            const int n_chunks = (nc + 63) >> 6;
-            const int groups_per_head = (n_chunks + E12_WAVES - 1) / E12_WAVES;
-            hipLaunchKernelGGL(pq12_encode_kernel, dim3((unsigned)(Hkv * groups_per_head), PQ12_M, 1), dim3(E12_WAVES * 64), 0,
-                               s, x, x, (const __half *)codebook, (const __half *)codebook, codes, codes, 1, Hkv, nc,
-                               groups_per_head, (int64_t)n_samples);
+            // assignment = the encode's matrix-core filter (one sequence, grid.z = 1: only the first pointers are used)
+            const int groups_per_head = (nc + 128 * F12_WAVES - 1) / (128 * F12_WAVES);
+            hipLaunchKernelGGL(pq12_encode_fast_kernel<2>, dim3((unsigned)(Hkv * groups_per_head), PQ12_M, 1),
+                               dim3(F12_WAVES * 64), 0, s, x, x, (const __half *)codebook, (const __half *)codebook, codes,
+                               codes, 1, Hkv, nc, groups_per_head, (int64_t)n_samples);
             const int64_t total = (int64_t)Hkv * nc * PQ12_M;
             hipLaunchKernelGGL(pq12_kmeans_accumulate_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x, codes,
                                sums, counts, (int64_t)n_samples, nc, total);

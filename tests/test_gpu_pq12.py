@@ -197,6 +197,54 @@ def test_encode_append_bit_exact_then_decode(n_old, n_new):
         check(out.cpu().numpy(), ref, "after append")
 
 
+@pytest.mark.parametrize("B_,n_new", [(1, 3), (2, 100), (3, 333)])
+def test_encode_filter_paths_are_bit_exact(B_, n_new):
+    """The 12-bit encode is a matrix-core filter with the fp64 expression as the decision: every way through it gives
+    the oracle's codes — ties inside one block of 16 centroids, across two blocks, across many (full scan), a
+    cluster of near-ties below the filter's resolution, subnormals and zeros, a codebook whose norms leave the fp16
+    range (full scan), outlier tokens, tokens near the midpoint of close centroid pairs in different blocks."""
+    w = W.Workload("filt12", B_, 2, 2, 128, 32, n_new + 3, "f16", n_new=n_new, seed=950 + n_new, n_centroids=4096)
+    data = W.generate(w)
+    rng = np.random.default_rng(23 + n_new)
+    for cb in (data["k_codebook"], data["v_codebook"]):
+        cb[:, 0, 1] = cb[:, 0, 0]
+        cb[:, 1, 3000] = cb[:, 1, 7]
+        cb[:, 2, [99, 777, 1400, 2010, 4095]] = cb[:, 2, 3][:, None]
+        base = cb[:, 3, 0].astype(np.float32)
+        steps = rng.integers(-3, 4, size=(cb.shape[0], 4096, 4)).astype(np.float32)
+        cb[:, 3] = (base[:, None, :] + steps * np.abs(np.spacing(base.astype(np.float16)))[:, None, :].astype(np.float32)).astype(np.float16)
+        cb[:, 4] = (cb[:, 4].astype(np.float32) * 1e-6).astype(np.float16)
+        cb[:, 5] = (cb[:, 5].astype(np.float32) * 150.0).astype(np.float16)
+        cb[:, 6, ::2] = 0
+        d = rng.standard_normal((cb.shape[0], 2048, 4)).astype(np.float32)
+        d *= (rng.uniform(0.02, 0.1, size=(cb.shape[0], 2048, 1)) / np.linalg.norm(d, axis=-1, keepdims=True)).astype(np.float32)
+        cb[:, 8, 2048:] = (cb[:, 8, :2048].astype(np.float32) + d).astype(np.float16)
+    for x in (data["new_k"], data["new_v"]):
+        x[..., 0:4] = data["k_codebook"][:, 0, 0][None, :, None, :]
+        x[..., 4:8] = data["k_codebook"][:, 1, 7][None, :, None, :]
+        x[..., 8:12] = data["k_codebook"][:, 2, 3][None, :, None, :]
+        x[..., 12:16] = data["k_codebook"][:, 3, 0][None, :, None, :]
+        x[..., 16:20] = (x[..., 16:20].astype(np.float32) * 1e-6).astype(np.float16)
+        x[..., 24:28] = 0
+        x[:, :, ::5, 28:32] = (x[:, :, ::5, 28:32].astype(np.float32) * 300.0).astype(np.float16)
+        pair = rng.integers(0, 2048, size=x.shape[:3])
+        cb8 = data["k_codebook"][:, 8].astype(np.float32)
+        hk = np.arange(x.shape[1])[None, :, None]
+        mid = 0.5 * (cb8[hk, pair] + cb8[hk, pair + 2048])
+        jit = rng.integers(-2, 3, size=mid.shape).astype(np.float32) * np.abs(np.spacing(mid.astype(np.float16))).astype(np.float32)
+        x[..., 32:36] = (mid + jit).astype(np.float16)
+    with PQSession(data, 2, "f16") as s:
+        s.ctx_len.zero_()
+        s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())
+        torch.cuda.synchronize()
+        got_k, got_v = s.unpack(PQ_CODES_K, n_new), s.unpack(PQ_CODES_V, n_new)
+    exp_k = O.encode(data["new_k"], data["k_codebook"])
+    exp_v = O.encode(data["new_v"], data["v_codebook"])
+    np.testing.assert_array_equal(got_k, exp_k)
+    np.testing.assert_array_equal(got_v, exp_v)
+    assert (exp_k[..., 0] == 0).all() and (exp_k[..., 1] == 7).all() and (exp_k[..., 2] == 3).all()
+
+
 def test_llama2_7b_layer_shape_at_32k():
     """The metric's shape with 12-bit codes: 1 x 32 heads x 32K tokens, 128 recent rows."""
     w = W.Workload("pq12_llama2_7b_32k", 1, 32, 32, 128, 32, 32768, "f16", recent_cap=128, recent_fixed=128,
