@@ -16,8 +16,8 @@ priority.  Decode reads the visible lengths, encode appends behind them using a 
 two kernels touch disjoint data; the caller publishes the new lengths between steps.
 
 train: Lloyd iterations of the per-subspace k-means (Section III-A, "Offline PQ Codebook Training") on 65 536
-sampled vectors per head, 32 heads, M = 64: time per iteration against the same fp64 vector-ALU roofline (the
-assignment step is the encode's scan).
+sampled vectors per head, 32 heads, M = 64: time per iteration against the vector-ALU roofline at the instruction
+count of the assignment (the encode's matrix-core filter), and the time the plain fp64 scan would need at that peak.
 
 pq12: the 12-bit setting (M = 32, 4096 centroids, 48 bytes per token and tensor; Section IV-A).  Decode
 against HBM: algorithmic bytes = codes + recent rows + both codebooks once per KV head (2 MiB per head: at 32K
@@ -155,7 +155,10 @@ def train():
 
     ms = _span_ms(run, 3, warmup=1) / iters
     ds = 128 // M
-    ops = Hkv * M * n * 256 * (2 * ds + 3)
+    # vector instructions of the assignment per (sample, subspace): the encode's matrix-core filter (2 + 4.5 per group
+    # of 4 centroids, 8 candidates in fp64, set-up) and the LDS atomics of the member sums
+    ops = Hkv * M * n * (256 * 1.625 + 8 * (2 * ds + 3) + 80)
+    scan_ops = Hkv * M * n * 256 * (2 * ds + 3)
     trained = cb.cpu().numpy()
     B.pq_attn_destroy(ctx)
 
@@ -163,8 +166,9 @@ def train():
                       "ms_per_iteration": round(ms, 3),
                       "sub_vectors_per_s": round(Hkv * M * n / (ms * 1e-3), 1),
                       "alu": {"bound": "alu", "achieved": round(ops / (ms * 1e-3) / 1e12, 2),
-                              "peak": round(ALU_LANE_OPS_PER_S / 1e12, 1), "unit": "T fp64 vector operations/s",
+                              "peak": round(ALU_LANE_OPS_PER_S / 1e12, 1), "unit": "T vector operations/s",
                               "frac": round(ops / (ms * 1e-3) / ALU_LANE_OPS_PER_S, 4)},
+                      "ms_of_the_fp64_scan_at_alu_peak": round(scan_ops / ALU_LANE_OPS_PER_S * 1e3, 3),
                       "trained_codebook_finite": bool(np.isfinite(trained.astype(np.float32)).all())}))
 
 

@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 
 #include "pq_internal.h"
+#include "pq_nearest_filter.h"
 
 namespace {
 
@@ -121,10 +122,6 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void pq_encode_kernel(const pq_enco
 // The matrix instruction takes fp16 subnormals as they are (no flush: measured, and the default mode of a HIP
 // kernel); n/2 beyond the fp16 range does not split into h + l: such a codebook takes the full scan.
 // Cost per (sub-vector, centroid): about 2 vector operations instead of 2 ds + 3 in fp64.
-typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4e __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2e __attribute__((ext_vector_type(2)));
-
 __device__ inline float wave_max_f(float x)
 {
 #pragma unroll
@@ -133,18 +130,10 @@ __device__ inline float wave_max_f(float x)
     return x;
 }
 
-__device__ inline int min4_bits(const f32x4e d)
-{
-    const int a = __float_as_int(d[0]), b = __float_as_int(d[1]), c = __float_as_int(d[2]), e = __float_as_int(d[3]);
-    const int ab = a < b ? a : b, ce = c < e ? c : e;
-    return ab < ce ? ab : ce;
-}
-
 template <int M, int DS, int NQ>
 __global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args a)
 {
-#pragma clang fp contract(off)
-    constexpr int ROW = DS == 2 ? 8 : 16;  // bytes of an A row: ds centroid coordinates, h, l (, 0, 0)
+    constexpr int ROW = pq_filter_row_bytes<DS>();
     __shared__ __attribute__((aligned(16))) unsigned char arow[256 * ROW];
     __shared__ double cb[256 * DS];
 
@@ -163,27 +152,7 @@ __global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int c = lane + 64 * r;
-        float n = 0.f;
-        _Float16 row[ROW / 2];
-#pragma unroll
-        for (int j = 0; j < DS; ++j) {
-            const _Float16 v = __builtin_bit_cast(_Float16, src[c * DS + j]);
-            const float f = (float)v;
-            cb[c * DS + j] = (double)f;
-            row[j] = v;
-            n += f * f;  // exact squares; the sum is rounded (covered by the bound)
-            c_max = fmaxf(c_max, fabsf(f));
-        }
-        const float h = 0.5f * n;
-        const _Float16 hh = (_Float16)h;
-        const _Float16 hl = (_Float16)(h - (float)hh);
-        row[DS] = hh;
-        row[DS + 1] = hl;
-        if (DS == 4)
-            row[6] = row[7] = (_Float16)0.f;
-        cb_bad |= !(h < 60000.f);
-        n_max = fmaxf(n_max, h);
-        __builtin_memcpy(arow + c * ROW, row, ROW);
+        pq_filter_build_row<DS>(src + c * DS, arow + c * ROW, cb + c * DS, n_max, c_max, cb_bad);
     }
     n_max = wave_max_f(n_max);
     c_max = wave_max_f(c_max);
@@ -193,12 +162,9 @@ __global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 
     // ---- this lane's tokens: one per 64-token sub-chunk
-    bool live[NQ], bad[NQ];
+    bool live[NQ];
     int bq[NQ], tq[NQ];
-    double xd[NQ][DS];
-    f16x4 bop[NQ];
-    f32x4e off4[NQ];
-    float tau[NQ];
+    _Float16 xv[NQ][DS];
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
         const int u = (chunk * NQ + q) * 64 + lane;
@@ -208,135 +174,22 @@ __global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args
         tq[q] = uu - bq[q] * a.n_new;
         const __half *xp =
             (const __half *)a.x[which] + (((int64_t)bq[q] * a.Hkv + hkv) * a.n_new + tq[q]) * PQ_HEAD_DIM + i * DS;
-        float x1 = 0.f, x2 = 0.f;
-        bad[q] = cb_bad;
-        _Float16 xv[4] = {(_Float16)1.f, (_Float16)1.f, (_Float16)1.f, (_Float16)1.f};
 #pragma unroll
-        for (int j = 0; j < DS; ++j) {
-            const _Float16 v = __builtin_bit_cast(_Float16, xp[j]);
-            const float f = (float)v;
-            xd[q][j] = (double)f;
-            xv[j] = -v;
-            x1 += fabsf(f);
-            x2 += f * f;
-        }
-        bop[q] = f16x4{xv[0], xv[1], xv[2], xv[3]};
-        {
-            // keep the negated operand in its registers (the compiler otherwise redoes the negation per use)
-            u32x2e w = __builtin_bit_cast(u32x2e, bop[q]);
-            asm volatile("" : "+v"(w));
-            bop[q] = __builtin_bit_cast(f16x4, w);
-        }
-        // off: |x|^2/2 with half a per cent on top, plus the same again as tau and a floor, so that every
-        // computed value stays above zero; T = N + X C + off; tau = 2^-18.3 T + 2^-22
-        const float t0 = n_max + x1 * c_max + 0.5025f * x2;
-        float off = 0.5025f * x2 + 2.0f * (3.1e-06f * (2.0f * t0) + 2.4e-07f);
-        tau[q] = 3.1e-06f * (t0 + off) + 2.4e-07f;
-        off += tau[q];
-        off4[q] = f32x4e{off, off, off, off};
-        bad[q] |= !(off < 1.0e30f);
+        for (int j = 0; j < DS; ++j)
+            xv[q][j] = __builtin_bit_cast(_Float16, xp[j]);
     }
-    const f16x4 ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)0.f, (_Float16)0.f};
-    const unsigned char *my_row = arow + (lane & 3) * ROW;
-    auto values = [&](int m, int q) -> f32x4e {
-        if (DS == 2) {
-            const f16x4 A = *(const f16x4 *)(my_row + m * (4 * ROW));
-            return __builtin_amdgcn_mfma_f32_4x4x4f16(A, bop[q], off4[q], 0, 0, 0);
-        }
-        const f16x4 A1 = *(const f16x4 *)(my_row + m * (4 * ROW));
-        const f16x4 A2 = *(const f16x4 *)(my_row + m * (4 * ROW) + 8);
-        return __builtin_amdgcn_mfma_f32_4x4x4f16(A2, ones, __builtin_amdgcn_mfma_f32_4x4x4f16(A1, bop[q], off4[q], 0, 0, 0), 0, 0, 0);
-    };
+    int codes[NQ];
+    pq_filter_codes<DS, NQ>(arow, cb, n_max, c_max, cb_bad, xv, live, codes);
 
-    // ---- pass 1: smallest computed value per token (positive floats order like their bit patterns)
-    int best[NQ];
-#pragma unroll
-    for (int q = 0; q < NQ; ++q)
-        best[q] = 0x7f800000;
-    for (int m = 0; m < 64; ++m) {
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const f32x4e d = values(m, q);
-            best[q] = min(min(best[q], __float_as_int(d[0])), __float_as_int(d[1]));
-            best[q] = min(min(best[q], __float_as_int(d[2])), __float_as_int(d[3]));
-        }
-    }
-    // ---- pass 2: candidate groups, one bit per group
-    uint32_t cand_lo[NQ], cand_hi[NQ];
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
-        const float b = __int_as_float(best[q]);
-        bad[q] |= !(b > 0.f && b < 1.0e30f);                   // the offset did not keep the values positive and finite
-        best[q] = __float_as_int(b + tau[q]);
-        cand_lo[q] = 0u;
-        cand_hi[q] = 0u;
-    }
-#pragma unroll 4
-    for (int m = 0; m < 32; ++m) {
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const f32x4e d = values(m, q);
-            const int m4 = min(min(__float_as_int(d[0]), __float_as_int(d[1])), min(__float_as_int(d[2]), __float_as_int(d[3])));
-            cand_lo[q] |= m4 <= best[q] ? 1u << m : 0u;
-        }
-    }
-#pragma unroll 4
-    for (int m = 0; m < 32; ++m) {
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const f32x4e d = values(m + 32, q);
-            const int m4 = min(min(__float_as_int(d[0]), __float_as_int(d[1])), min(__float_as_int(d[2]), __float_as_int(d[3])));
-            cand_hi[q] |= m4 <= best[q] ? 1u << m : 0u;
-        }
-    }
-    int cnt[NQ], first[NQ], last[NQ];
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-        const uint64_t cand = ((uint64_t)cand_hi[q] << 32) | cand_lo[q];
-        cnt[q] = __builtin_popcountll(cand);
-        first[q] = cand ? __builtin_ctzll(cand) : 0;
-        last[q] = cand ? 63 - __builtin_clzll(cand) : 0;
-    }
-
-    // ---- refine / full scan, store
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-        int code = 0;
-        double bd = __builtin_huge_val();
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {  // ascending centroid index: first group, then last group (the same if one)
-            const int c = 4 * (k < 4 ? first[q] : last[q]) + (k & 3);
-            double dist = 0.0;
-#pragma unroll
-            for (int j = 0; j < DS; ++j) {
-                const double diff = xd[q][j] - cb[c * DS + j];
-                dist = __builtin_fma(diff, diff, dist);
-            }
-            code = dist < bd ? c : code;  // strict: the lowest index among equal distances stays
-            bd = __builtin_fmin(bd, dist);
-        }
-        const bool unsure = live[q] && (bad[q] || cnt[q] < 1 || cnt[q] > 2);
-        if (__builtin_amdgcn_ballot_w64(unsure) != 0) {  // wave-uniform: the defining scan for this sub-chunk
-            code = 0;
-            bd = __builtin_huge_val();
-            for (int c = 0; c < 256; ++c) {
-                double dist = 0.0;
-#pragma unroll
-                for (int j = 0; j < DS; ++j) {
-                    const double diff = xd[q][j] - cb[c * DS + j];
-                    dist = __builtin_fma(diff, diff, dist);
-                }
-                code = dist < bd ? c : code;
-                bd = __builtin_fmin(bd, dist);
-            }
-        }
         int n_old = a.ctx_len[bq[q]];
         n_old = n_old < 0 ? 0 : n_old;
         const int64_t pos = (int64_t)n_old + tq[q];
         if (live[q] && pos < a.max_context) {
             uint8_t *dst = a.codes[which] + ((int64_t)bq[q] * a.Hkv + hkv) * a.head_stride;
             const int64_t off = which == 0 ? pq_k_code_offset(pos, i, M, a.k_skew) : pq_v_code_offset(pos, i, M);
-            dst[off] = (uint8_t)code;
+            dst[off] = (uint8_t)codes[q];
         }
     }
 }

@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 
 #include "pq_internal.h"
+#include "pq_nearest_filter.h"
 
 namespace {
 
@@ -34,10 +35,13 @@ __global__ __launch_bounds__(KM_WAVES * 64) void pq_kmeans_assign_kernel(const _
                                                                         unsigned long long *sums, unsigned int *counts,
                                                                         int n_samples, int n_slices)
 {
-#pragma clang fp contract(off)
+    constexpr int ROW = pq_filter_row_bytes<DS>();
+    static_assert(KM_WAVES * 64 == 256, "one thread per centroid below");
     __shared__ double cb[256 * DS];
+    __shared__ __attribute__((aligned(16))) unsigned char arow[256 * ROW];
     __shared__ unsigned long long part_sum[256 * DS];
     __shared__ unsigned int part_cnt[256];
+    __shared__ float red[2 * KM_WAVES];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -46,45 +50,59 @@ __global__ __launch_bounds__(KM_WAVES * 64) void pq_kmeans_assign_kernel(const _
     const int slice = blockIdx.x - head * n_slices;
     const int i = blockIdx.y;  // subspace
 
+    // codebook of this (head, subspace): fp64 copy and matrix-instruction rows for the nearest-centroid filter of
+    // the encode (pq_nearest_filter.h), one centroid per thread; accumulators cleared
     const int64_t cb_base = ((int64_t)head * M + i) * 256 * DS;
-    for (int e = tid; e < 256 * DS; e += KM_WAVES * 64) {
-        cb[e] = (double)__half2float(codebook[cb_base + e]);
+    float n_max = 0.f, c_max = 0.f;
+    bool cb_bad = false;
+    pq_filter_build_row<DS>(codebook + cb_base + tid * DS, arow + tid * ROW, cb + tid * DS, n_max, c_max, cb_bad);
+    for (int e = tid; e < 256 * DS; e += KM_WAVES * 64)
         part_sum[e] = 0ull;
+    part_cnt[tid] = 0u;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        n_max = fmaxf(n_max, __shfl_xor(n_max, o));
+        c_max = fmaxf(c_max, __shfl_xor(c_max, o));
     }
-    for (int e = tid; e < 256; e += KM_WAVES * 64)
-        part_cnt[e] = 0u;
+    if (lane == 0) {
+        red[wave] = n_max;
+        red[KM_WAVES + wave] = __builtin_amdgcn_ballot_w64(cb_bad) != 0 ? -1.f : c_max;
+    }
     __syncthreads();
+#pragma unroll
+    for (int w = 0; w < KM_WAVES; ++w) {
+        n_max = fmaxf(n_max, red[w]);
+        const float cw = red[KM_WAVES + w];
+        cb_bad |= cw < 0.f;
+        c_max = fmaxf(c_max, cw);
+    }
+    cb_bad = __builtin_amdgcn_ballot_w64(cb_bad) != 0;
 
+    // this wavefront's KM_CHUNKS 64-sample chunks, assigned together (the same rule and arithmetic as the encode)
+    bool live[KM_CHUNKS];
+    _Float16 xv[KM_CHUNKS][DS];
+#pragma unroll
     for (int ch = 0; ch < KM_CHUNKS; ++ch) {
         const int s = slice * KM_SLICE + (ch * KM_WAVES + wave) * 64 + lane;
-        if (s >= n_samples)
+        live[ch] = s < n_samples;
+        const int ss = live[ch] ? s : 0;
+#pragma unroll
+        for (int j = 0; j < DS; ++j)
+            xv[ch][j] = __builtin_bit_cast(_Float16, samples[((int64_t)head * n_samples + ss) * PQ_HEAD_DIM + i * DS + j]);
+    }
+    int codes[KM_CHUNKS];
+    pq_filter_codes<DS, KM_CHUNKS>(arow, cb, n_max, c_max, cb_bad, xv, live, codes);
+#pragma unroll
+    for (int ch = 0; ch < KM_CHUNKS; ++ch) {
+        if (!live[ch])
             continue;
-        float xf[DS];
-        double x[DS];
-#pragma unroll
-        for (int j = 0; j < DS; ++j) {
-            xf[j] = __half2float(samples[((int64_t)head * n_samples + s) * PQ_HEAD_DIM + i * DS + j]);
-            x[j] = (double)xf[j];
-        }
-        int best = 0;
-        double best_dist = __builtin_huge_val();
-        for (int c = 0; c < 256; ++c) {
-            double dist = 0.0;
-#pragma unroll
-            for (int j = 0; j < DS; ++j) {
-                const double diff = x[j] - cb[c * DS + j];
-                dist = __builtin_fma(diff, diff, dist);
-            }
-            best = dist < best_dist ? c : best;  // strict "<", ascending scan: lowest index among equals
-            best_dist = __builtin_fmin(best_dist, dist);
-        }
 #pragma unroll
         for (int j = 0; j < DS; ++j) {
             // exact: an fp16 value times 2^24 is an integer below 2^41 in magnitude
-            const long long fixed = (long long)(xf[j] * 16777216.0f);
-            atomicAdd(&part_sum[best * DS + j], (unsigned long long)fixed);
+            const long long fixed = (long long)((float)xv[ch][j] * 16777216.0f);
+            atomicAdd(&part_sum[codes[ch] * DS + j], (unsigned long long)fixed);
         }
-        atomicAdd(&part_cnt[best], 1u);
+        atomicAdd(&part_cnt[codes[ch]], 1u);
     }
     __syncthreads();
 
