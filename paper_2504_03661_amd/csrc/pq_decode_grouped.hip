@@ -409,23 +409,39 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         return;
     asm volatile("" ::: "memory");  // the loads below stay behind the ticket in the instruction stream
     {
-        // the other workgroups' partials, by device-scope loads issued after the ticket has returned
+        // The other workgroups' partials, by device-scope loads issued after the ticket has returned: the first 32
+        // splits' outputs together with the (maximum, weight sum) pairs, so that the merge costs one memory round
+        // trip instead of three.  Loads of splits beyond S repeat the last split (unconditional loads from
+        // wave-uniform bases); their factor is zero.
         const float *ps = a.partials + (int64_t)(bh0 + g) * S * PQ_PART_STRIDE;
+        float2 o[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u)
+            o[u] = fetch(ps + (u < S ? u : S - 1) * PQ_PART_STRIDE + 4 + 2 * lane);
         const float2 ml = lane < S ? fetch(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
         const float mx = wave_max(ml.x);
         const float f_lane = __builtin_amdgcn_exp2f(ml.x - mx);
         const float l = wave_sum(ml.y * f_lane);
         float o0 = 0.f, o1 = 0.f;
-        for (int s0 = 0; s0 < S; s0 += 16) {
-            float2 o[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u)
-                o[u] = s0 + u < S ? fetch(ps + (s0 + u) * PQ_PART_STRIDE + 4 + 2 * lane) : make_float2(0.f, 0.f);
+        for (int u = 0; u < 32; ++u) {
+            float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), u));
+            f = u < S ? f : 0.f;  // wave-uniform
+            o0 = fmaf(o[u].x, f, o0);
+            o1 = fmaf(o[u].y, f, o1);
+        }
+        // more than 32 splits (few heads, long contexts): four at a time
+        for (int s0 = 32; s0 < S; s0 += 4) {
+            float2 t[4];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), (s0 + u) & 63));
-                o0 = fmaf(o[u].x, f, o0);
-                o1 = fmaf(o[u].y, f, o1);
+            for (int u = 0; u < 4; ++u)
+                t[u] = fetch(ps + (s0 + u < S ? s0 + u : S - 1) * PQ_PART_STRIDE + 4 + 2 * lane);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), (s0 + u) & 63));
+                f = s0 + u < S ? f : 0.f;
+                o0 = fmaf(t[u].x, f, o0);
+                o1 = fmaf(t[u].y, f, o1);
             }
         }
         const float inv = l > 0.f ? 1.f / l : 0.f;
