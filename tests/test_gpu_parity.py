@@ -298,7 +298,8 @@ def test_bulk_encode_at_prefill_shape_is_bit_exact():
 
 
 @pytest.mark.parametrize("M", [64, 32])
-@pytest.mark.parametrize("B_,n_new", [(1, 1), (3, 20), (2, 50), (2, 200), (5, 333)])
+@pytest.mark.parametrize("B_,n_new", [(1, 1), (3, 20), (2, 50), (2, 200), (5, 333), (1, 64), (1, 65), (2, 64), (1, 129), (1, 256),
+                                       (1, 257)])
 def test_encode_filter_paths_are_bit_exact(M, B_, n_new):
     """fp16 encode = matrix-core filter + fp64 decision: every way through it gives the oracle's codes — ties inside
     one group of 4 centroids, across two groups, across three and more (full scan), clusters of near-ties far
