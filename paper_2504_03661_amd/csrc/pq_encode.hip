@@ -15,6 +15,9 @@
 // best is a compare + two selects, and no cross-lane reduction is needed.  The
 // strict "<" on an ascending scan keeps the lowest index among equal distances.
 // The code byte is stored straight into the device layout of its tensor.
+// This scan (pq_encode_kernel) serves fp32 contexts; fp16 contexts reach the same codes through
+// pq_encode_fast_kernel further down, where the matrix cores find the few centroids that can be
+// the nearest and the expression above decides among them.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
