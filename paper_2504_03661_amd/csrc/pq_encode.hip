@@ -197,6 +197,80 @@ __global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args
     }
 }
 
+// ---------------------------------------------------------------------------------
+// A handful of tokens per KV head (one decoding step of a small batch): lane = CENTROID.  With one token per
+// lane a wavefront would walk 256 centroids for a few live lanes; here every lane holds 4 centroids in
+// registers, evaluates the defining fp64 distances of the token at hand to its 4 (ascending, strict "<") and
+// the wavefront takes the lexicographic minimum of (distance, index) — the lowest index among equal distances,
+// as in the scan.  One wavefront per (K or V, KV head, subspace) loops over the head's tokens of all sequences.
+constexpr int FEW_TOKENS = 16;
+
+template <int M, int DS, typename T>
+__global__ __launch_bounds__(64) void pq_encode_few_kernel(const pq_encode_args a)
+{
+#pragma clang fp contract(off)
+    const int lane = threadIdx.x;
+    const int which = blockIdx.z;
+    const int i = blockIdx.y;
+    const int hkv = blockIdx.x;
+    const int n_tok = a.B * a.n_new;  // <= FEW_TOKENS
+
+    const int64_t cb_base = ((int64_t)hkv * M + i) * 256 * DS;
+    double c[4][DS];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int j = 0; j < DS; ++j)
+            c[r][j] = widen<T>(a.codebook[which], cb_base + (int64_t)(lane + 64 * r) * DS + j);
+
+    // lane u < n_tok fetches token u: its sub-vector, sequence and position
+    const int u_mine = lane < n_tok ? lane : 0;
+    const int b_mine = u_mine / a.n_new;
+    const int t_mine = u_mine - b_mine * a.n_new;
+    double x_mine[DS];
+#pragma unroll
+    for (int j = 0; j < DS; ++j)
+        x_mine[j] = widen<T>(a.x[which], (((int64_t)b_mine * a.Hkv + hkv) * a.n_new + t_mine) * PQ_HEAD_DIM + i * DS + j);
+    int n_old = a.ctx_len[b_mine];
+    n_old = n_old < 0 ? 0 : n_old;
+
+    int code_mine = 0;
+    for (int u = 0; u < n_tok; ++u) {
+        double x[DS];
+#pragma unroll
+        for (int j = 0; j < DS; ++j)
+            x[j] = __shfl(x_mine[j], u);
+        double bd = __builtin_huge_val();
+        int bc = lane;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            double dist = 0.0;
+#pragma unroll
+            for (int j = 0; j < DS; ++j) {
+                const double diff = x[j] - c[r][j];
+                dist = __builtin_fma(diff, diff, dist);
+            }
+            bc = dist < bd ? lane + 64 * r : bc;  // ascending index inside the lane, strict "<"
+            bd = __builtin_fmin(bd, dist);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double od = __shfl_xor(bd, o);
+            const int oc = __shfl_xor(bc, o);
+            const bool take = od < bd || (od == bd && oc < bc);
+            bd = take ? od : bd;
+            bc = take ? oc : bc;
+        }
+        code_mine = lane == u ? bc : code_mine;
+    }
+    const int64_t pos = (int64_t)n_old + t_mine;
+    if (lane < n_tok && pos < a.max_context) {
+        uint8_t *dst = a.codes[which] + ((int64_t)b_mine * a.Hkv + hkv) * a.head_stride;
+        const int64_t off = which == 0 ? pq_k_code_offset(pos, i, M, a.k_skew) : pq_v_code_offset(pos, i, M);
+        dst[off] = (uint8_t)code_mine;
+    }
+}
+
 __global__ void pq_bump_len_kernel(int32_t *ctx_len, int B, int n_new, int max_context, unsigned int *dev_err)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -248,6 +322,20 @@ hipError_t pq_launch_encode(const pq_attn_ctx *ctx, const pq_encode_args &a, int
                             hipStream_t s)
 {
     const bool f16 = ctx->cfg.dtype == PQ_F16;
+    if ((int64_t)a.B * a.n_new <= FEW_TOKENS) {
+        const dim3 grid(a.Hkv, ctx->cfg.n_subspaces, 2);
+        if (ctx->cfg.n_subspaces == 64) {
+            if (f16) hipLaunchKernelGGL((pq_encode_few_kernel<64, 2, __half>), grid, dim3(64), 0, s, a);
+            else hipLaunchKernelGGL((pq_encode_few_kernel<64, 2, float>), grid, dim3(64), 0, s, a);
+        } else {
+            if (f16) hipLaunchKernelGGL((pq_encode_few_kernel<32, 4, __half>), grid, dim3(64), 0, s, a);
+            else hipLaunchKernelGGL((pq_encode_few_kernel<32, 4, float>), grid, dim3(64), 0, s, a);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return e;
+        return pq_launch_bump_len(ctx_len, a.B, a.n_new, a.max_context, dev_err, s);
+    }
     // the filter kernel indexes the tokens of a head over all sequences with 32 bits
     const bool fast = f16 && (int64_t)a.B * a.n_new < ((int64_t)1 << 30);
     if (ctx->cfg.n_subspaces == 64) {

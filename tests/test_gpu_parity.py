@@ -299,12 +299,13 @@ def test_bulk_encode_at_prefill_shape_is_bit_exact():
 
 @pytest.mark.parametrize("M", [64, 32])
 @pytest.mark.parametrize("B_,n_new", [(1, 1), (3, 20), (2, 50), (2, 200), (5, 333), (1, 64), (1, 65), (2, 64), (1, 129), (1, 256),
-                                       (1, 257)])
+                                       (1, 257), (16, 1), (1, 16), (2, 5), (1, 17)])
 def test_encode_filter_paths_are_bit_exact(M, B_, n_new):
     """fp16 encode = matrix-core filter + fp64 decision: every way through it gives the oracle's codes — ties inside
     one group of 4 centroids, across two groups, across three and more (full scan), clusters of near-ties far
     below the filter's resolution, subnormal and zero inputs, a codebook whose norms leave the fp16 range (full
-    scan), tokens that are far outliers; token counts per head that take the 1-, 2- and 4-chunk instantiations."""
+    scan), tokens that are far outliers; token counts per head that take the 1-, 2- and 4-chunk instantiations, and (16 tokens or fewer)
+    the centroid-per-lane kernel."""
     ds = 128 // M
     w = W.Workload("filt", B_, 4, 2, 128, M, n_new + 3, "f16", n_new=n_new, seed=900 + M + n_new)
     data = W.generate(w)
