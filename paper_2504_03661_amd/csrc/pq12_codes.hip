@@ -14,6 +14,7 @@
 #include <hip/hip_runtime.h>
 
 #include "pq_internal.h"
+#include "pq_device_utils.h"
 
 namespace {
 
@@ -331,6 +332,99 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// A handful of tokens per KV head (one decoding step of a small batch): thread = CENTROID.  The filter kernel
+// above would build 4096 rows and run both passes for a wavefront with a few live lanes; here the 1024 threads
+// of a workgroup hold 4 centroids each in registers, evaluate the defining fp64 distances of the token at hand
+// (ascending index per thread, strict "<") and the workgroup takes the lexicographic minimum of (distance,
+// index): the lowest index among equal distances, as in the scan.  The floor is reading the codebooks once
+// (64 MiB for K and V of 32 heads).
+// ---------------------------------------------------------------------------------------------------
+constexpr int FEW12_TOKENS = 16;
+constexpr int FEW12_WAVES = 16;
+
+__global__ __launch_bounds__(FEW12_WAVES * 64) void pq12_encode_few_kernel(const __half *x0, const __half *x1,
+                                                                          const __half *cb0, const __half *cb1,
+                                                                          uint16_t *out0, uint16_t *out1, int B, int Hkv,
+                                                                          int n_new)
+{
+#pragma clang fp contract(off)
+    static_assert(FEW12_TOKENS <= 64, "lane u fetches token u");
+    __shared__ double red_d[FEW12_TOKENS][FEW12_WAVES];
+    __shared__ int red_c[FEW12_TOKENS][FEW12_WAVES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int which = blockIdx.z;
+    const int i = blockIdx.y;
+    const int hkv = blockIdx.x;
+    const int n_tok = B * n_new;  // <= FEW12_TOKENS
+    const __half *x = which ? x1 : x0;
+    const __half *cb = (which ? cb1 : cb0) + ((int64_t)hkv * PQ12_M + i) * PQ12_CENTROIDS * 4;
+    uint16_t *out = which ? out1 : out0;
+
+    double c[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const u32x2e raw = *(const u32x2e *)(cb + (int64_t)(tid + 1024 * r) * 4);
+        const f16x4 v = __builtin_bit_cast(f16x4, raw);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            c[r][j] = (double)(float)v[j];
+    }
+    // lane u < n_tok of every wavefront fetches token u's sub-vector
+    const int u_mine = lane < n_tok ? lane : 0;
+    const int b_mine = u_mine / n_new;
+    const int t_mine = u_mine - b_mine * n_new;
+    double x_mine[4];
+    {
+        const u32x2e raw = *(const u32x2e *)(x + ((((int64_t)b_mine * Hkv + hkv) * n_new + t_mine) * PQ_HEAD_DIM + i * 4));
+        const f16x4 v = __builtin_bit_cast(f16x4, raw);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            x_mine[j] = (double)(float)v[j];
+    }
+
+    for (int u = 0; u < n_tok; ++u) {
+        double xv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            xv[j] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x_mine[j]), u),
+                                     __builtin_amdgcn_readlane(__double2loint(x_mine[j]), u));
+        double bd = __builtin_huge_val();
+        int bc = tid;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            double dist = 0.0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const double diff = xv[j] - c[r][j];
+                dist = __builtin_fma(diff, diff, dist);
+            }
+            bc = dist < bd ? tid + 1024 * r : bc;  // ascending index inside the thread, strict "<"
+            bd = __builtin_fmin(bd, dist);
+        }
+        wave_argmin(bd, bc);
+        if (lane == 0) {
+            red_d[u][wave] = bd;
+            red_c[u][wave] = bc;
+        }
+    }
+    __syncthreads();
+    // wavefront u finishes token u: the 16 wavefronts' candidates sit in every row of 16 lanes
+    if (wave < n_tok) {
+        double d = red_d[wave][lane & (FEW12_WAVES - 1)];
+        int cc = red_c[wave][lane & (FEW12_WAVES - 1)];
+        wave_argmin(d, cc);
+        if (lane == 0) {
+            const int b = wave / n_new;
+            const int t = wave - b * n_new;
+            out[(((int64_t)b * Hkv + hkv) * n_new + t) * PQ12_M + i] = (uint16_t)cc;
+        }
+    }
+}
+
 // K units: one thread per (head, token j of the source, group of 8 subspaces)
 __global__ void pq12_pack_k_kernel(const uint16_t *src, uint8_t *dst, const int32_t *pos0, int n, int Hkv, int max_context,
                                    int64_t head_stride, int64_t total)
@@ -459,7 +553,11 @@ hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_arg
                                      unsigned int *dev_err, hipStream_t s)
 {
     const int64_t n_tok = (int64_t)a.B * a.n_new;  // tokens of a head over all sequences
-    if (n_tok < ((int64_t)1 << 30)) {
+    if (n_tok <= FEW12_TOKENS) {
+        hipLaunchKernelGGL(pq12_encode_few_kernel, dim3((unsigned)a.Hkv, PQ12_M, 2), dim3(FEW12_WAVES * 64), 0, s,
+                           (const __half *)a.x[0], (const __half *)a.x[1], (const __half *)a.codebook[0],
+                           (const __half *)a.codebook[1], ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new);
+    } else if (n_tok < ((int64_t)1 << 30)) {
         // matrix-core filter: 8 wavefronts per workgroup, each takes 64 NQ tokens of the head
         const int nq = n_tok > 64 * F12_WAVES ? 2 : 1;
         const int groups_per_head = (int)((n_tok + 64 * nq * F12_WAVES - 1) / (64 * nq * F12_WAVES));

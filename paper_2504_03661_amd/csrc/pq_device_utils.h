@@ -122,4 +122,44 @@ template <bool READ_ONCE> __device__ inline uint4 load_codes(const u32x4 *p)
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 
+// (d, c) <- the smaller of (d, c) and (od, oc) in the order (distance, index)
+__device__ inline void argmin_take(double &d, int &c, const double od, const int oc)
+{
+    const bool take = od < d || (od == d && oc < c);
+    d = take ? od : d;
+    c = take ? oc : c;
+}
+
+template <int CTRL> __device__ inline void argmin_dpp(double &d, int &c)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(d), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(d), CTRL, 0xf, 0xf, true);
+    const int oc = __builtin_amdgcn_update_dpp(0, c, CTRL, 0xf, 0xf, true);
+    argmin_take(d, c, __hiloint2double(hi, lo), oc);
+}
+
+// minimum over the 64 lanes, the same in every lane: lane exchanges inside a row of 16 by DPP (vector-ALU
+// speed; a shuffle goes through the LDS crossbar), then the 4 rows' results
+__device__ inline void wave_argmin(double &d, int &c)
+{
+    argmin_dpp<0xB1>(d, c);   // quad_perm [1,0,3,2]
+    argmin_dpp<0x4E>(d, c);   // quad_perm [2,3,0,1]
+    argmin_dpp<0x141>(d, c);  // row_half_mirror
+    argmin_dpp<0x140>(d, c);  // row_mirror
+    double rd[4];
+    int rc[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        rd[r] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(d), 16 * r),
+                                 __builtin_amdgcn_readlane(__double2loint(d), 16 * r));
+        rc[r] = __builtin_amdgcn_readlane(c, 16 * r);
+    }
+    d = rd[0];
+    c = rc[0];
+#pragma unroll
+    for (int r = 1; r < 4; ++r)
+        argmin_take(d, c, rd[r], rc[r]);
+}
+
+
 }  // namespace

@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 
 #include "pq_internal.h"
+#include "pq_device_utils.h"
 #include "pq_nearest_filter.h"
 
 namespace {
@@ -239,7 +240,8 @@ __global__ __launch_bounds__(64) void pq_encode_few_kernel(const pq_encode_args 
         double x[DS];
 #pragma unroll
         for (int j = 0; j < DS; ++j)
-            x[j] = __shfl(x_mine[j], u);
+            x[j] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x_mine[j]), u),
+                                    __builtin_amdgcn_readlane(__double2loint(x_mine[j]), u));
         double bd = __builtin_huge_val();
         int bc = lane;
 #pragma unroll
@@ -253,14 +255,7 @@ __global__ __launch_bounds__(64) void pq_encode_few_kernel(const pq_encode_args 
             bc = dist < bd ? lane + 64 * r : bc;  // ascending index inside the lane, strict "<"
             bd = __builtin_fmin(bd, dist);
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const double od = __shfl_xor(bd, o);
-            const int oc = __shfl_xor(bc, o);
-            const bool take = od < bd || (od == bd && oc < bc);
-            bd = take ? od : bd;
-            bc = take ? oc : bc;
-        }
+        wave_argmin(bd, bc);
         code_mine = lane == u ? bc : code_mine;
     }
     const int64_t pos = (int64_t)n_old + t_mine;

@@ -197,7 +197,7 @@ def test_encode_append_bit_exact_then_decode(n_old, n_new):
         check(out.cpu().numpy(), ref, "after append")
 
 
-@pytest.mark.parametrize("B_,n_new", [(1, 3), (2, 100), (3, 333), (1, 512), (1, 513), (2, 512), (1, 1025)])
+@pytest.mark.parametrize("B_,n_new", [(1, 3), (2, 100), (3, 333), (1, 512), (1, 513), (2, 512), (1, 1025), (16, 1), (2, 8), (1, 17)])
 def test_encode_filter_paths_are_bit_exact(B_, n_new):
     """The 12-bit encode is a matrix-core filter with the fp64 expression as the decision: every way through it gives
     the oracle's codes — ties inside one block of 16 centroids, across two blocks, across many (full scan), a
