@@ -77,8 +77,10 @@ int choose_splits(const pq_attn_config *c, int n_cu)
         (int64_t)c->batch * (pq_config_uses_grouped_kernel(c) ? c->n_q_heads / pq_grouped_heads_per_workgroup(g) : c->n_q_heads);
     int64_t s = n_cu / heads;
     const int64_t blocks = padded_capacity(c) / 64;
-    // 8-bit kernels: at least a 64-token block per wavefront; 12-bit kernel: at least one 4096-token chunk
-    const int64_t per_split = pq_config_is_12bit(c) ? 64 : 16;
+    // 8-bit kernels: at least 4 blocks of 64 tokens per split — short contexts gain more from the parallelism
+    // than they lose to idle wavefronts (32 heads x 1K tokens: 11.1 us with one split, 8.2 us with four; 2K: 11.3
+    // -> 8.8; 4K: 10.9 -> 9.6); 12-bit kernel: at least one 4096-token chunk
+    const int64_t per_split = pq_config_is_12bit(c) ? 64 : 4;
     const int64_t max_by_work = blocks / per_split > 0 ? blocks / per_split : 1;
     if (s > max_by_work)
         s = max_by_work;
