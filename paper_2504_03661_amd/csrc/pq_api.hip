@@ -173,10 +173,12 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     ctx->k_skew = pq_config_uses_grouped_kernel(cfg) ? PQ_K_SKEW_QUAD : PQ_K_SKEW_LANE;
     ctx->n_splits = cfg->n_splits > 0 ? cfg->n_splits : choose_splits(cfg, prop.multiProcessorCount);
     // 12-bit contexts with few (sequence, query head) pairs decode in two passes (split by subspace group, see
-    // pq12_decode.hip): chosen when the fused kernel would need 5 or more token splits per head (measured at 32 heads x 32K: one
-    // sequence 44 against 64 us, two sequences 87 against 84 us, four 182 against 164 us), or on request
+    // pq12_decode.hip): chosen when there are 5 or more compute units per (sequence, head) pair, whatever the context
+    // length (measured with 32 heads: one sequence 21 against 47 us at 1K tokens, 32 against 56 us at 16K, 45 against
+    // 64 us at 32K; two sequences at 32K 87 against 84 us, four 182 against 164 us), or on request
     bool two_pass = false;
-    if (pq_config_is_12bit(cfg) && (cfg->n_splits < 0 || (cfg->n_splits == 0 && ctx->n_splits >= 5))) {
+    const int64_t cus_per_head = prop.multiProcessorCount / ((int64_t)cfg->batch * cfg->n_q_heads);
+    if (pq_config_is_12bit(cfg) && (cfg->n_splits < 0 || (cfg->n_splits == 0 && cus_per_head >= 5))) {
         two_pass = true;
         const int64_t n_bh8 = (int64_t)cfg->batch * cfg->n_q_heads * 8;
         int64_t ts = cfg->n_splits < 0 ? -cfg->n_splits : prop.multiProcessorCount / n_bh8;
