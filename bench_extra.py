@@ -5,6 +5,8 @@
     python bench_extra.py async     # encode on a second stream while decode runs
     python bench_extra.py train     # offline codebook training (k-means), 64K samples x 32 heads
     python bench_extra.py pq12      # 12-bit codes: decode at 1 x 32 heads x 32K and 8 x 32 x 32K, 64-token append
+    python bench_extra.py ctx       # decode time against context length (1K .. 128K), 32 heads and 32 query / 8 KV heads
+    python bench_extra.py step1     # one decoding step of one sequence: one-token append + decode, 8-bit and 12-bit
 
 prefill: the nearest-centroid encode at prompt shape (Section III-A, "Online Prefill with KV Cache
 Quantization"): vectors per second against the vector-ALU roofline (256 CUs x 64 lanes x 2.4 GHz = 39.3 T
@@ -23,6 +25,11 @@ pq12: the 12-bit setting (M = 32, 4096 centroids, 48 bytes per token and tensor;
 against HBM: algorithmic bytes = codes + recent rows + both codebooks once per KV head (2 MiB per head: at 32K
 tokens they are 40 % of the bytes) + q / out.  With few (sequence, head) pairs the decode runs in two passes
 (partial scores per subspace group, then softmax and values): "n_passes" in the output.
+ctx: decode kernel time against context length, 1K .. 128K tokens, for 1 x 32 heads (one query head per KV head) and for
+32 query / 8 KV heads (the grouped-query kernel); split counts as the library chooses them.
+
+step1: one decoding step of a single sequence, 32 heads at 32K tokens: append of one token per head, then decode, for
+8-bit codes (M = 64) and 12-bit codes (M = 32, 4096 centroids).
 Each mode prints one JSON line.
 """
 import json
@@ -225,6 +232,68 @@ def pq12():
     print(json.dumps(res))
 
 
+def ctx():
+    import torch
+    from paper_2504_03661_amd.harness import PQSession
+    from synth import workloads as W
+
+    res = {"mode": "decode_vs_context", "unit": "us per decode"}
+    for label, hq, hkv in (("32_heads", 32, 32), ("32q_8kv", 32, 8)):
+        rows = {}
+        for n in (1024, 2048, 4096, 8192, 16384, 32768, 65536, 131072):
+            w = W.Workload("ctx", 1, hq, hkv, 128, 64, n, "f16", recent_cap=128, recent_fixed=128, seed=W.BASE_SEED + 21)
+            data = W.generate(w)
+            copies = max(2, min(16, -(-(1 << 30) // (2 * hkv * n * 64))))
+            with PQSession(data, hq, "f16", code_copies=copies) as s:
+                dec = [s.prepared_decode(W.attention_scale(w), copy=c) for c in range(copies)]
+                it = [0]
+
+                def step():
+                    dec[it[0] % copies]()
+                    it[0] += 1
+                rows[str(n)] = {"us": round(_span_ms(step, 400, warmup=1500) * 1e3, 2), "n_splits": s.n_splits}
+        res[label] = rows
+    print(json.dumps(res))
+
+
+def step1():
+    import torch
+    from paper_2504_03661_amd.harness import PQSession
+    from synth import workloads as W
+
+    res = {"mode": "single_sequence_step", "unit": "us"}
+    for label, m, c in (("8bit_M64", 64, 256), ("12bit_M32", 32, 4096)):
+        w = W.Workload("step1_" + label, 1, 32, 32, 128, m, 32768, "f16", recent_cap=128, recent_fixed=128, n_new=1,
+                       seed=W.BASE_SEED + 22, n_centroids=c)
+        data = W.generate(w)
+        with PQSession(data, 32, "f16", code_copies=8) as s:
+            nk, nv = torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda()
+            base = s.ctx_len.clone()
+            apps = [s.prepared_append(nk, nv, copy=k) for k in range(8)]
+            decs = [s.prepared_decode(W.attention_scale(w), copy=k) for k in range(8)]
+            it = [0]
+
+            def reset_only():
+                s.ctx_len.copy_(base)
+
+            def append_only():
+                s.ctx_len.copy_(base)
+                apps[it[0] % 8]()
+                it[0] += 1
+
+            def whole():
+                s.ctx_len.copy_(base)
+                apps[it[0] % 8]()
+                decs[it[0] % 8]()
+                it[0] += 1
+            t_reset = _span_ms(reset_only, 400, warmup=400) * 1e3
+            t_app = _span_ms(append_only, 400, warmup=400) * 1e3
+            t_all = _span_ms(whole, 400, warmup=800) * 1e3
+        res[label] = {"length_reset_copy": round(t_reset, 2), "append_one_token_per_head": round(t_app - t_reset, 2),
+                      "append_and_decode": round(t_all - t_reset, 2)}
+    print(json.dumps(res))
+
+
 if __name__ == "__main__":
     mode = sys.argv[1] if len(sys.argv) > 1 else ""
     if mode == "prefill":
@@ -235,6 +304,10 @@ if __name__ == "__main__":
         train()
     elif mode == "pq12":
         pq12()
+    elif mode == "ctx":
+        ctx()
+    elif mode == "step1":
+        step1()
     else:
         print(__doc__)
         sys.exit(2)
