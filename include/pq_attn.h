@@ -113,7 +113,7 @@ int pq_attn_set_codebooks(pq_attn_ctx *ctx, const void *k_codebook /* device */,
  *   v_codebook  likewise
  *   recent_k/v  device [B][Hkv][max_recent][d]    dtype; both NULL = no window
  *   recent_len  device [B] int32                  R_b, clamped to [0, max_recent]; NULL = all 0
- *   scale       1/sqrt(d) of Eq. 1
+ *   scale       1/sqrt(d) of Eq. 1; must be finite (PQ_ERR_SHAPE otherwise)
  *   out         device [B][Hq][d] float32
  *
  * Rows >= R_b of the recent tensors and tokens >= N_b of the code tensors are never

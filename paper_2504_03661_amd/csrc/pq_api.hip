@@ -253,7 +253,7 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
         return PQ_ERR_NULL;
     if (recent_k != nullptr && ctx->cfg.max_recent == 0)
         return PQ_ERR_SHAPE;
-    if (!(scale == scale))
+    if (!(fabsf(scale) <= 3.0e38f))  // NaN or infinite
         return PQ_ERR_SHAPE;
     device_guard guard(ctx->cfg.device);
     if (!guard.ok)

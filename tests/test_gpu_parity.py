@@ -407,6 +407,10 @@ def test_argument_errors_on_gpu():
         with pytest.raises(PQAttnError):           # recent_k without recent_v
             binding.pq_attn_decode(s.ctx, s.q, s.k_codes[0], s.v_codes[0], s.ctx_len, s.k_codebook, s.v_codebook,
                                    s.q, None, None, 1.0, s.out)
+        for bad_scale in (float("nan"), float("inf"), -float("inf")):
+            with pytest.raises(PQAttnError) as e:
+                s.decode(bad_scale, pass_codebooks=True)
+            assert e.value.status == -2
         out = s.decode(W.attention_scale(w), pass_codebooks=True)
         check(out.cpu().numpy(), oracle_out(w, data), "after errors")
 
