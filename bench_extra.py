@@ -78,9 +78,11 @@ def prefill():
             app()
         ms = _span_ms(step, 5)
     vectors = 2 * w.batch * w.n_kv_heads * n_new
-    # vector instructions the fp16 filter kernel issues per (token, subspace): 2 + 4.5 per group of 4 centroids
-    # in its two passes, 8 candidates evaluated in fp64 at 2 ds + 3 each, about 60 of set-up and store
-    ops_per_subvector = 256 * 1.625 + 8 * (2 * w.sub_dim + 3) + 60
+    # vector instructions the fp16 filter kernel issues per (token, subspace), matrix instructions not counted: 2 + 3
+    # per group of 4 centroids in its two passes, about 180 for token set-up, the fp64 evaluation of 4 to 8 candidates
+    # and the store (rocprofv3 SQ_INSTS_VALU - SQ_INSTS_MFMA: 499); 2 matrix instructions per group of 4
+    ops_per_subvector = 256 * 1.25 + 180
+    mfma_per_subvector = 2 * 64 * (w.sub_dim // 2)
     ops = vectors * w.n_subspaces * ops_per_subvector
     achieved = ops / (ms * 1e-3)
     scan_ops = vectors * w.n_subspaces * 256 * (2 * w.sub_dim + 3)
@@ -89,6 +91,9 @@ def prefill():
                       "roofline": {"bound": "alu", "unit": "lane-op/s", "achieved": achieved,
                                    "peak": ALU_LANE_OPS_PER_S, "frac": round(achieved / ALU_LANE_OPS_PER_S, 4),
                                    "ops_per_subvector": ops_per_subvector},
+                      # a SIMD issues a 64-lane vector instruction in 4 cycles and a 4x4x4 matrix instruction in 8
+                      "ms_at_the_issue_limit": round(vectors * w.n_subspaces / 64 * (4 * ops_per_subvector + 8 * mfma_per_subvector)
+                                                     / (1024 * 2.4e9) * 1e3, 3),
                       "ms_of_the_fp64_scan_at_alu_peak": round(scan_ops / ALU_LANE_OPS_PER_S * 1e3, 3)}))
 
 
@@ -162,9 +167,9 @@ def train():
 
     ms = _span_ms(run, 3, warmup=1) / iters
     ds = 128 // M
-    # vector instructions of the assignment per (sample, subspace): the encode's matrix-core filter (2 + 4.5 per group
-    # of 4 centroids, 8 candidates in fp64, set-up) and the LDS atomics of the member sums
-    ops = Hkv * M * n * (256 * 1.625 + 8 * (2 * ds + 3) + 80)
+    # vector instructions of the assignment per (sample, subspace): the encode's matrix-core filter (2 + 3 per group
+    # of 4 centroids, 4 to 8 candidates in fp64, set-up) and the LDS atomics of the member sums
+    ops = Hkv * M * n * (256 * 1.25 + 200)
     scan_ops = Hkv * M * n * 256 * (2 * ds + 3)
     trained = cb.cpu().numpy()
     B.pq_attn_destroy(ctx)
@@ -220,14 +225,17 @@ def pq12():
             s.ctx_len.copy_(base)
             app()
         ms = _span_ms(step2, 20, warmup=10)
-    # vector instructions of the matrix-core filter per (token, subspace): 2 + 3.75 per group of 4 centroids in its
-    # two passes, 16-32 candidates evaluated in fp64 (about 450), about 60 of set-up; the plain fp64 scan has 4096 x 11
+    # vector instructions of the matrix-core filter per (token, subspace), matrix instructions not counted: 2 + 2.25
+    # per group of 4 centroids in its two passes, about 1100 for 16-32 candidates evaluated in fp64, set-up and store
+    # (rocprofv3 SQ_INSTS_VALU - SQ_INSTS_MFMA: 5470); the plain fp64 scan has 4096 x 11
     pairs = 2 * 16 * 32 * 64 * 32
-    ops = pairs * (4096 * 5.75 / 4 + 450 + 60)
+    ops = pairs * (4096 * 4.25 / 4 + 1100)
     res["append_16x32x64"] = {"ms": round(ms, 4), "vectors_per_s": round(2 * 16 * 32 * 64 / (ms * 1e-3), 1),
                               "alu": {"bound": "alu", "achieved": round(ops / (ms * 1e-3) / 1e12, 2),
                                       "peak": round(ALU_LANE_OPS_PER_S / 1e12, 1), "unit": "T vector operations/s",
                                       "frac": round(ops / (ms * 1e-3) / ALU_LANE_OPS_PER_S, 4)},
+                              # 4 cycles of a SIMD per 64-lane vector instruction, 8 per 4x4x4 matrix instruction (4 per group)
+                              "ms_at_the_issue_limit": round(pairs / 64 * (4 * (4096 * 4.25 / 4 + 1100) + 8 * 4096) / (1024 * 2.4e9) * 1e3, 3),
                               "ms_of_the_fp64_scan_at_alu_peak": round(pairs * 4096 * 11 / ALU_LANE_OPS_PER_S * 1e3, 3)}
     print(json.dumps(res))
 

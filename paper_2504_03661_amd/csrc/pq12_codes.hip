@@ -101,21 +101,16 @@ __global__ __launch_bounds__(E12_WAVES * 64) void pq12_encode_kernel(const __hal
 // here ds = 4, so an A row is (c_0 .. c_3) and (h, l, 0, 0), two matrix instructions per value quad, 6 fp32
 // adds).  A workgroup keeps the 4096 A rows of its (K or V, KV head, subspace) in LDS (64 KiB) and each of its 8
 // wavefronts takes up to NQ 64-token sub-chunks of the head's tokens over all sequences.  Pass 1: the minimum
-// of the 4096 computed values per token.  Pass 2: one bit per block of 16 centroids whose smallest value is
-// within tau of it (256 bits per token).  One or two marked blocks: their 16 or 32 centroids are evaluated in
+// of the 4096 computed values per token.  Pass 2: one bit per block of 16 centroids that holds a value
+// within tau of it (256 bits per token; the sign of the value once best + tau is folded into the C operand).
+// One or two marked blocks: their 16 or 32 centroids are evaluated in
 // the defining fp64 arithmetic, ascending, lowest index first.  More, or a codebook whose |c|^2 / 2 leaves the
-// fp16 range: the sub-chunk runs the full fp64 scan.  About 1.5 vector instructions per (sub-vector, centroid)
+// fp16 range: the sub-chunk runs the full fp64 scan.  About 1.1 vector instructions per (sub-vector, centroid)
 // instead of 11.
 // ---------------------------------------------------------------------------------------------------
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4e __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2e __attribute__((ext_vector_type(2)));
-
-__device__ inline int min4_bits(const f32x4e d)
-{
-    const int a = __float_as_int(d[0]), b = __float_as_int(d[1]), c = __float_as_int(d[2]), e = __float_as_int(d[3]);
-    return min(min(a, b), min(c, e));
-}
 
 constexpr int F12_WAVES = 8;  // wavefronts that share one set of A rows
 
@@ -238,13 +233,16 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
             best[q] = min(min(best[q], __float_as_int(d[2])), __float_as_int(d[3]));
         }
     }
-    // ---- pass 2: one bit per block of 16 centroids within tau of the minimum
+    // ---- pass 2: one bit per block of 16 centroids within tau of the minimum.  With off - (best + tau) in the C
+    // operand a computed value is negative exactly where it is a candidate: the OR of a block's 16 results carries
+    // that in its sign bit, which one v_alignbit shifts into the mask (block 32 wd + k lands in bit 31 - k).
     uint32_t cand[NQ][8];
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
         const float b = __int_as_float(best[q]);
         bad[q] |= !(b > 0.f && b < 1.0e30f);
-        best[q] = __float_as_int(b + tau[q]);
+        const float d = off4[q][0] - (b + tau[q]);
+        off4[q] = f32x4e{d, d, d, d};
     }
 #pragma unroll
     for (int wd = 0; wd < 8; ++wd) {
@@ -254,19 +252,21 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
             bits[q] = 0u;
 #pragma unroll 1
         for (int k = 0; k < 32; ++k) {  // block 32 wd + k: groups 4 (32 wd + k) .. + 3
-            int bmin[NQ];
+            uint32_t any[NQ];
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
-                bmin[q] = 0x7f800000;
+                any[q] = 0u;
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
 #pragma unroll
-                for (int q = 0; q < NQ; ++q)
-                    bmin[q] = min(bmin[q], min4_bits(values(4 * (32 * wd + k) + g4, q)));
+                for (int q = 0; q < NQ; ++q) {
+                    const f32x4e d = values(4 * (32 * wd + k) + g4, q);
+                    any[q] |= (__float_as_uint(d[0]) | __float_as_uint(d[1])) | (__float_as_uint(d[2]) | __float_as_uint(d[3]));
+                }
             }
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
-                bits[q] |= bmin[q] <= best[q] ? 1u << k : 0u;
+                bits[q] = __builtin_amdgcn_alignbit(bits[q], any[q], 31);
         }
 #pragma unroll
         for (int q = 0; q < NQ; ++q)
@@ -305,12 +305,12 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
         for (int wd = 7; wd >= 0; --wd) {
             const uint32_t wbits = cand[q][wd];
             cnt += __builtin_popcount(wbits);
-            first = wbits ? 32 * wd + __builtin_ctz(wbits) : first;
+            first = wbits ? 32 * wd + __builtin_clz(wbits) : first;
         }
 #pragma unroll
         for (int wd = 0; wd < 8; ++wd) {
             const uint32_t wbits = cand[q][wd];
-            last = wbits ? 32 * wd + 31 - __builtin_clz(wbits) : last;
+            last = wbits ? 32 * wd + 31 - __builtin_ctz(wbits) : last;
         }
         int code = 0;
         double bd = __builtin_huge_val();

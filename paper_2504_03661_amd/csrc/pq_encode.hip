@@ -106,17 +106,21 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void pq_encode_kernel(const pq_enco
 // as integers (v_min3_i32: half a vector operation per value, no NaN quieting).  That is a filter, not the
 // decision:
 //   pass 1  best = min over all 256 centroids of the computed v;
-//   pass 2  the same products again; a group of 4 centroids is a candidate when its smallest computed v is
-//           <= best + tau; count the candidate groups, remember the first and the last;
+//   pass 2  the same products again with off - (best + tau) in the C operand: a computed value is negative
+//           where it lies within tau of the best one, so a group of 4 centroids is a candidate when the OR of
+//           its 4 results has the sign bit set (one v_alignbit shifts that bit into the group mask); count the
+//           candidate groups, remember the first and the last;
 //   refine  one or two candidate groups (nearly always): the true minimiser is among their centroids — the
-//           distances of those 4 or 8 are evaluated in the defining fp64 arithmetic (see the top of this file),
+//           distances of those 4 (8 if some token of the wavefront has two groups) are evaluated in the
+//           defining fp64 arithmetic (see the top of this file),
 //           ascending, and the smallest, lowest index first, is the code.  Otherwise (three or more groups
 //           within tau: duplicated centroids, near-ties; subnormal or out-of-range inputs) the 64-token chunk
 //           runs the full fp64 scan.
 // Either way the code is decided by the fp64 expression, so it is bit-exact by construction; the filter only
 // has to be SAFE: every centroid outside the candidate groups must have a strictly larger true distance.  With
 // |computed - true| <= e for every centroid and c^ the minimiser of the computed values, a centroid c outside
-// the candidate groups has true v(c) > best + tau - e and true v(c^) <= best + e: tau >= 2 e suffices.
+// the candidate groups has true v(c) > best + tau - e and true v(c^) <= best + e: tau >= 2 e suffices (plus the
+// two roundings of off - (best + tau), <= 2^-23 T, and strictly: tau exceeds 2 e by 2^-20.4 T).
 // Bound on e: A row = (c_0 .. c_{ds-1}, h, l) with h + l = n/2 split into two fp16 (n summed in fp32 from
 // exact squares: <= 2^-21.2 n/2 in all), B column = (-x_0 .. -x_{ds-1}, 1, 1); fp32 accumulation of at most 7
 // terms, even if every one of the 6 adds truncates, <= 6 x 2^-23 T with T = N + X C + off >= the sum of the
@@ -135,7 +139,7 @@ __device__ inline float wave_max_f(float x)
 }
 
 template <int M, int DS, int NQ>
-__global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args a)
+__global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args a, const int rounds)
 {
     constexpr int ROW = pq_filter_row_bytes<DS>();
     __shared__ __attribute__((aligned(16))) unsigned char arow[256 * ROW];
@@ -146,8 +150,9 @@ __global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args
     const int i = blockIdx.y;      // subspace
     const int n_tok = a.B * a.n_new;  // tokens of one KV head over all sequences: they share its codebook
     const int n_chunks = (n_tok + 64 * NQ - 1) / (64 * NQ);
-    const int hkv = blockIdx.x / n_chunks;
-    const int chunk = blockIdx.x - hkv * n_chunks;
+    const int n_jobs = (n_chunks + rounds - 1) / rounds;  // a wavefront takes `rounds` chunks in a row: one codebook set-up
+    const int hkv = blockIdx.x / n_jobs;
+    const int chunk0 = (blockIdx.x - hkv * n_jobs) * rounds;
 
     // ---- codebook of this subspace: fp64 copy for the exact evaluations, A rows for the filter
     const __half *src = (const __half *)a.codebook[which] + ((int64_t)hkv * M + i) * 256 * DS;
@@ -165,6 +170,8 @@ __global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 
+#pragma unroll 1
+    for (int chunk = chunk0; chunk < chunk0 + rounds && chunk < n_chunks; ++chunk) {
     // ---- this lane's tokens: one per 64-token sub-chunk
     bool live[NQ];
     int bq[NQ], tq[NQ];
@@ -195,6 +202,7 @@ __global__ __launch_bounds__(64) void pq_encode_fast_kernel(const pq_encode_args
             const int64_t off = which == 0 ? pq_k_code_offset(pos, i, M, a.k_skew) : pq_v_code_offset(pos, i, M);
             dst[off] = (uint8_t)codes[q];
         }
+    }
     }
 }
 
@@ -302,14 +310,18 @@ void launch_fast(const pq_encode_args &a, hipStream_t s)
 {
     const int n_tok = a.B * a.n_new;
     if (n_tok > 128) {
-        dim3 grid(a.Hkv * ((n_tok + 255) / 256), M, 2);
-        hipLaunchKernelGGL((pq_encode_fast_kernel<M, DS, 4>), grid, dim3(64), 0, s, a);
+        // prompt-sized inputs: up to 8 chunks of 256 tokens per wavefront while at least 8192 wavefronts remain
+        const int n_chunks = (n_tok + 255) / 256;
+        const int64_t waves = (int64_t)a.Hkv * n_chunks * M * 2;
+        const int rounds = (int)(waves / 8192 < 1 ? 1 : waves / 8192 > 8 ? 8 : waves / 8192);
+        dim3 grid(a.Hkv * ((n_chunks + rounds - 1) / rounds), M, 2);
+        hipLaunchKernelGGL((pq_encode_fast_kernel<M, DS, 4>), grid, dim3(64), 0, s, a, rounds);
     } else if (n_tok > 64) {
         dim3 grid(a.Hkv, M, 2);
-        hipLaunchKernelGGL((pq_encode_fast_kernel<M, DS, 2>), grid, dim3(64), 0, s, a);
+        hipLaunchKernelGGL((pq_encode_fast_kernel<M, DS, 2>), grid, dim3(64), 0, s, a, 1);
     } else {
         dim3 grid(a.Hkv, M, 2);
-        hipLaunchKernelGGL((pq_encode_fast_kernel<M, DS, 1>), grid, dim3(64), 0, s, a);
+        hipLaunchKernelGGL((pq_encode_fast_kernel<M, DS, 1>), grid, dim3(64), 0, s, a, 1);
     }
 }
 

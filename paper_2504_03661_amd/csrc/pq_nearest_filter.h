@@ -115,13 +115,18 @@ __device__ inline void pq_filter_codes(const unsigned char *arow, const double *
             best[q] = min(min(best[q], __float_as_int(d[2])), __float_as_int(d[3]));
         }
     }
-    // ---- pass 2: candidate groups, one bit per group
+    // ---- pass 2: candidate groups, one bit per group.  The C operand becomes off - (best + tau): a computed value
+    // is then negative exactly where it lies within tau of the best one, so the sign bit IS the candidate flag —
+    // OR over the group's 4 values, shifted into the mask by one v_alignbit (group g lands in bit 63 - g).
+    // The rounding differs from pass 1's (another C), within the same bound e; the minimiser's value comes out
+    // <= 2 e - tau + (the two roundings of best + tau - off, <= 2^-23 T) < 0, so it is marked.
     uint32_t cand_lo[NQ], cand_hi[NQ];
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
         const float b = __int_as_float(best[q]);
         bad[q] |= !(b > 0.f && b < 1.0e30f);                   // the offset did not keep the values positive and finite
-        best[q] = __float_as_int(b + tau[q]);
+        const float d = off4[q][0] - (b + tau[q]);
+        off4[q] = f32x4e{d, d, d, d};
         cand_lo[q] = 0u;
         cand_hi[q] = 0u;
     }
@@ -130,8 +135,8 @@ __device__ inline void pq_filter_codes(const unsigned char *arow, const double *
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const f32x4e d = values(m, q);
-            const int m4 = min(min(__float_as_int(d[0]), __float_as_int(d[1])), min(__float_as_int(d[2]), __float_as_int(d[3])));
-            cand_lo[q] |= m4 <= best[q] ? 1u << m : 0u;
+            const uint32_t any = (__float_as_uint(d[0]) | __float_as_uint(d[1])) | (__float_as_uint(d[2]) | __float_as_uint(d[3]));
+            cand_lo[q] = __builtin_amdgcn_alignbit(cand_lo[q], any, 31);
         }
     }
 #pragma unroll 4
@@ -139,27 +144,28 @@ __device__ inline void pq_filter_codes(const unsigned char *arow, const double *
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const f32x4e d = values(m + 32, q);
-            const int m4 = min(min(__float_as_int(d[0]), __float_as_int(d[1])), min(__float_as_int(d[2]), __float_as_int(d[3])));
-            cand_hi[q] |= m4 <= best[q] ? 1u << m : 0u;
+            const uint32_t any = (__float_as_uint(d[0]) | __float_as_uint(d[1])) | (__float_as_uint(d[2]) | __float_as_uint(d[3]));
+            cand_hi[q] = __builtin_amdgcn_alignbit(cand_hi[q], any, 31);
         }
     }
     int cnt[NQ], first[NQ], last[NQ];
+    bool two = false;
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
-        const uint64_t cand = ((uint64_t)cand_hi[q] << 32) | cand_lo[q];
+        const uint64_t cand = ((uint64_t)cand_lo[q] << 32) | cand_hi[q];
         cnt[q] = __builtin_popcountll(cand);
-        first[q] = cand ? __builtin_ctzll(cand) : 0;
-        last[q] = cand ? 63 - __builtin_clzll(cand) : 0;
+        first[q] = cand ? __builtin_clzll(cand) : 0;
+        last[q] = cand ? 63 - __builtin_ctzll(cand) : 0;
+        two |= live[q] && cnt[q] == 2;
     }
+    two = __builtin_amdgcn_ballot_w64(two) != 0;  // wave-uniform: some token has a second candidate group
 
     // ---- refine / full scan
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
         int code = 0;
         double bd = __builtin_huge_val();
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {  // ascending centroid index: first group, then last group (the same if one)
-            const int c = 4 * (k < 4 ? first[q] : last[q]) + (k & 3);
+        auto take = [&](int c) {
             double dist = 0.0;
 #pragma unroll
             for (int j = 0; j < DS; ++j) {
@@ -168,6 +174,14 @@ __device__ inline void pq_filter_codes(const unsigned char *arow, const double *
             }
             code = dist < bd ? c : code;  // strict: the lowest index among equal distances stays
             bd = __builtin_fmin(bd, dist);
+        };
+#pragma unroll
+        for (int k = 0; k < 4; ++k)  // ascending centroid index: the first group ...
+            take(4 * first[q] + k);
+        if (two) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)  // ... then the last one (the same group again where there is only one)
+                take(4 * last[q] + k);
         }
         const bool unsure = live[q] && (bad[q] || cnt[q] < 1 || cnt[q] > 2);
         if (__builtin_amdgcn_ballot_w64(unsure) != 0) {  // wave-uniform: the defining scan for this sub-chunk

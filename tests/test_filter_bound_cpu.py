@@ -59,6 +59,25 @@ def test_tau_covers_twice_the_worst_case_error(ds, c_scale, x_scale):
     assert (2.0 * err <= tau.astype(np.float64)).all(), (2.0 * err / tau).max()
     assert (2.0 * err <= 0.85 * tau.astype(np.float64)).all()          # and with room to spare
     assert (acc > 0).all()                                  # the offset keeps every value positive: integer order = float order
+    # pass 2: the C operand becomes off - (best + tau) and a NEGATIVE computed value marks a candidate.  Under the same
+    # worst-case rounding (truncation toward zero makes negative values less negative) every centroid that is not
+    # marked must have a strictly larger true value than the true minimiser, which itself must be marked.
+    best = acc.min(axis=1)
+    d = (off - (best + tau)).astype(np.float32)
+    for rounding in (trunc32, lambda v: np.asarray(v, np.float64).astype(np.float32)):
+        acc2 = np.repeat(d[:, None], 256, axis=1).astype(np.float32)
+        for j in range(ds):
+            prod = -(x[:, j].astype(np.float64)[:, None] * c[:, j].astype(np.float64)[None, :])
+            acc2 = rounding(acc2.astype(np.float64) + prod)
+        acc2 = rounding(acc2.astype(np.float64) + hh.astype(np.float64)[None, :])
+        acc2 = rounding(acc2.astype(np.float64) + hl.astype(np.float64)[None, :])
+        marked = np.signbit(acc2)
+        rows = np.arange(len(x))
+        assert marked[rows, true.argmin(axis=1)].all()
+        unmarked_min = np.where(marked, np.inf, true).min(axis=1)
+        assert (unmarked_min > true.min(axis=1)).all()
+        if c_scale >= 1e-3:                                 # (tiny centroids all sit within the absolute floor of tau)
+            assert marked.sum(axis=1).max() <= 64           # a filter, not a pass-through
 
 
 def test_truncation_helper():

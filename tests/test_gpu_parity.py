@@ -297,6 +297,20 @@ def test_bulk_encode_at_prefill_shape_is_bit_exact():
             np.testing.assert_array_equal(s.unpack(PQ_CODES_V, 3000), O.encode(data["new_v"], data["v_codebook"]))
 
 
+@pytest.mark.parametrize("M,n_new", [(64, 7000), (32, 9300)])
+def test_bulk_encode_with_several_chunks_per_wavefront(M, n_new):
+    """Enough 256-token chunks that a wavefront of the filter kernel takes several in a row, the last
+    wavefront of a head fewer than the others."""
+    w = W.Workload("pre_rounds", 1, 8, 8, 128, M, n_new, "f16", n_new=n_new, seed=310 + M)
+    data = W.generate(w)
+    with PQSession(data, 8, "f16") as s:
+        s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())
+        torch.cuda.synchronize()
+        assert s.ctx_len.cpu().tolist() == [n_new]
+        np.testing.assert_array_equal(s.unpack(PQ_CODES_K, n_new), O.encode(data["new_k"], data["k_codebook"]))
+        np.testing.assert_array_equal(s.unpack(PQ_CODES_V, n_new), O.encode(data["new_v"], data["v_codebook"]))
+
+
 @pytest.mark.parametrize("M", [64, 32])
 @pytest.mark.parametrize("B_,n_new", [(1, 1), (3, 20), (2, 50), (2, 200), (5, 333), (1, 64), (1, 65), (2, 64), (1, 129), (1, 256),
                                        (1, 257), (16, 1), (1, 16), (2, 5), (1, 17)])
