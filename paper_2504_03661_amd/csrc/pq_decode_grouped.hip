@@ -1,5 +1,5 @@
 // Decode attention over a product-quantized KV cache for grouped queries (2..4 query heads
-// per KV head, fp16, M = 64 subspaces of 2 dims): one fused kernel per call.
+// per KV head, fp16, M = 64 subspaces of 2 dims or M = 32 of 4): one fused kernel per call.
 //
 // Same result as the per-head table kernel (Eq. 7 = Eq. 6), different evaluation.  With G
 // query heads reading one KV head, per-head score tables cost G x 64 KiB of LDS and G times
@@ -76,10 +76,16 @@ __device__ inline f16x4 as_f16x4(uint32_t lo, uint32_t hi)
 // READ_ONCE: one workgroup per (sequence, KV head, split) reads the head's codes, so they stream with the
 // non-temporal hint; with more than 4 query heads per KV head several workgroups (4 heads each) share the
 // code stream through their XCD's L2 and load normally.
-template <bool READ_ONCE>
+//
+// M = 32 (subspaces of 4 dims) runs as 64 VIRTUAL subspaces of 2 dims: virtual subspace v is the dim pair v & 1 of
+// real subspace v >> 1 and carries that subspace's code.  The packed codebook images are the same bytes either way
+// ([256][128 dims] fp16), so only the code loads differ: half the bytes per token, one K code byte serves two of
+// the four gathers of a score step, and two neighbouring lanes of the value pass share one V code stream.
+template <bool READ_ONCE, int M>
 __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_decode_args a)
 {
-    constexpr int M = 64;
+    static_assert(M == 64 || M == 32, "64 subspaces of 2 dims or 32 of 4");
+    constexpr int KVEC = M / 16;  // 16-byte vectors of K codes per lane and block
     constexpr int NW = GNW;
     __shared__ __attribute__((aligned(1024))) unsigned char smem[GSMEM_BYTES];
     lds_u8 *lbase = (lds_u8 *)smem;
@@ -148,21 +154,21 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     // One K and one V buffer per wavefront, each refilled as soon as its pass is over: the V codes
     // of a block are requested when its score pass starts, the K codes of the next block when
     // that score pass ends.  With 4 wavefronts per SIMD that is enough to keep the loads ahead.
-    uint4 kbuf[4], vbuf[4];
+    uint4 kbuf[KVEC], vbuf[4];
     // `live` false: a dead load by a wavefront that has run out of blocks (loads stay unconditional
     // so that the wait counts stay exact); all lanes then read the same 16 bytes, not 4 KiB.
-    auto load_k = [&](uint4 (&dst)[4], int blk_id, bool live) {
+    auto load_k = [&](uint4 (&dst)[KVEC], int blk_id, bool live) {
         const u32x4 *kp = (const u32x4 *)(k_head + (int64_t)blk_id * (64 * M)) + (live ? lane : 0);
         const int step = live ? 64 : 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < KVEC; ++j)
             dst[j] = load_codes<READ_ONCE>(kp + j * step);
     };
-    auto load_v = [&](int blk_id) {
-        const u32x4 *vp = (const u32x4 *)(v_head + (int64_t)blk_id * (64 * M)) + lane;
+    auto load_v = [&](int blk_id) {  // 4 tiles of 16 tokens; this lane's (real) subspace in each
+        const u32x4 *vp = (const u32x4 *)(v_head + (int64_t)blk_id * (64 * M)) + (M == 64 ? lane : lane >> 1);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            vbuf[j] = load_codes<READ_ONCE>(vp + j * 64);
+            vbuf[j] = load_codes<READ_ONCE>(vp + j * M);
     };
     int blk = blk0 + wave;
     *(lds_u32 *)(lbase + GCTR_OFF) = (uint32_t)(blk0 + NW);
@@ -188,12 +194,15 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
 #pragma unroll
     for (int r = 0; r < 16; ++r)
         idx[r] = 0x0c080400u + 0x10101010u * (uint32_t)((r + quad) & 15);
-    // gather r of a step: this lane's byte (r + 2 * (row / 2)) % 4 -> address = code << 8 | column
-    uint32_t ksel[4];
+    // gather r of a step: this lane's (virtual) subspace kk = (r + 2 * (row / 2)) % 4 of the step -> address =
+    // code << 8 | column.  M = 64: the step's word holds 4 codes, byte kk.  M = 32: a word holds two steps' 2 codes,
+    // byte kk / 2 of the step's half (ksel[r][1] for odd steps).
+    uint32_t ksel[4][2];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const uint32_t kk = (uint32_t)(r + (row & 2)) & 3u;
-        ksel[r] = 0x0c0c0000u | ((4u + kk) << 8) | kk;
+        ksel[r][0] = 0x0c0c0000u | ((4u + (M == 64 ? kk : kk >> 1)) << 8) | kk;
+        ksel[r][1] = 0x0c0c0000u | ((6u + (kk >> 1)) << 8) | kk;
     }
     const uint32_t rot2 = (row & 2) ? 0x07060504u : 0x03020100u;  // v_perm selector: first / second operand
     const uint32_t vcol = (uint32_t)(lane * 4) | ((VIMG_OFF >> 16) << 8);
@@ -222,11 +231,11 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         f32x4 sc0 = {0.f, 0.f, 0.f, 0.f}, sc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int U = 0; U < 16; ++U) {
-            const uint32_t w = comp(kbuf[U >> 2], U & 3);
+            const uint32_t w = M == 64 ? comp(kbuf[U >> 2], U & 3) : comp(kbuf[(U >> 3) % KVEC], (U >> 1) & 3);
             uint32_t got[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                got[r] = *(lds_u32 *)(lbase + __builtin_amdgcn_perm(w, idx[U], ksel[r]));
+                got[r] = *(lds_u32 *)(lbase + __builtin_amdgcn_perm(w, idx[U], ksel[r][M == 64 ? 0 : U & 1]));
             // lanes 2 and 3 of the quad hold their four results rotated by two registers: rotate back
             // (v_perm as a two-way select with a per-lane selector)
             uint32_t c[4];
@@ -468,17 +477,21 @@ int pq_grouped_heads_per_workgroup(int g)
 bool pq_config_uses_grouped_kernel(const pq_attn_config *cfg)
 {
     const int g = cfg->n_kv_heads > 0 ? cfg->n_q_heads / cfg->n_kv_heads : 0;
-    return cfg->dtype == PQ_F16 && cfg->n_subspaces == 64 && cfg->n_centroids == 256 && cfg->head_dim == PQ_HEAD_DIM &&
+    return cfg->dtype == PQ_F16 && (cfg->n_subspaces == 64 || cfg->n_subspaces == 32) && cfg->n_centroids == 256 &&
+           cfg->head_dim == PQ_HEAD_DIM &&
            pq_grouped_heads_per_workgroup(g) > 0;
 }
 
 hipError_t pq_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
 {
-    (void)ctx;
     const int grid = a.B * a.Hkv * (a.G / a.Gs) * a.S;
-    if (a.G == a.Gs)
-        hipLaunchKernelGGL(pq_decode_grouped_kernel<true>, dim3(grid), dim3(GNW * 64), 0, s, a);
-    else
-        hipLaunchKernelGGL(pq_decode_grouped_kernel<false>, dim3(grid), dim3(GNW * 64), 0, s, a);
+    const bool once = a.G == a.Gs;
+    if (ctx->cfg.n_subspaces == 64) {
+        if (once) hipLaunchKernelGGL((pq_decode_grouped_kernel<true, 64>), dim3(grid), dim3(GNW * 64), 0, s, a);
+        else hipLaunchKernelGGL((pq_decode_grouped_kernel<false, 64>), dim3(grid), dim3(GNW * 64), 0, s, a);
+    } else {
+        if (once) hipLaunchKernelGGL((pq_decode_grouped_kernel<true, 32>), dim3(grid), dim3(GNW * 64), 0, s, a);
+        else hipLaunchKernelGGL((pq_decode_grouped_kernel<false, 32>), dim3(grid), dim3(GNW * 64), 0, s, a);
+    }
     return hipGetLastError();
 }

@@ -32,7 +32,7 @@
 __host__ __device__ inline int64_t pq_k_code_offset(int64_t t, int i, int M, int skew)
 {
     const int l = (int)(t & 63);
-    const int rot = skew == PQ_K_SKEW_QUAD ? (l & ~3) : l;
+    const int rot = skew == PQ_K_SKEW_QUAD ? (l >> 2) * (M >> 4) : l;  // by quad: 4 (M = 64) or 2 (M = 32) subspaces per score step
     const int s = (i - rot) & (M - 1);  // M is a power of two
     return (t >> 6) * (64 * (int64_t)M) + (int64_t)(s >> 4) * 1024 + l * 16 + (s & 15);
 }
@@ -137,7 +137,7 @@ struct pq_encode_args {
 // launchers (each returns hipGetLastError() after its launches)
 hipError_t pq_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
 hipError_t pq_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
-// true when the grouped-query kernel serves this configuration (fp16, M = 64, 8-bit codes, Hq / Hkv a multiple of
+// true when the grouped-query kernel serves this configuration (fp16, M = 64 or 32, 8-bit codes, Hq / Hkv a multiple of
 // 2, 3 or 4); the kernel takes pq_grouped_heads_per_workgroup(Hq / Hkv) query heads per workgroup
 bool pq_config_uses_grouped_kernel(const pq_attn_config *cfg);
 int pq_grouped_heads_per_workgroup(int g);

@@ -16,6 +16,7 @@ CASES = [
     ("per_head", 2, 4, 4, 64, 9000, 40, 256, 3),
     ("grouped", 1, 8, 2, 64, 20000, 16, 256, 4),
     ("two_bit", 2, 2, 2, 32, 5000, 0, 256, 2),
+    ("two_bit_grouped", 1, 8, 2, 32, 12000, 9, 256, 3),
     ("pq12_fused", 1, 2, 2, 32, 9000, 8, 4096, 2),
     ("pq12_two_pass", 1, 2, 2, 32, 9000, 8, 4096, -2),
 ]

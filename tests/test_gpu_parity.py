@@ -47,7 +47,7 @@ def gpu_decode(w, data, n_splits=0, max_context=None, pass_codebooks=False):
 
 def k_offset(t, i, M, quad_skew=False):
     lane = t % 64
-    rot = (lane // 4) * 4 if quad_skew else lane
+    rot = (lane // 4) * (M // 16) if quad_skew else lane
     s = (i - rot) % M
     return (t // 64) * 64 * M + (s // 16) * 1024 + lane * 16 + s % 16
 
@@ -58,11 +58,11 @@ def v_offset(t, i, M):
 
 @pytest.mark.parametrize("M,Hq", [(64, 2), (32, 2), (64, 8), (32, 8)])
 def test_pack_layouts_and_unpack_roundtrip(M, Hq):
-    """Hq = 8 over 2 KV heads with M = 64 is served by the grouped-query kernel, whose K layout
-    rotates by lane quad instead of by lane."""
+    """Hq = 8 over 2 KV heads is served by the grouped-query kernel, whose K layout rotates by lane
+    quad (4 subspaces per quad at M = 64, 2 at M = 32) instead of by lane."""
     w = W.Workload("p", 2, Hq, 2, 128, M, 200, "f16", seed=5)
     data = W.generate(w)
-    quad = (M == 64 and Hq == 8)
+    quad = Hq == 8
     with PQSession(data, Hq, "f16") as s:
         cap = 256
         koff = lambda t, i, M: k_offset(t, i, M, quad)
@@ -102,6 +102,12 @@ CASES = [
     ("gqa4_m64_f32_per_head", 1, 4, 1, 64, "f32", (700,), 7, 2),
     ("gqa_edges", 6, 8, 2, 64, "f16", (0, 1, 63, 64, 65, 0), 8, 4),
     ("mha_m32_f16", 2, 4, 4, 32, "f16", (777, 4096), 20, 0),
+    ("gqa4_m32_f16", 2, 8, 2, 32, "f16", (3001, 640), 33, 3),
+    ("gqa4_m32_f16_s1", 2, 8, 2, 32, "f16", (2100, 129), 5, 1),
+    ("gqa3_m32_f16", 1, 6, 2, 32, "f16", (4097,), 7, 5),
+    ("gqa8_m32_f16_two_subgroups", 1, 8, 1, 32, "f16", (1500,), 7, 2),
+    ("gqa5_m32_f16_per_head", 1, 5, 1, 32, "f16", (1300,), 6, 2),
+    ("gqa_m32_edges", 6, 8, 2, 32, "f16", (0, 1, 63, 64, 65, 0), 8, 4),
     ("gqa_m32_f16_s5", 2, 8, 4, 32, "f16", (1500, 63), 9, 5),
     ("mha_m64_f32", 2, 2, 2, 64, "f32", (900, 65), 12, 2),
     ("mha_m32_f32", 2, 2, 2, 32, "f32", (300, 1025), 5, 3),
@@ -236,7 +242,8 @@ def test_split_exchange_is_never_stale_over_many_launches(Hq, Hkv, S):
 
 
 @pytest.mark.parametrize("M,dtype,n_new,n_old,Hq", [(32, "f16", 64, 100, 4), (64, "f16", 70, 0, 4), (32, "f32", 5, 60, 4),
-                                                    (64, "f32", 129, 3, 4), (64, "f16", 77, 150, 16)])
+                                                    (64, "f32", 129, 3, 4), (64, "f16", 77, 150, 16), (32, "f16", 70, 130, 16),
+                                                    (32, "f16", 3, 62, 8)])
 def test_encode_append_bit_exact_then_decode(M, dtype, n_new, n_old, Hq):
     ctx = n_old + n_new
     w = W.Workload("enc", 2, Hq, 4, 128, M, ctx, dtype, n_new=n_new, seed=100 + M + n_new)
@@ -463,6 +470,19 @@ def test_cfg3_full_size_gqa_outliers():
     check(got, ref, "cfg3")
     for h in range(w.n_q_heads):                     # worst head also within the bar
         check(got[:, h], ref[:, h], f"cfg3 head {h}")
+
+
+def test_grouped_queries_at_two_bits_per_dim_full_size():
+    """The grouped-query workload's shape with M = 32 (subspaces of 4 dims): the grouped kernel on virtual
+    2-dim subspaces."""
+    import dataclasses
+    w = dataclasses.replace(W.config(3), name="cfg3_shape_m32", n_subspaces=32, seed=W.BASE_SEED + 33)
+    data = W.generate(w)
+    got = gpu_decode(w, data)
+    ref = oracle_out(w, data)
+    check(got, ref, "32q/8kv x 128K, M=32")
+    for h in range(w.n_q_heads):
+        check(got[:, h], ref[:, h], f"head {h}")
 
 
 def test_cfg4_full_size_encode_then_decode():
