@@ -91,11 +91,19 @@ int pq_attn_n_passes(const pq_attn_ctx *ctx);
 
 /* Registers the codebooks trained offline (Section III-A, "Offline PQ Codebook
  * Training"): C_K, C_V as [Hkv][M][C][ds] in the context dtype, device memory.
- * The library keeps its own re-packed copy (centroid-major, the image the decode
- * kernel streams into LDS), so the caller's tensors are only read during this
- * call's kernels.  pq_attn_decode and pq_encode_append call this themselves when
- * they are handed codebook pointers that differ from the registered ones; a
- * caller that overwrites a registered codebook in place must call it again. */
+ * The kernels launched by this call copy them into context-owned memory (a plain
+ * copy for the encode kernels, a centroid-major image for the decode kernels); the
+ * caller's tensors are read by those kernels only and may be freed, overwritten
+ * or reused once they have run (i.e. after later work on the same stream, or a
+ * stream synchronisation).  The library keeps no pointer to them.
+ *
+ * pq_attn_decode and pq_encode_append take codebook pointers too: non-NULL
+ * pointers are registered by that call, on its stream, before its kernels (the
+ * copy costs a few microseconds per call — register once and pass NULL in a
+ * decoding loop).  A codebook changed in place has to be registered again.
+ * Registration must be stream-ordered with every other call on the context that
+ * uses the codebooks: with two streams (asynchronous quantization), register
+ * first, synchronise, then pass NULL on both. */
 int pq_attn_set_codebooks(pq_attn_ctx *ctx, const void *k_codebook /* device */,
                           const void *v_codebook /* device */, void *hip_stream);
 
@@ -139,8 +147,9 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
  * two are given different length arrays and the decode does not attend over the positions being
  * written (asynchronous quantization, Section III-B); the caller publishes the new lengths afterwards.
  *
- * With 12-bit codes the call stages the codes in context-owned memory; an append larger than any before on
- * this context allocates that memory and synchronises the device first.
+ * With 12-bit codes the call stages the codes in context-owned memory sized at pq_attn_create; a long
+ * append runs as several chunks through it (more launches, no allocation, no synchronisation).  Two appends
+ * on one context must not overlap.
  *
  * 0 < n_new <= max_context, else PQ_ERR_CAPACITY.  Tokens that would land beyond
  * max_context for some sequence are dropped, that sequence's length saturates, and

@@ -18,19 +18,24 @@
  *
  *   encode  (Eq. 4 read with Section II-C's "assigned to the nearest centroid"):
  *           for each sub-vector the index of the centroid at the smallest squared
- *           Euclidean distance, ties going to the lowest index.  The paper fixes no
- *           rounding, so the decision is taken in the arithmetic the GPU kernel uses:
- *           IEEE double, dist = fma(x_j - c_j, x_j - c_j, dist) for j = 0 .. ds-1 in
- *           order (each difference rounded once, each fused multiply-add rounded once;
- *           nothing else may be contracted: build with -ffp-contract=off).
+ *           Euclidean distance, equal distances going to the lowest index.  The paper
+ *           fixes no rounding; the distance is evaluated in IEEE double, left to right:
+ *           dist = 0, then for j = 0 .. ds-1  dist = fma(x_j - c_j, x_j - c_j, dist)
+ *           (each difference rounded once, each fused multiply-add rounded once;
+ *           nothing else may be contracted: build with -ffp-contract=off).  For fp16
+ *           inputs every difference is exact, and while distances stay below 32 so is
+ *           every sum: the code is then the exact-arithmetic nearest centroid.  Beyond
+ *           that it is the nearest centroid up to two roundings of 2^-53 relative.
  *
  * Pins (tests that hold it to something other than itself): brute-force
  * attention with library softmax on tiny inputs, codebooks that contain the
  * source vectors (exact dense attention), softmax weights summing to one, q = 0
  * giving the mean of the value rows, single-token and all-equal-code closed
  * forms, permutation and code/recent exchange invariance, GQA as replicated MHA,
- * the table-sum form of Eq. 7 in double, duplicated centroids and exact-hit
- * cases for encode.  No function here is "parity unpinned".
+ * the table-sum form of Eq. 7 in double; for encode a library vector quantizer,
+ * duplicated centroids, exact hits, and exact integer arithmetic (fp16 values as
+ * integers x 2^-24) on large magnitudes, near-midpoint tokens, subnormals and ties.
+ * No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>

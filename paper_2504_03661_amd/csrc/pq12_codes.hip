@@ -15,6 +15,7 @@
 
 #include "pq_internal.h"
 #include "pq_device_utils.h"
+#include "pq_filter_constants.h"
 
 namespace {
 
@@ -204,9 +205,9 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
         u32x2e neg = raw ^ 0x80008000u;
         asm volatile("" : "+v"(neg));  // keep the negated operand in its registers
         bop[q] = __builtin_bit_cast(f16x4, neg);
-        const float t0 = n_max + x1s * c_max + 0.5025f * x2s;
-        float off = 0.5025f * x2s + 2.0f * (3.1e-06f * (2.0f * t0) + 2.4e-07f);
-        tau[q] = 3.1e-06f * (t0 + off) + 2.4e-07f;
+        const float t0 = n_max + x1s * c_max + PQ_FILTER_X2_FACTOR * x2s;
+        float off = PQ_FILTER_X2_FACTOR * x2s + 2.0f * (PQ_FILTER_TAU_REL * (2.0f * t0) + PQ_FILTER_TAU_ABS);
+        tau[q] = PQ_FILTER_TAU_REL * (t0 + off) + PQ_FILTER_TAU_ABS;
         off += tau[q];
         off4[q] = f32x4e{off, off, off, off};
         bad[q] = cb_bad || !(off < 1.0e30f);
@@ -346,7 +347,7 @@ constexpr int FEW12_WAVES = 16;
 __global__ __launch_bounds__(FEW12_WAVES * 64) void pq12_encode_few_kernel(const __half *x0, const __half *x1,
                                                                           const __half *cb0, const __half *cb1,
                                                                           uint16_t *out0, uint16_t *out1, int B, int Hkv,
-                                                                          int n_new)
+                                                                          int n_new, int64_t x_head_stride)
 {
 #pragma clang fp contract(off)
     static_assert(FEW12_TOKENS <= 64, "lane u fetches token u");
@@ -379,7 +380,7 @@ __global__ __launch_bounds__(FEW12_WAVES * 64) void pq12_encode_few_kernel(const
     const int t_mine = u_mine - b_mine * n_new;
     double x_mine[4];
     {
-        const u32x2e raw = *(const u32x2e *)(x + ((((int64_t)b_mine * Hkv + hkv) * n_new + t_mine) * PQ_HEAD_DIM + i * 4));
+        const u32x2e raw = *(const u32x2e *)(x + ((((int64_t)b_mine * Hkv + hkv) * x_head_stride + t_mine) * PQ_HEAD_DIM + i * 4));
         const f16x4 v = __builtin_bit_cast(f16x4, raw);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -549,14 +550,14 @@ hipError_t pq12_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint16
     return hipGetLastError();
 }
 
-hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len,
+hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_args &a, int64_t x_rows, int32_t *ctx_len,
                                      unsigned int *dev_err, hipStream_t s)
 {
     const int64_t n_tok = (int64_t)a.B * a.n_new;  // tokens of a head over all sequences
     if (n_tok <= FEW12_TOKENS) {
         hipLaunchKernelGGL(pq12_encode_few_kernel, dim3((unsigned)a.Hkv, PQ12_M, 2), dim3(FEW12_WAVES * 64), 0, s,
                            (const __half *)a.x[0], (const __half *)a.x[1], (const __half *)a.codebook[0],
-                           (const __half *)a.codebook[1], ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new);
+                           (const __half *)a.codebook[1], ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, x_rows);
     } else if (n_tok < ((int64_t)1 << 30)) {
         // matrix-core filter: 8 wavefronts per workgroup, each takes 64 NQ tokens of the head
         const int nq = n_tok > 64 * F12_WAVES ? 2 : 1;
@@ -565,18 +566,18 @@ hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_arg
         if (nq == 2)
             hipLaunchKernelGGL(pq12_encode_fast_kernel<2>, grid, dim3(F12_WAVES * 64), 0, s, (const __half *)a.x[0],
                                (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
-                               ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, (int64_t)a.n_new);
+                               ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, x_rows);
         else
             hipLaunchKernelGGL(pq12_encode_fast_kernel<1>, grid, dim3(F12_WAVES * 64), 0, s, (const __half *)a.x[0],
                                (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
-                               ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, (int64_t)a.n_new);
+                               ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, x_rows);
     } else {
         const int n_chunks = (a.n_new + 63) >> 6;
         const int groups_per_head = (a.B * n_chunks + E12_WAVES - 1) / E12_WAVES;
         const dim3 grid((unsigned)(a.Hkv * groups_per_head), PQ12_M, 2);
         hipLaunchKernelGGL(pq12_encode_kernel, grid, dim3(E12_WAVES * 64), 0, s, (const __half *)a.x[0],
                            (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
-                           ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, (int64_t)a.n_new);
+                           ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, x_rows);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess)

@@ -91,35 +91,50 @@ int choose_splits(const pq_attn_config *c, int n_cu)
     return (int)s;
 }
 
-int ensure_codebooks(pq_attn_ctx *ctx, const void *k, const void *v, hipStream_t s, bool force)
+// Codebook pointers passed to an entry point are registered there and then: the context copies them on the
+// stream (its own natural-layout copy for the encode kernels, the centroid-major image for the decode
+// kernels) and never looks at the caller's tensors again.  NULL, NULL means "the registered ones".
+int ensure_codebooks(pq_attn_ctx *ctx, const void *k, const void *v, hipStream_t s)
 {
-    if (k == nullptr && v == nullptr && !force)
-        return (ctx->reg_k && ctx->reg_v) ? PQ_OK : PQ_ERR_NULL;
+    if (k == nullptr && v == nullptr)
+        return ctx->registered ? PQ_OK : PQ_ERR_NULL;
     if (k == nullptr || v == nullptr)
         return PQ_ERR_NULL;
-    if (!force && k == ctx->reg_k && v == ctx->reg_v)
-        return PQ_OK;
     if (pq_config_is_12bit(&ctx->cfg)) {
-        // the 12-bit kernels read the natural layout [Hkv][M][4096][ds]: the context keeps a plain copy
-        const size_t bytes = (size_t)ctx->cfg.n_kv_heads * PQ12_M * PQ12_CENTROIDS * 4 * sizeof(uint16_t);
-        if (hipMemcpyAsync(ctx->kcb_packed, k, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess ||
-            hipMemcpyAsync(ctx->vcb_packed, v, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess)
+        // the 12-bit kernels read the natural layout [Hkv][M][4096][ds]: one plain copy serves both paths
+        const int64_t bytes = (int64_t)ctx->cfg.n_kv_heads * PQ12_M * PQ12_CENTROIDS * 4 * sizeof(uint16_t);
+        if (pq_launch_copy16(k, ctx->kcb_packed, bytes, s) != hipSuccess ||
+            pq_launch_copy16(v, ctx->vcb_packed, bytes, s) != hipSuccess)
             return PQ_ERR_HIP;
     } else {
-        if (pq_launch_pack_codebook(ctx, k, ctx->kcb_packed, s) != hipSuccess)
+        if (pq_launch_pack_codebook(ctx, k, ctx->kcb_packed, ctx->kcb_natural, s) != hipSuccess)
             return PQ_ERR_HIP;
-        if (pq_launch_pack_codebook(ctx, v, ctx->vcb_packed, s) != hipSuccess)
+        if (pq_launch_pack_codebook(ctx, v, ctx->vcb_packed, ctx->vcb_natural, s) != hipSuccess)
             return PQ_ERR_HIP;
     }
-    ctx->reg_k = k;
-    ctx->reg_v = v;
+    ctx->registered = true;
     return PQ_OK;
+}
+
+// Tokens per (sequence, KV head) the staging buffers of a 12-bit context hold: the whole capacity when that is
+// small, otherwise what 8 MiB per tensor give (an append of more tokens runs as several chunks), at least 64.
+int32_t stage_tokens_for(const pq_attn_config *c)
+{
+    const int64_t heads = (int64_t)c->batch * c->n_kv_heads;
+    int64_t t = ((int64_t)8 << 20) / (heads * PQ12_M * (int64_t)sizeof(uint16_t));
+    if (t < 64)
+        t = 64;
+    if (t > c->max_context)
+        t = c->max_context;
+    return (int32_t)t;
 }
 
 void free_ctx(pq_attn_ctx *ctx)
 {
     if (ctx->kcb_packed) (void)hipFree(ctx->kcb_packed);
     if (ctx->vcb_packed) (void)hipFree(ctx->vcb_packed);
+    if (ctx->kcb_natural && ctx->kcb_natural != ctx->kcb_packed) (void)hipFree(ctx->kcb_natural);
+    if (ctx->vcb_natural && ctx->vcb_natural != ctx->vcb_packed) (void)hipFree(ctx->vcb_natural);
     if (ctx->partials) (void)hipFree(ctx->partials);
     if (ctx->tickets) (void)hipFree(ctx->tickets);
     if (ctx->dev_err) (void)hipFree(ctx->dev_err);
@@ -198,6 +213,17 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     ok = ok && hipMalloc((void **)&ctx->dev_err, 2 * sizeof(unsigned int)) == hipSuccess;  // [1]: probe sink
     if (two_pass)  // partial scores [B*Hq][4 groups][capacity]
         ok = ok && hipMalloc((void **)&ctx->scores12, n_bh * 4 * (size_t)ctx->cap_padded * sizeof(float)) == hipSuccess;
+    if (pq_config_is_12bit(cfg)) {
+        ctx->kcb_natural = ctx->kcb_packed;
+        ctx->vcb_natural = ctx->vcb_packed;
+        ctx->stage_tokens = stage_tokens_for(cfg);
+        const size_t st_bytes = (size_t)cfg->batch * cfg->n_kv_heads * ctx->stage_tokens * PQ12_M * sizeof(uint16_t);
+        ok = ok && hipMalloc((void **)&ctx->stage[0], st_bytes) == hipSuccess;
+        ok = ok && hipMalloc((void **)&ctx->stage[1], st_bytes) == hipSuccess;
+    } else {
+        ok = ok && hipMalloc(&ctx->kcb_natural, cb_bytes) == hipSuccess;
+        ok = ok && hipMalloc(&ctx->vcb_natural, cb_bytes) == hipSuccess;
+    }
     if (!ok) {
         (void)hipGetLastError();
         free_ctx(ctx);
@@ -239,7 +265,7 @@ int pq_attn_set_codebooks(pq_attn_ctx *ctx, const void *k_codebook, const void *
     device_guard guard(ctx->cfg.device);
     if (!guard.ok)
         return PQ_ERR_HIP;
-    return ensure_codebooks(ctx, k_codebook, v_codebook, (hipStream_t)hip_stream, true);
+    return ensure_codebooks(ctx, k_codebook, v_codebook, (hipStream_t)hip_stream);
 }
 
 int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, const uint8_t *v_codes,
@@ -259,7 +285,7 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
     if (!guard.ok)
         return PQ_ERR_HIP;
     hipStream_t s = (hipStream_t)hip_stream;
-    const int rc = ensure_codebooks(ctx, k_codebook, v_codebook, s, false);
+    const int rc = ensure_codebooks(ctx, k_codebook, v_codebook, s);
     if (rc != PQ_OK)
         return rc;
 
@@ -305,15 +331,15 @@ int pq_encode_append(pq_attn_ctx *ctx, const void *new_k, const void *new_v, int
         return PQ_ERR_HIP;
     hipStream_t s = (hipStream_t)hip_stream;
     // keeps the decode path's packed copy in step with the codebooks used to encode
-    const int rc = ensure_codebooks(ctx, k_codebook, v_codebook, s, false);
+    const int rc = ensure_codebooks(ctx, k_codebook, v_codebook, s);
     if (rc != PQ_OK)
         return rc;
 
     pq_encode_args a;
     a.x[0] = new_k;
     a.x[1] = new_v;
-    a.codebook[0] = ctx->reg_k;
-    a.codebook[1] = ctx->reg_v;
+    a.codebook[0] = ctx->kcb_natural;  // the context's own copies, never the caller's tensors
+    a.codebook[1] = ctx->vcb_natural;
     a.codes[0] = k_codes;
     a.codes[1] = v_codes;
     a.ctx_len = ctx_len;
@@ -324,26 +350,16 @@ int pq_encode_append(pq_attn_ctx *ctx, const void *new_k, const void *new_v, int
     a.k_skew = ctx->k_skew;
     a.head_stride = ctx->cap_padded * token_bytes(&ctx->cfg);
     if (pq_config_is_12bit(&ctx->cfg)) {
-        // codes are staged token-major (uint16) and packed by a second kernel; the staging buffers grow on demand
-        if (n_new > ctx->stage_tokens) {
-            const size_t bytes = (size_t)ctx->cfg.batch * ctx->cfg.n_kv_heads * n_new * PQ12_M * sizeof(uint16_t);
-            if (hipDeviceSynchronize() != hipSuccess)  // earlier appends may still read the old buffers
+        // codes are staged token-major (uint16) and packed by a second kernel; the staging buffers were sized at
+        // creation, a longer append goes through them in chunks (each chunk: encode, pack, advance the lengths)
+        for (int32_t t0 = 0; t0 < n_new; t0 += ctx->stage_tokens) {
+            a.n_new = n_new - t0 < ctx->stage_tokens ? n_new - t0 : ctx->stage_tokens;
+            a.x[0] = (const char *)new_k + (int64_t)t0 * PQ_HEAD_DIM * sizeof(uint16_t);
+            a.x[1] = (const char *)new_v + (int64_t)t0 * PQ_HEAD_DIM * sizeof(uint16_t);
+            if (pq12_launch_encode_append(ctx, a, n_new, ctx_len, ctx->dev_err, s) != hipSuccess)
                 return PQ_ERR_HIP;
-            for (int w = 0; w < 2; ++w) {
-                if (ctx->stage[w]) (void)hipFree(ctx->stage[w]);
-                ctx->stage[w] = nullptr;
-            }
-            ctx->stage_tokens = 0;
-            if (hipMalloc((void **)&ctx->stage[0], bytes) != hipSuccess ||
-                hipMalloc((void **)&ctx->stage[1], bytes) != hipSuccess) {
-                (void)hipGetLastError();
-                return PQ_ERR_ALLOC;
-            }
-            ctx->stage_tokens = n_new;
         }
-        a.codebook[0] = ctx->kcb_packed;  // the context's own copies (natural layout)
-        a.codebook[1] = ctx->vcb_packed;
-        return pq12_launch_encode_append(ctx, a, ctx_len, ctx->dev_err, s) == hipSuccess ? PQ_OK : PQ_ERR_HIP;
+        return PQ_OK;
     }
     return pq_launch_encode(ctx, a, ctx_len, ctx->dev_err, s) == hipSuccess ? PQ_OK : PQ_ERR_HIP;
 }

@@ -92,16 +92,18 @@ struct pq_attn_ctx {
     int k_skew;           // PQ_K_SKEW_*: which decode kernel this context runs, hence its K code layout
     int64_t cap_padded;   // max_context rounded up to 64 tokens
     size_t elem_bytes;    // 2 or 4
-    void *kcb_packed;     // [Hkv][256][M][ds] dtype   (centroid-major)
+    void *kcb_packed;     // [Hkv][256][M][ds] dtype   (centroid-major); 12-bit contexts: the natural layout
     void *vcb_packed;     // [Hkv][256][M][ds] dtype
-    const void *reg_k;    // caller pointers the packed copies were made from
-    const void *reg_v;
+    void *kcb_natural;    // the context's own copy of the registered codebooks in the caller's layout
+    void *vcb_natural;    // [Hkv][M][C][ds] (what the encode kernels read); 12-bit contexts: = *_packed
+    bool registered;      // codebooks have been registered (the copies above hold them)
     float *partials;      // [B*Hq][n_splits][PQ_PART_STRIDE]
     unsigned int *tickets;  // [B*Hq], zero between calls
     unsigned int *dev_err;  // sticky error word
-    // 12-bit contexts: token-major uint16 staging of an append's codes, grown on demand
+    // 12-bit contexts: token-major uint16 staging of an append's codes, sized once at creation; a longer
+    // append runs as several chunks of at most stage_tokens tokens per (sequence, KV head)
     uint16_t *stage[2];
-    int64_t stage_tokens;   // tokens per (sequence, KV head) the staging buffers hold
+    int32_t stage_tokens;
     // 12-bit contexts that decode in two passes: partial scores [B*Hq][4][cap_padded]; n_splits then counts the
     // token ranges of the second pass
     float *scores12;
@@ -145,7 +147,8 @@ hipError_t pq_launch_encode(const pq_attn_ctx *ctx, const pq_encode_args &a, int
                             hipStream_t s);
 // lengths += n_new, saturating at max_context (sets the overflow flag)
 hipError_t pq_launch_bump_len(int32_t *ctx_len, int B, int n_new, int max_context, unsigned int *dev_err, hipStream_t s);
-hipError_t pq_launch_pack_codebook(const pq_attn_ctx *ctx, const void *src, void *dst, hipStream_t s);
+// src [Hkv][M][256][ds] (caller memory) -> packed [Hkv][256][M][ds] and a plain copy in the source layout
+hipError_t pq_launch_pack_codebook(const pq_attn_ctx *ctx, const void *src, void *packed, void *natural, hipStream_t s);
 hipError_t pq_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint8_t *token_major, int n_tokens,
                                 uint8_t *packed, bool unpack, hipStream_t s);
 hipError_t pq_launch_stream_read(const void *src, int64_t bytes, uint32_t *sink, hipStream_t s);
@@ -159,8 +162,12 @@ hipError_t pq_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n_s
 // packing of the staged codes behind the current lengths, and the layout conversions of whole tensors
 bool pq_config_is_12bit(const pq_attn_config *cfg);
 hipError_t pq12_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
-hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len,
+// a.x holds rows [B][Hkv][x_rows][d]; rows 0 .. a.n_new - 1 of every head are encoded and appended
+// (a.n_new <= ctx->stage_tokens)
+hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_args &a, int64_t x_rows, int32_t *ctx_len,
                                      unsigned int *dev_err, hipStream_t s);
+// plain device-to-device copy of `bytes` bytes (a multiple of 16, 16-byte aligned) by a kernel
+hipError_t pq_launch_copy16(const void *src, void *dst, int64_t bytes, hipStream_t s);
 hipError_t pq12_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint16_t *token_major, int n_tokens,
                                   uint8_t *packed, bool unpack, hipStream_t s);
 // pieces of the training shared by the 8-bit and the 12-bit path

@@ -9,8 +9,9 @@
 namespace {
 
 // [Hkv][M][256][ds] -> [Hkv][256][M][ds]; one thread per (head, centroid, subspace)
+// (also writes `nat`, a plain copy of src: the context's own codebooks for the encode kernels)
 template <typename E>
-__global__ void pq_pack_codebook_kernel(const E *src, E *dst, int Hkv, int M, int ds)
+__global__ void pq_pack_codebook_kernel(const E *src, E *dst, E *nat, int Hkv, int M, int ds)
 {
     const int64_t n = (int64_t)Hkv * 256 * M;
     const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -19,10 +20,20 @@ __global__ void pq_pack_codebook_kernel(const E *src, E *dst, int Hkv, int M, in
     const int i = (int)(x % M);
     const int c = (int)((x / M) % 256);
     const int h = (int)(x / ((int64_t)M * 256));
-    const E *s = src + (((int64_t)h * M + i) * 256 + c) * ds;
+    const int64_t so = (((int64_t)h * M + i) * 256 + c) * ds;
     E *d = dst + x * ds;
-    for (int j = 0; j < ds; ++j)
-        d[j] = s[j];
+    for (int j = 0; j < ds; ++j) {
+        const E v = src[so + j];
+        d[j] = v;
+        nat[so + j] = v;
+    }
+}
+
+__global__ void pq_copy16_kernel(const u32x4 *src, u32x4 *dst, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+        dst[i] = src[i];
 }
 
 // one thread per code byte of the token-major tensor
@@ -60,17 +71,17 @@ __global__ __launch_bounds__(1024) void pq_stream_read_kernel(const u32x4 *p, in
 
 }  // namespace
 
-hipError_t pq_launch_pack_codebook(const pq_attn_ctx *ctx, const void *src, void *dst, hipStream_t s)
+hipError_t pq_launch_pack_codebook(const pq_attn_ctx *ctx, const void *src, void *dst, void *natural, hipStream_t s)
 {
     const int Hkv = ctx->cfg.n_kv_heads, M = ctx->cfg.n_subspaces, ds = ctx->ds;
     const int64_t n = (int64_t)Hkv * 256 * M;
     const dim3 grid((unsigned)((n + 255) / 256)), block(256);
     if (ctx->cfg.dtype == PQ_F16)
         hipLaunchKernelGGL(pq_pack_codebook_kernel<uint16_t>, grid, block, 0, s, (const uint16_t *)src,
-                           (uint16_t *)dst, Hkv, M, ds);
+                           (uint16_t *)dst, (uint16_t *)natural, Hkv, M, ds);
     else
         hipLaunchKernelGGL(pq_pack_codebook_kernel<uint32_t>, grid, block, 0, s, (const uint32_t *)src,
-                           (uint32_t *)dst, Hkv, M, ds);
+                           (uint32_t *)dst, (uint32_t *)natural, Hkv, M, ds);
     return hipGetLastError();
 }
 
@@ -85,6 +96,17 @@ hipError_t pq_launch_pack_codes(const pq_attn_ctx *ctx, int kind, const uint8_t 
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     hipLaunchKernelGGL(pq_pack_codes_kernel, grid, block, 0, s, token_major, packed, n_heads, n_tokens, M,
                        ctx->cap_padded * M, kind, unpack ? 1 : 0, ctx->k_skew);
+    return hipGetLastError();
+}
+
+hipError_t pq_launch_copy16(const void *src, void *dst, int64_t bytes, hipStream_t s)
+{
+    const int64_t n = bytes / 16;
+    if (n == 0)
+        return hipSuccess;
+    const int64_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(pq_copy16_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s, (const u32x4 *)src,
+                       (u32x4 *)dst, n);
     return hipGetLastError();
 }
 

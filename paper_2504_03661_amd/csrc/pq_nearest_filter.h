@@ -9,6 +9,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "pq_filter_constants.h"
+
 namespace {
 
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
@@ -83,9 +85,9 @@ __device__ inline void pq_filter_codes(const unsigned char *arow, const double *
         }
         // off: |x|^2/2 with half a per cent on top, plus the same again as tau and a floor, so that every
         // computed value stays above zero; T = N + X C + off; tau = 2^-18.3 T + 2^-22
-        const float t0 = n_max + x1 * c_max + 0.5025f * x2;
-        float off = 0.5025f * x2 + 2.0f * (3.1e-06f * (2.0f * t0) + 2.4e-07f);
-        tau[q] = 3.1e-06f * (t0 + off) + 2.4e-07f;
+        const float t0 = n_max + x1 * c_max + PQ_FILTER_X2_FACTOR * x2;
+        float off = PQ_FILTER_X2_FACTOR * x2 + 2.0f * (PQ_FILTER_TAU_REL * (2.0f * t0) + PQ_FILTER_TAU_ABS);
+        tau[q] = PQ_FILTER_TAU_REL * (t0 + off) + PQ_FILTER_TAU_ABS;
         off += tau[q];
         off4[q] = f32x4e{off, off, off, off};
         bad[q] |= !(off < 1.0e30f);

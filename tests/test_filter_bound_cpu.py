@@ -1,12 +1,26 @@
 """The fp16 encode decides codes in fp64 but first filters centroids with fp32 matrix-core sums; the filter is safe
 if its threshold tau is at least twice the largest deviation of a computed value from the true one.  This test
-re-computes the kernel's tau (the constants of pq_nearest_filter.h / pq12_codes.hip) and checks it against an
+re-computes the kernel's tau (with the constants of csrc/pq_filter_constants.h, which both encode kernels include) and checks it against an
 emulation of the sums under the WORST rounding the bound allows for — every fp32 addition truncated toward zero,
 terms added one after the other — on random inputs of very different magnitudes."""
+import os
+import re
+
 import numpy as np
 import pytest
 
-K_REL, K_ABS = np.float32(3.1e-06), np.float32(2.4e-07)       # tau = K_REL * T + K_ABS
+_HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2504_03661_amd", "csrc",
+                       "pq_filter_constants.h")
+
+
+def _constant(name):
+    """The value the kernels are compiled with: parsed from the header both encode kernels include."""
+    m = re.search(r"^#define\s+" + name + r"\s+([0-9.eE+-]+)f\s*$", open(_HEADER).read(), re.M)
+    assert m, name
+    return np.float32(m.group(1))
+
+
+K_REL, K_ABS, X2F = _constant("PQ_FILTER_TAU_REL"), _constant("PQ_FILTER_TAU_ABS"), _constant("PQ_FILTER_X2_FACTOR")
 
 
 def trunc32(v):
@@ -23,8 +37,8 @@ def kernel_tau_and_off(x, n_max, c_max):
     for j in range(x.shape[1]):
         x1 = x1 + np.abs(x[:, j])
         x2 = x2 + x[:, j] * x[:, j]
-    t0 = n_max + x1 * c_max + np.float32(0.5025) * x2
-    off = np.float32(0.5025) * x2 + np.float32(2.0) * (K_REL * (np.float32(2.0) * t0) + K_ABS)
+    t0 = n_max + x1 * c_max + X2F * x2
+    off = X2F * x2 + np.float32(2.0) * (K_REL * (np.float32(2.0) * t0) + K_ABS)
     tau = K_REL * (t0 + off) + K_ABS
     return tau, off + tau
 

@@ -59,9 +59,11 @@ def test_decode_replays_from_a_graph(case):
             assert dev <= 4e-6, f"{name}: replay {rep} differs from the eager call by {dev:.3e}"
 
 
-def test_append_and_decode_in_one_graph():
-    """One decoding step as a caller would capture it: append 3 tokens per head, then attend."""
-    w = W.Workload("graph_step", 2, 4, 4, 128, 64, 700, "f16", n_new=3, seed=78)
+@pytest.mark.parametrize("M,C", [(64, 256), (32, 4096)], ids=["8bit", "12bit"])
+def test_append_and_decode_in_one_graph(M, C):
+    """One decoding step as a caller would capture it: append 3 tokens per head, then attend.  (12-bit codes: the
+    append stages its codes in memory the context allocated at creation, so the very first append is capturable.)"""
+    w = W.Workload("graph_step", 2, 4, 4, 128, M, 700, "f16", n_new=3, seed=78, n_centroids=C)
     data = W.generate(w, ctx_cap=800)
     scale = W.attention_scale(w)
     nk, nv = torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda()

@@ -436,17 +436,88 @@ def test_argument_errors_on_gpu():
         check(out.cpu().numpy(), oracle_out(w, data), "after errors")
 
 
+# ------------------------------------------------------------------ codebook ownership
+
+
+@pytest.mark.parametrize("M,dtype,Hq,C", [(64, "f16", 4, 256), (32, "f16", 8, 256), (64, "f32", 4, 256), (32, "f16", 2, 4096)])
+def test_registered_codebooks_are_copied_not_referenced(M, dtype, Hq, C):
+    """After pq_attn_set_codebooks the context works from its own copies: the caller's tensors are overwritten with
+    NaN, then tokens are appended and attended with NULL codebook pointers — codes bit-exact, output within the bar."""
+    n_old, n_new = 300, 70
+    ctx = n_old + n_new
+    w = W.Workload("own", 2, Hq, 2, 128, M, ctx, dtype, recent_cap=8, recent_fixed=5, n_new=n_new, seed=4242 + M + C,
+                   n_centroids=C)
+    data = W.generate(w, ctx_cap=ctx + 20)
+    with PQSession(data, Hq, dtype, max_context=ctx + 20) as s:       # registers the codebooks
+        torch.cuda.synchronize()
+        s.k_codebook.fill_(float("nan"))
+        s.v_codebook.fill_(float("nan"))
+        torch.cuda.synchronize()
+        s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())
+        out = s.decode(W.attention_scale(w)).cpu().numpy()
+        got_k = s.unpack(PQ_CODES_K, ctx)
+        got_v = s.unpack(PQ_CODES_V, ctx)
+        assert s.device_error() == 0
+    exp_k = data["k_codes"][:, :, :ctx].copy()
+    exp_v = data["v_codes"][:, :, :ctx].copy()
+    exp_k[:, :, n_old:] = O.encode(data["new_k"], data["k_codebook"])
+    exp_v[:, :, n_old:] = O.encode(data["new_v"], data["v_codebook"])
+    np.testing.assert_array_equal(got_k, exp_k)
+    np.testing.assert_array_equal(got_v, exp_v)
+    check(out, oracle_out(w, data, ctx_len=np.full((2,), ctx, np.int32), k_codes=exp_k, v_codes=exp_v),
+          "decode from the context's own codebook copies")
+
+
+def test_codebooks_at_a_reused_address_are_registered_again():
+    """Codebook pointers handed to decode / append are registered by that call whatever was registered before:
+    new centroids written into the SAME device tensors must take effect (no caching by address)."""
+    w = W.Workload("reuse", 1, 4, 4, 128, 64, 500, "f16", n_new=9, seed=515)
+    data = W.generate(w, ctx_cap=520)
+    other = W.generate(W.Workload("reuse_b", 1, 4, 4, 128, 64, 500, "f16", n_new=9, seed=516), ctx_cap=520)
+    with PQSession(data, 4, "f16", max_context=520) as s:
+        first = s.decode(W.attention_scale(w)).cpu().numpy()
+        check(first, oracle_out(w, data), "first codebooks")
+        s.k_codebook.copy_(torch.from_numpy(other["k_codebook"]))    # same tensors, new centroids
+        s.v_codebook.copy_(torch.from_numpy(other["v_codebook"]))
+        data["k_codebook"], data["v_codebook"] = other["k_codebook"], other["v_codebook"]
+        second = s.decode(W.attention_scale(w), pass_codebooks=True).cpu().numpy()
+        check(second, oracle_out(w, data), "second codebooks at the same address")
+        s.ctx_len.fill_(491)
+        s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())   # NULL: registered
+        got = s.unpack(PQ_CODES_K, 500)[:, :, 491:]
+    np.testing.assert_array_equal(got, O.encode(data["new_k"], data["k_codebook"]))
+
+
 # ------------------------------------------------------------------ the named workloads at full size
 
 
 def test_decode_at_maximum_capacity():
     """One head at the capacity limit of the interface, 2^24 tokens (1 GiB of K codes, 1 GiB of V codes), with
-    the largest split count; the whole output row is compared with the oracle."""
+    the largest split count; the whole output row is compared with the oracle (which needs about 36 GB of host
+    memory for the de-quantized rows: skipped on a smaller host, the periodic case below runs everywhere)."""
+    import psutil
+    if psutil.virtual_memory().available < (48 << 30):
+        pytest.skip("the oracle needs ~36 GB of host memory for 2^24 de-quantized rows")
     n = 1 << 24
     w = W.Workload("max_capacity", 1, 1, 1, 128, 64, n, "f16", recent_cap=4, recent_fixed=4, seed=99)
     data = W.generate(w)
     got = gpu_decode(w, data, n_splits=64)
     check(got, oracle_out(w, data), "2^24 tokens")
+
+
+def test_decode_at_maximum_capacity_periodic_codes():
+    """2^24 tokens whose codes repeat with a period of 2^16 tokens and no recent rows: every distinct row appears
+    256 times, so softmax attention over all of them equals attention over one period — which the oracle evaluates."""
+    period, n = 1 << 16, 1 << 24
+    w = W.Workload("max_capacity_periodic", 1, 1, 1, 128, 64, period, "f16", seed=98)
+    small = W.generate(w)
+    ref = oracle_out(w, small)
+    big = dict(small)
+    big["k_codes"] = np.tile(small["k_codes"], (1, 1, n // period, 1))
+    big["v_codes"] = np.tile(small["v_codes"], (1, 1, n // period, 1))
+    big["ctx_len"] = np.full((1,), n, np.int32)
+    got = gpu_decode(w, big, n_splits=64)
+    check(got, ref, "2^24 periodic tokens")
 
 
 def test_cfg1_full_size():
@@ -501,9 +572,9 @@ def test_cfg4_full_size_encode_then_decode():
     np.testing.assert_array_equal(tail_v, exp_v)
     data["k_codes"][:, :, n_old:] = exp_k
     data["v_codes"][:, :, n_old:] = exp_v
-    rng = np.random.default_rng(0)
-    pairs = [(int(b), int(h)) for b, h in zip(rng.integers(0, w.batch, 24), rng.integers(0, w.n_q_heads, 24))]
-    ref = oracle_out(w, data, ctx_len=np.full((w.batch,), w.context, np.int32), pairs=pairs)
-    for b, h in pairs:
-        check(out[b, h], ref[b, h], f"cfg4 ({b},{h})")
-    assert np.isfinite(out).all()
+    # every (sequence, head) row: this is the only M = 32 per-head workload whose grid exceeds the chip's compute units
+    ref = oracle_out(w, data, ctx_len=np.full((w.batch,), w.context, np.int32))
+    check(out, ref, "cfg4")
+    for b in range(w.batch):
+        for h in range(w.n_q_heads):
+            check(out[b, h], ref[b, h], f"cfg4 ({b},{h})")

@@ -197,6 +197,29 @@ def test_encode_append_bit_exact_then_decode(n_old, n_new):
         check(out.cpu().numpy(), ref, "after append")
 
 
+def test_long_append_runs_in_chunks_through_the_fixed_staging():
+    """The staging of a 12-bit context is sized at creation (8 MiB per tensor, at least 64 tokens per head); an
+    append of more tokens per head runs as several chunks: 512 (sequence, head) pairs leave 256 tokens per chunk,
+    515 tokens are three chunks (256 + 256 + 3, the last one through the few-token kernel).  Codes bit-exact,
+    lengths advanced chunk by chunk."""
+    B_, Hkv, n_old, n_new = 4, 128, 5, 515
+    w = W.Workload("chunks12", B_, Hkv, Hkv, 128, 32, n_old + n_new, "f16", n_new=n_new, seed=4700, n_centroids=4096)
+    data = W.generate(w)
+    want_k = O.encode(data["new_k"], data["k_codebook"])
+    want_v = O.encode(data["new_v"], data["v_codebook"])
+    with PQSession(data, Hkv, "f16") as s:
+        s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())
+        torch.cuda.synchronize()
+        assert (s.ctx_len.cpu().numpy() == n_old + n_new).all()
+        got_k = s.unpack(PQ_CODES_K, n_old + n_new)
+        got_v = s.unpack(PQ_CODES_V, n_old + n_new)
+        assert s.device_error() == 0
+    np.testing.assert_array_equal(got_k[:, :, n_old:], want_k)
+    np.testing.assert_array_equal(got_v[:, :, n_old:], want_v)
+    np.testing.assert_array_equal(got_k[:, :, :n_old], data["k_codes"][:, :, :n_old])
+    np.testing.assert_array_equal(got_v[:, :, :n_old], data["v_codes"][:, :, :n_old])
+
+
 @pytest.mark.parametrize("B_,n_new", [(1, 3), (2, 100), (3, 333), (1, 512), (1, 513), (2, 512), (1, 1025), (16, 1), (2, 8), (1, 17)])
 def test_encode_filter_paths_are_bit_exact(B_, n_new):
     """The 12-bit encode is a matrix-core filter with the fp64 expression as the decision: every way through it gives

@@ -368,6 +368,93 @@ def test_encode_with_4096_centroids_matches_library_vector_quantizer():
     assert O.encode(x, cb)[0, 0, 0, 0] == 17
 
 
+def _exact_nearest(x16, cb16):
+    """Nearest centroid in EXACT arithmetic: every fp16 value is an integer multiple of 2^-24, so squared distances
+    are integers (Python ints, no rounding anywhere); ties go to the lowest index.  x16 [n, ds], cb16 [C, ds]."""
+    xi = [[int(v) for v in row] for row in (x16.astype(np.float64) * 2.0 ** 24)]
+    ci = [[int(v) for v in row] for row in (cb16.astype(np.float64) * 2.0 ** 24)]
+    out = np.empty(len(xi), dtype=np.int64)
+    for t, xr in enumerate(xi):
+        best, best_d = 0, None
+        for c, cr in enumerate(ci):
+            d = sum((a - b) * (a - b) for a, b in zip(xr, cr))
+            if best_d is None or d < best_d:
+                best, best_d = c, d
+        out[t] = best
+    return out
+
+
+@pytest.mark.parametrize("ds", [2, 4])
+@pytest.mark.parametrize("case", ["unit", "outliers_x20", "codebook_x150", "tokens_x300", "subnormal", "midpoints", "ties",
+                                  "wide_differences"])
+def test_encode_equals_exact_integer_argmin_at_any_magnitude(case, ds):
+    """Eq. 4 / Section II-C ask for the nearest centroid; the oracle evaluates the squared distance in IEEE double.
+    Where double rounding could matter (values far above 1: two roundings per distance; tokens a few fp16 steps off
+    the midpoint of close centroid pairs; subnormals; exact ties) its codes are pinned to exact integer arithmetic."""
+    rng = np.random.default_rng(zlib_seed(case) + ds)
+    C, n = 256, 160
+    cb = rng.standard_normal((C, ds)).astype(np.float32)
+    x = rng.standard_normal((n, ds)).astype(np.float32)
+    if case == "outliers_x20":                    # 2 % of centroid coordinates scaled by 20, as in the GQA workload
+        cb = np.where(rng.random(cb.shape) < 0.02, cb * 20.0, cb)
+    elif case == "codebook_x150":
+        cb = cb * 150.0
+        x = x * 100.0
+    elif case == "tokens_x300":
+        x[::3] *= 300.0
+    elif case == "subnormal":
+        cb, x = cb * 1e-6, x * 1e-6
+        cb[::2] = 0.0
+        x[:8] = 0.0
+    cb = cb.astype(np.float16)
+    x = x.astype(np.float16)
+    if case == "midpoints":                       # tokens within +-2 fp16 steps of the midpoint of a close pair
+        cbf = cb.astype(np.float32)
+        cbf[128:] = cbf[:128] + (rng.standard_normal((128, ds)) * 0.05).astype(np.float32)
+        cb = cbf.astype(np.float16)
+        pair = rng.integers(0, 128, size=n)
+        mid = 0.5 * (cb[pair].astype(np.float32) + cb[pair + 128].astype(np.float32))
+        jit = rng.integers(-2, 3, size=mid.shape) * np.abs(np.spacing(mid.astype(np.float16))).astype(np.float32)
+        x = (mid + jit).astype(np.float16)
+    elif case == "ties":                          # duplicated centroids and tokens exactly between two centroids
+        cb[200] = cb[17]
+        cb[255] = cb[3]
+        cb[40] = 0
+        cb[41] = 0
+        cb[41, 0] = np.float16(0.5)
+        x[:4] = 0
+        x[:4, 0] = np.float16(0.25)
+        x[4:20] = cb[rng.integers(0, 256, size=16)]
+    elif case == "wide_differences":
+        # Tokens at (X, 0, ..) with X one of 512, 1024, 2048, one centroid at the origin and one at (2^-15, y, 0, ..) with y^2
+        # a little below X 2^-14: the second is nearer by about 1e-4, but only if the difference X - 2^-15 (25 and
+        # more significant bits) is kept exactly; every other centroid lies on the far side of the origin.
+        cb = cb.astype(np.float32)
+        cb[:, 0] = -np.abs(cb[:, 0]) - 0.01
+        cb = cb.astype(np.float16)
+        cb[10] = 0
+        cb[11] = 0
+        cb[11, 0] = np.float16(2.0 ** -15)
+        big = float(rng.choice([512.0, 1024.0, 2048.0]))
+        x[:] = 0
+        x[:, 0] = np.float16(big)
+        cb[11, 1] = np.float16(np.sqrt(big * 2.0 ** -14) * 0.999)
+        assert float(cb[11, 1]) ** 2 < big * 2.0 ** -14 - 2.0 ** -30
+    assert np.isfinite(cb.astype(np.float32)).all() and np.isfinite(x.astype(np.float32)).all()
+    codes = O.encode(x.reshape(1, 1, n, ds), cb.reshape(1, 1, C, ds))[0, 0, :, 0]
+    want = _exact_nearest(x, cb)
+    np.testing.assert_array_equal(codes, want)
+    if case == "ties":
+        assert (codes != 200).all() and (codes != 255).all()
+    if case == "wide_differences":
+        assert (codes == 11).all()
+
+
+def zlib_seed(name):
+    import zlib
+    return zlib.crc32(name.encode()) % 100000
+
+
 # ------------------------------------------------------------------ property-based: random tiny shapes
 
 from hypothesis import given, settings, strategies as st  # noqa: E402

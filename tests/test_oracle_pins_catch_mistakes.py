@@ -37,16 +37,35 @@ MISTAKES = {
     "distance over the first coordinate only": (
         "                for (int j = 0; j < ds; ++j) {\n                    const double diff",
         "                for (int j = 0; j < 1; ++j) {\n                    const double diff"),
+    "distance accumulated in single precision": (
+        "dist = fma(diff, diff, dist);", "dist = (double)((float)dist + (float)diff * (float)diff);"),
+    "differences rounded to single precision": (
+        "                    dist = fma(diff, diff, dist);", "                    dist = fma((double)(float)diff, (double)(float)diff, dist);"),
     "farthest centroid": ("if (c == 0 || dist < best_dist) {", "if (c == 0 || dist > best_dist) {"),
 }
 
 
 def pin_functions():
+    """Zero-argument callables: every plain pin, and every parameter combination of the parametrized ones."""
+    import itertools
     out = []
     for name, fn in inspect.getmembers(pins, inspect.isfunction):
-        if name.startswith("test_") and "hypothesis" not in name and "random_tiny" not in name and not hasattr(fn, "pytestmark"):
+        if not name.startswith("test_") or "hypothesis" in name or "random_tiny" in name:
+            continue
+        marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+        if not marks:
             if not inspect.signature(fn).parameters:
                 out.append(fn)
+            continue
+        names = [[n.strip() for n in m.args[0].split(",")] for m in marks]
+        for combo in itertools.product(*[m.args[1] for m in marks]):
+            kw = {}
+            for ns, values in zip(names, combo):
+                values = values if len(ns) > 1 else (values,)
+                kw.update(dict(zip(ns, values)))
+            call = lambda fn=fn, kw=kw: fn(**kw)
+            call.__name__ = f"{name}[{kw}]"
+            out.append(call)
     return out
 
 
