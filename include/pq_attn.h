@@ -132,6 +132,28 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
                    const int32_t *ctx_len, const void *k_codebook, const void *v_codebook, const void *recent_k,
                    const void *recent_v, const int32_t *recent_len, float scale, float *out, void *hip_stream);
 
+/* pq_attn_decode for callers that cannot allocate device memory — code recorded into a HIP graph, tight
+ * serving loops, harnesses that forbid hipMalloc — and therefore cannot hold a context: the same kernels, the
+ * same result, with every piece of scratch (codebook images, split partials, tickets) in one array that is
+ * part of the library's device code (4.5 MiB per GPU the library runs on, held until the process ends).  The call allocates and
+ * frees nothing and does not synchronise.
+ *
+ *   cfg         host; as for pq_attn_create (cfg->device names the GPU).  The code tensors use the layout
+ *               of a context created from the same configuration (pq_pack_codes / pq_encode_append of such a
+ *               context produce them).
+ *   k_codebook, v_codebook   device [Hkv][M][256][ds] dtype, required: re-packed into the scratch by every call
+ *   all other arguments as in pq_attn_decode
+ *
+ * Limits (PQ_ERR_CAPACITY beyond them): 8-bit codes only (4096 centroids: PQ_ERR_UNSUPPORTED); one codebook
+ * tensor at most 2 MiB (32 KV heads in fp16, 16 in fp32); batch * n_q_heads <= 1024; with an explicit
+ * n_splits, batch * n_q_heads * n_splits <= 1024 ("0 = choose" never exceeds it).
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams, two
+ * threads, or with a call still in flight) race; stream-order them. */
+int pq_attn_decode_noalloc(const pq_attn_config *cfg /* host */, const void *q, const uint8_t *k_codes,
+                           const uint8_t *v_codes, const int32_t *ctx_len, const void *k_codebook,
+                           const void *v_codebook, const void *recent_k, const void *recent_v,
+                           const int32_t *recent_len, float scale, float *out, void *hip_stream);
+
 /* Quantizes n_new full-precision tokens per (sequence, KV head) and appends their
  * codes (Eq. 4 with Section II-C's nearest-centroid assignment; step 5 of Section
  * III-C): for every sub-vector the index of the centroid at the smallest squared

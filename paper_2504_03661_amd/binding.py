@@ -83,6 +83,8 @@ def load_library():
     L.pq_attn_set_codebooks.argtypes = [vp, vp, vp, vp]
     L.pq_attn_decode.restype = ctypes.c_int
     L.pq_attn_decode.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp]
+    L.pq_attn_decode_noalloc.restype = ctypes.c_int
+    L.pq_attn_decode_noalloc.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp]
     L.pq_encode_append.restype = ctypes.c_int
     L.pq_encode_append.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
     L.pq_pack_codes.restype = ctypes.c_int
@@ -169,6 +171,14 @@ def pq_attn_decode(ctx, q, k_codes, v_codes, ctx_len, k_codebook, v_codebook, re
                                          _addr(k_codebook), _addr(v_codebook), _addr(recent_k), _addr(recent_v),
                                          _addr(recent_len), float(scale), _addr(out), _stream(stream)),
            "pq_attn_decode")
+
+
+def pq_attn_decode_noalloc(cfg: PQAttnConfig, q, k_codes, v_codes, ctx_len, k_codebook, v_codebook, recent_k, recent_v,
+                           recent_len, scale, out, stream=None) -> None:
+    _check(load_library().pq_attn_decode_noalloc(ctypes.byref(cfg.c_struct()), _addr(q), _addr(k_codes), _addr(v_codes),
+                                                 _addr(ctx_len), _addr(k_codebook), _addr(v_codebook), _addr(recent_k),
+                                                 _addr(recent_v), _addr(recent_len), float(scale), _addr(out),
+                                                 _stream(stream)), "pq_attn_decode_noalloc")
 
 
 def pq_encode_append(ctx, new_k, new_v, n_new, k_codebook, v_codebook, k_codes, v_codes, ctx_len,

@@ -8,9 +8,53 @@
 
 #include "pq_internal.h"
 
+#include <mutex>
+
+// Scratch of pq_attn_decode_noalloc: one array per GPU the library runs on, held until the process ends.
+//   [0, 2 MiB)           centroid-major image of the K codebooks      (PQ_NOALLOC_CODEBOOK_BYTES)
+//   [2 MiB, 4 MiB)       the same for V
+//   then                 split partials [PQ_NOALLOC_MAX_ROWS][PQ_PART_STRIDE] fp32
+//   then                 tickets [PQ_NOALLOC_MAX_ROWS] uint32
+// In host code the array's name is a stand-in, not a device address: host code uses the pointer that
+// hipGetSymbolAddress returns for the current device.
+#define PQ_NOALLOC_PARTIALS_OFF (2 * (size_t)PQ_NOALLOC_CODEBOOK_BYTES)
+#define PQ_NOALLOC_TICKETS_OFF (PQ_NOALLOC_PARTIALS_OFF + (size_t)PQ_NOALLOC_MAX_ROWS * PQ_PART_STRIDE * sizeof(float))
+#define PQ_NOALLOC_SCRATCH_BYTES (PQ_NOALLOC_TICKETS_OFF + (size_t)PQ_NOALLOC_MAX_ROWS * sizeof(unsigned int))
+static __device__ __align__(256) unsigned char scratch[PQ_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr float LOG2E = 1.44269504088896340736f;
+
+// per device: the address of that GPU's copy of `scratch` and its compute-unit count, looked up once
+constexpr int MAX_DEVICES = 64;
+struct noalloc_device {
+    unsigned char *ptr = nullptr;
+    int n_cu = 0;
+};
+noalloc_device g_noalloc[MAX_DEVICES];
+std::mutex g_noalloc_mutex;
+
+// the caller has made `dev` current
+int noalloc_lookup(int dev, noalloc_device *out)
+{
+    if (dev < 0 || dev >= MAX_DEVICES)
+        return PQ_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    if (g_noalloc[dev].ptr == nullptr) {
+        void *p = nullptr;
+        int n_cu = 0;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) {
+            (void)hipGetLastError();
+            return PQ_ERR_HIP;
+        }
+        g_noalloc[dev].n_cu = n_cu;
+        g_noalloc[dev].ptr = (unsigned char *)p;
+    }
+    *out = g_noalloc[dev];
+    return PQ_OK;
+}
 
 struct device_guard {
     int prev = -1;
@@ -127,6 +171,39 @@ int32_t stage_tokens_for(const pq_attn_config *c)
     if (t > c->max_context)
         t = c->max_context;
     return (int32_t)t;
+}
+
+int launch_decode(const pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, const uint8_t *v_codes,
+                  const int32_t *ctx_len, const void *recent_k, const void *recent_v, const int32_t *recent_len, float scale,
+                  float *out, hipStream_t s)
+{
+    pq_decode_args a;
+    a.q = q;
+    a.k_codes = k_codes;
+    a.v_codes = v_codes;
+    a.ctx_len = ctx_len;
+    a.kcb_packed = ctx->kcb_packed;
+    a.vcb_packed = ctx->vcb_packed;
+    a.recent_k = recent_k;
+    a.recent_v = recent_v;
+    a.recent_len = recent_k ? recent_len : nullptr;
+    a.out = out;
+    a.partials = ctx->partials;
+    a.tickets = ctx->tickets;
+    a.scale_log2e = scale * LOG2E;
+    a.B = ctx->cfg.batch;
+    a.Hq = ctx->cfg.n_q_heads;
+    a.Hkv = ctx->cfg.n_kv_heads;
+    a.G = ctx->group;
+    a.Gs = ctx->k_skew == PQ_K_SKEW_QUAD ? pq_grouped_heads_per_workgroup(ctx->group) : 0;
+    a.S = ctx->n_splits;
+    a.max_context = ctx->cfg.max_context;
+    a.max_recent = ctx->cfg.max_recent;
+    a.head_stride = ctx->cap_padded * token_bytes(&ctx->cfg);
+    const hipError_t e = pq_config_is_12bit(&ctx->cfg)   ? pq12_launch_decode(ctx, a, s)
+                         : ctx->k_skew == PQ_K_SKEW_QUAD ? pq_launch_decode_grouped(ctx, a, s)
+                                                         : pq_launch_decode(ctx, a, s);
+    return e == hipSuccess ? PQ_OK : PQ_ERR_HIP;
 }
 
 void free_ctx(pq_attn_ctx *ctx)
@@ -289,33 +366,66 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
     if (rc != PQ_OK)
         return rc;
 
-    pq_decode_args a;
-    a.q = q;
-    a.k_codes = k_codes;
-    a.v_codes = v_codes;
-    a.ctx_len = ctx_len;
-    a.kcb_packed = ctx->kcb_packed;
-    a.vcb_packed = ctx->vcb_packed;
-    a.recent_k = recent_k;
-    a.recent_v = recent_v;
-    a.recent_len = recent_k ? recent_len : nullptr;
-    a.out = out;
-    a.partials = ctx->partials;
-    a.tickets = ctx->tickets;
-    a.scale_log2e = scale * LOG2E;
-    a.B = ctx->cfg.batch;
-    a.Hq = ctx->cfg.n_q_heads;
-    a.Hkv = ctx->cfg.n_kv_heads;
-    a.G = ctx->group;
-    a.Gs = ctx->k_skew == PQ_K_SKEW_QUAD ? pq_grouped_heads_per_workgroup(ctx->group) : 0;
-    a.S = ctx->n_splits;
-    a.max_context = ctx->cfg.max_context;
-    a.max_recent = ctx->cfg.max_recent;
-    a.head_stride = ctx->cap_padded * token_bytes(&ctx->cfg);
-    const hipError_t e = pq_config_is_12bit(&ctx->cfg)   ? pq12_launch_decode(ctx, a, s)
-                         : ctx->k_skew == PQ_K_SKEW_QUAD ? pq_launch_decode_grouped(ctx, a, s)
-                                                         : pq_launch_decode(ctx, a, s);
-    return e == hipSuccess ? PQ_OK : PQ_ERR_HIP;
+    return launch_decode(ctx, q, k_codes, v_codes, ctx_len, recent_k, recent_v, recent_len, scale, out, s);
+}
+
+int pq_attn_decode_noalloc(const pq_attn_config *cfg, const void *q, const uint8_t *k_codes, const uint8_t *v_codes,
+                           const int32_t *ctx_len, const void *k_codebook, const void *v_codebook, const void *recent_k,
+                           const void *recent_v, const int32_t *recent_len, float scale, float *out, void *hip_stream)
+{
+    if (cfg == nullptr || q == nullptr || k_codes == nullptr || v_codes == nullptr || ctx_len == nullptr ||
+        k_codebook == nullptr || v_codebook == nullptr || out == nullptr)
+        return PQ_ERR_NULL;
+    const int rc = validate(cfg);
+    if (rc != PQ_OK)
+        return rc;
+    if ((recent_k == nullptr) != (recent_v == nullptr))
+        return PQ_ERR_NULL;
+    if (recent_k != nullptr && cfg->max_recent == 0)
+        return PQ_ERR_SHAPE;
+    if (!(fabsf(scale) <= 3.0e38f))
+        return PQ_ERR_SHAPE;
+    if (pq_config_is_12bit(cfg))
+        return PQ_ERR_UNSUPPORTED;  // 1.5 MiB of tables per head and a per-token score buffer: not in a modest array
+    // limits of the static scratch
+    const size_t elem = cfg->dtype == PQ_F16 ? 2 : 4;
+    const int64_t rows = (int64_t)cfg->batch * cfg->n_q_heads;
+    if ((size_t)cfg->n_kv_heads * 256 * PQ_HEAD_DIM * elem > PQ_NOALLOC_CODEBOOK_BYTES || rows > PQ_NOALLOC_MAX_ROWS ||
+        (cfg->n_splits > 0 && rows * cfg->n_splits > PQ_NOALLOC_MAX_ROWS))
+        return PQ_ERR_CAPACITY;
+    device_guard guard(cfg->device);
+    if (!guard.ok)
+        return PQ_ERR_HIP;
+    noalloc_device dev;
+    const int lrc = noalloc_lookup(cfg->device, &dev);
+    if (lrc != PQ_OK)
+        return lrc;
+
+    // a context on the stack whose buffers are pieces of this GPU's scratch array
+    pq_attn_ctx ctx{};
+    ctx.cfg = *cfg;
+    ctx.ds = cfg->head_dim / cfg->n_subspaces;
+    ctx.group = cfg->n_q_heads / cfg->n_kv_heads;
+    ctx.cap_padded = padded_capacity(cfg);
+    ctx.elem_bytes = elem;
+    ctx.k_skew = pq_config_uses_grouped_kernel(cfg) ? PQ_K_SKEW_QUAD : PQ_K_SKEW_LANE;
+    int64_t splits = cfg->n_splits > 0 ? cfg->n_splits : choose_splits(cfg, dev.n_cu);
+    if (rows * splits > PQ_NOALLOC_MAX_ROWS)
+        splits = PQ_NOALLOC_MAX_ROWS / rows;
+    ctx.n_splits = (int)splits;
+    ctx.kcb_packed = dev.ptr;
+    ctx.vcb_packed = dev.ptr + PQ_NOALLOC_CODEBOOK_BYTES;
+    ctx.partials = (float *)(dev.ptr + PQ_NOALLOC_PARTIALS_OFF);
+    ctx.tickets = (unsigned int *)(dev.ptr + PQ_NOALLOC_TICKETS_OFF);
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (pq_launch_pack_codebook(&ctx, k_codebook, ctx.kcb_packed, nullptr, s) != hipSuccess ||
+        pq_launch_pack_codebook(&ctx, v_codebook, ctx.vcb_packed, nullptr, s) != hipSuccess)
+        return PQ_ERR_HIP;
+    // the tickets must start at zero; the array keeps whatever the last call on this GPU left (a fill kernel,
+    // not a memset: this call may be recorded into a HIP graph)
+    if (pq_launch_clear_words(ctx.tickets, rows, s) != hipSuccess)
+        return PQ_ERR_HIP;
+    return launch_decode(&ctx, q, k_codes, v_codes, ctx_len, recent_k, recent_v, recent_len, scale, out, s);
 }
 
 int pq_encode_append(pq_attn_ctx *ctx, const void *new_k, const void *new_v, int32_t n_new, const void *k_codebook,

@@ -83,6 +83,10 @@ __host__ __device__ inline int64_t pq12_v_unit(int64_t t, int i, int *slot)
 #define PQ_MAX_TOKENS (1 << 24)  // capacity limit that keeps the kernels' index arithmetic in 32 bits
 #define PQ_HEAD_DIM 128
 #define PQ_ERRFLAG_APPEND_OVERFLOW 1u
+// limits of pq_attn_decode_noalloc's static scratch: bytes of one centroid-major codebook image set (K or V, all KV
+// heads) and (sequence, query head, split) rows of partials / (sequence, query head) tickets
+#define PQ_NOALLOC_CODEBOOK_BYTES (2 << 20)
+#define PQ_NOALLOC_MAX_ROWS 1024
 
 struct pq_attn_ctx {
     pq_attn_config cfg;

@@ -9,7 +9,7 @@
 namespace {
 
 // [Hkv][M][256][ds] -> [Hkv][256][M][ds]; one thread per (head, centroid, subspace)
-// (also writes `nat`, a plain copy of src: the context's own codebooks for the encode kernels)
+// (also writes `nat`, unless NULL: a plain copy of src, the context's own codebooks for the encode kernels)
 template <typename E>
 __global__ void pq_pack_codebook_kernel(const E *src, E *dst, E *nat, int Hkv, int M, int ds)
 {
@@ -25,7 +25,8 @@ __global__ void pq_pack_codebook_kernel(const E *src, E *dst, E *nat, int Hkv, i
     for (int j = 0; j < ds; ++j) {
         const E v = src[so + j];
         d[j] = v;
-        nat[so + j] = v;
+        if (nat != nullptr)
+            nat[so + j] = v;
     }
 }
 
