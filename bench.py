@@ -2,6 +2,7 @@
 """Benchmark of PQ decode attention on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--copies C] [--no-cpu-baseline] [--warm]
+                    [--no-others]
 
 A step is one pass of the hot path over one batch: pq_attn_decode (table build,
 score pass, softmax, value pass, recent rows, split merge — one fused kernel) on
@@ -18,6 +19,9 @@ kernel against HBM: algorithmic bytes per launch / average kernel duration, the
 span between two HIP events on the launching stream around the K back-to-back
 launches divided by K (so it includes the gap between kernels).
 `cpu_baseline` is the double-precision oracle on the same workload on the host.
+The default run (workload 1) also times the other named workloads — batched, grouped-query 128K, 2-bit +
+encode — with fewer launches each and lists them under `other_workloads` (kernel time, algorithmic bytes,
+fraction of the HBM peak); `value` stays the metric's workload.
 """
 import argparse
 import json
@@ -47,6 +51,67 @@ def algorithmic_bytes(w, data):
             "total": codes + recent + codebooks + qo}
 
 
+def time_other_workload(index, steps, warmup):
+    """Decode kernel time (HIP-event span / launches on the launching stream, rotating code copies) of another
+    named workload, and for the workload with an append the whole step as well."""
+    import numpy as np
+    import torch
+
+    from paper_2504_03661_amd.harness import PQSession
+    from synth import workloads as W
+
+    w = W.config(index)
+    data = W.generate(w)
+    scale = W.attention_scale(w)
+    bytes_alg = algorithmic_bytes(w, data)
+    one_copy = 2 * w.batch * w.n_kv_heads * w.context * w.n_subspaces
+    copies = max(2, min(8, -(-(1 << 30) // one_copy)))
+    sess = PQSession(data, w.n_q_heads, w.dtype, code_copies=copies)
+    dec = [sess.prepared_decode(scale, copy=c) for c in range(copies)]
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    if w.n_new > 0:
+        sess.ctx_len.fill_(w.context)          # decode alone: the cache as it is after the append
+
+    def span(fn, n):
+        torch.cuda.synchronize()
+        ev0.record()
+        for i in range(n):
+            fn(i)
+        ev1.record()
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) / n
+
+    span(lambda i: dec[i % copies](), warmup)
+    kernel_ms = span(lambda i: dec[i % copies](), steps)
+    out = {"workload": w.name, "n_splits": sess.n_splits, "launches": steps, "kernel_ms": round(kernel_ms, 5),
+           "algorithmic_bytes": bytes_alg["total"], "code_bytes": bytes_alg["codes"],
+           "achieved_gbps": round(bytes_alg["total"] / (kernel_ms * 1e-3) / 1e9, 1),
+           "frac": round(bytes_alg["total"] / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+           "code_read_frac_of_peak": round(bytes_alg["codes"] / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    tokens = int(np.asarray(data["ctx_len"], dtype=np.int64).sum() + w.n_new * w.batch +
+                 np.asarray(data["recent_len"], dtype=np.int64).sum())
+    out["context_tokens_per_s"] = round(tokens / (kernel_ms * 1e-3), 1)
+    if w.n_new > 0:
+        new_k = torch.from_numpy(data["new_k"]).cuda()
+        new_v = torch.from_numpy(data["new_v"]).cuda()
+        base_len = torch.from_numpy(data["ctx_len"]).cuda()
+        app = [sess.prepared_append(new_k, new_v, copy=c) for c in range(copies)]
+
+        def step(i):
+            sess.ctx_len.copy_(base_len)
+            app[i % copies]()
+            dec[i % copies]()
+
+        span(step, max(warmup // 4, 10))
+        out["step_ms_append_then_decode"] = round(span(step, steps), 5)
+        out["n_new"] = w.n_new
+    sess.close()
+    del sess, dec, data
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +124,7 @@ def main():
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="also time the same-buffer (cache-warm) case")
+    ap.add_argument("--no-others", action="store_true", help="skip the other named workloads (only with --config 1 they run)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -190,12 +256,18 @@ def main():
     value = tokens_per_step / (ms_per_step * 1e-3)
 
     achieved = bytes_alg["total"] / (kernel_ms * 1e-3) / 1e9
+    # HBM bytes per launch from rocprofv3 counters cannot be read inside this process: the figure is the one a
+    # separate counter run of this same command left under profiles/ (static; the file names the commands)
     traffic = None
+    traffic_source = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.txt")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-    roofline = {"bound": "hbm", "kernel": "pq_decode_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+        traffic_source = f"profiles/traffic_{w.name}.txt (static: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, not measured in this run)"
+    kernel_name = {True: "pq_decode_grouped_kernel", False: "pq_decode_kernel"}[w.n_q_heads != w.n_kv_heads and w.dtype == "f16"]
+    roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "traffic_source": traffic_source,
                 "kernel_ms": round(kernel_ms, 5), "event_span_ms_per_step": round(span_ms, 5),
                 "measured_stream_read_gbps": round(stream_gbps, 1),
                 "frac_of_measured_stream_read": round(achieved / stream_gbps, 4),
@@ -207,6 +279,10 @@ def main():
     out_gpu = sess.out.cpu().numpy().astype(np.float64)
     n_splits = sess.n_splits
     sess.close()
+
+    others = None
+    if args.config == 1 and not args.no_others:
+        others = [time_other_workload(k, steps=n, warmup=wu) for k, n, wu in ((3, 1500, 800), (2, 400, 200), (4, 200, 100))]
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -260,6 +336,7 @@ def main():
                    "io_dtype": w.dtype, "recent_cap": w.recent_cap, "n_new": w.n_new, "n_splits": n_splits,
                    "code_copies_rotated": copies, "seed": w.seed},
         "roofline": roofline,
+        "other_workloads": others,
         "cpu_baseline": cpu,
         "paper_context": "MILLION reports 2.09x end-to-end and 2.01x attention speed-up at 32K on one A40 "
                          "(Llama-2-7B, TPOT 63.41 ms vs 132.97 ms); no kernel-level figure is published",

@@ -66,11 +66,11 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     uint32_t logical = blockIdx.x;
     if ((grid & 7u) == 0)
         logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
-    const int S = a.S;
+    const int S_grid = a.S;  // splits the grid was launched with (partials are laid out with this stride)
     // neighbours: the splits of a (sequence, query head), the query heads of its KV group, then the same
     // KV head of the other sequences (they load the same codebooks: once per XCD instead of once per sequence)
-    const uint32_t unit = logical / (uint32_t)S;
-    const int split = (int)(logical - unit * (uint32_t)S);
+    const uint32_t unit = logical / (uint32_t)S_grid;
+    const int split = (int)(logical - unit * (uint32_t)S_grid);
     const uint32_t bkv = unit / (uint32_t)a.G;          // hkv * B + b
     const int gq = (int)(unit - bkv * (uint32_t)a.G);
     const int hkv = (int)(bkv / (uint32_t)a.B);
@@ -129,6 +129,12 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     // 32-bit unsigned arithmetic: the capacities are limited to 2^24 tokens and S to 64, and a
     // 64-bit division costs more instructions than the whole table build
     const uint32_t nblk = (uint32_t)(N + 63) >> 6;
+    // The grid is sized for the capacity; the LIVE splits follow the length: a split scans at least 4 blocks,
+    // so a short sequence in a long cache uses the first few splits only and the others leave here, before
+    // they build tables (every workgroup of the row computes the same count; the merge expects that many).
+    const int S = (int)(nblk / 4u < 1u ? 1u : (nblk / 4u < (uint32_t)S_grid ? nblk / 4u : (uint32_t)S_grid));
+    if (split >= S)
+        return;
     const int blk0 = (int)(nblk * (uint32_t)split / (uint32_t)S);
     const int blk1 = (int)(nblk * (uint32_t)(split + 1) / (uint32_t)S);
     const int r0 = (int)((uint32_t)R * (uint32_t)split / (uint32_t)S);
@@ -418,7 +424,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     // output dims 2l, 2l+1), publishes the split partial and takes a ticket.
     if (wave != 0)
         return;
-    float *gpart = a.partials + ((int64_t)bh * S + split) * PQ_PART_STRIDE;
+    float *gpart = a.partials + ((int64_t)bh * S_grid + split) * PQ_PART_STRIDE;
     float *orow = a.out + (int64_t)bh * PQ_HEAD_DIM;
     const lds_f32 *parts = (const lds_f32 *)(lbase + PART_OFF);
     float mx = NEG_BIG;
@@ -456,7 +462,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         return;
     asm volatile("" ::: "memory");  // the loads below stay behind the ticket in the instruction stream
     // the other splits' partials: device-scope loads, issued after the ticket has returned
-    const float *ps = a.partials + (int64_t)bh * S * PQ_PART_STRIDE;
+    const float *ps = a.partials + (int64_t)bh * S_grid * PQ_PART_STRIDE;
     // Lane s holds (maximum, weight sum) of split s.  The first eight splits' output loads are issued
     // together with that load, so the merge costs one memory round trip for up to eight splits.
     float2 o[8];

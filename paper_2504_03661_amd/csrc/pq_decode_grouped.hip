@@ -99,10 +99,10 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     uint32_t logical = blockIdx.x;
     if ((grid & 7u) == 0)
         logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
-    const int S = a.S;
+    const int S_grid = a.S;  // splits the grid was launched with (partials are laid out with this stride)
     // workgroups of one KV head are neighbours: (sequence, KV head, sub-group of G query heads, split)
-    const int unit = (int)(logical / (uint32_t)S);
-    const int split = (int)(logical - (uint32_t)unit * (uint32_t)S);
+    const int unit = (int)(logical / (uint32_t)S_grid);
+    const int split = (int)(logical - (uint32_t)unit * (uint32_t)S_grid);
     const int n_sub = a.G / G;                     // sub-groups per KV head
     // ... then the same KV head of the other sequences (same codebook images: once per XCD from memory)
     const int hb = (int)((uint32_t)unit / (uint32_t)n_sub);  // hkv * B + b
@@ -144,6 +144,10 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
     R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
     const uint32_t nblk = (uint32_t)(N + 63) >> 6;
+    // live splits follow the length (at least 4 blocks each); the others leave before the images are staged
+    const int S = (int)(nblk / 4u < 1u ? 1u : (nblk / 4u < (uint32_t)S_grid ? nblk / 4u : (uint32_t)S_grid));
+    if (split >= S)
+        return;
     const int blk0 = (int)(nblk * (uint32_t)split / (uint32_t)S);
     const int blk1 = (int)(nblk * (uint32_t)(split + 1) / (uint32_t)S);
     const int r0 = (int)((uint32_t)R * (uint32_t)split / (uint32_t)S);
@@ -152,8 +156,8 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const uint8_t *v_head = a.v_codes + (int64_t)bkv * a.head_stride;
 
     // One K and one V buffer per wavefront, each refilled as soon as its pass is over: the V codes
-    // of a block are requested when its score pass starts, the K codes of the next block when
-    // that score pass ends.  With 4 wavefronts per SIMD that is enough to keep the loads ahead.
+    // of a block are requested when its score pass starts (the first block's: in the prologue), the K codes of
+    // the next block when that score pass ends.  With 4 wavefronts per SIMD that is enough to keep the loads ahead.
     uint4 kbuf[KVEC], vbuf[4];
     // `live` false: a dead load by a wavefront that has run out of blocks (loads stay unconditional
     // so that the wait counts stay exact); all lanes then read the same 16 bytes, not 4 KiB.
@@ -174,6 +178,11 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     *(lds_u32 *)(lbase + GCTR_OFF) = (uint32_t)(blk0 + NW);
     const uint32_t ctr_addr = (uint32_t)(uintptr_t)(lbase + GCTR_OFF);
     load_k(kbuf, blk < blk1 ? blk : 0, blk < blk1);
+    // The first block's V codes are requested here too: a wavefront scans only a handful of blocks, and a round
+    // trip to memory in front of its first value pass is not amortised (measured on the 128K-token workload:
+    // 35.7 -> 33.3 us on a box with slow memory round trips, no change on a faster one).
+    load_v(blk < blk1 ? blk : 0);
+    bool first_block = true;
 
 #pragma unroll
     for (int v = 0; v < VPT / 2; ++v) {
@@ -307,7 +316,9 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
 
     while (blk < blk1) {
         const int nb = lds_grab(ctr_addr);
-        load_v(blk);
+        if (!first_block)  // wave-uniform
+            load_v(blk);
+        first_block = false;
         process(blk, nb < blk1 ? nb : blk, nb < blk1);
         blk = nb;
     }
@@ -394,7 +405,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
             const float inv = l > 0.f ? 1.f / l : 0.f;
             *(float2 *)(a.out + (int64_t)(bh0 + g) * PQ_HEAD_DIM + 2 * lane) = make_float2(o0 * inv, o1 * inv);
         } else {
-            float *gpart = a.partials + ((int64_t)(bh0 + g) * S + split) * PQ_PART_STRIDE;
+            float *gpart = a.partials + ((int64_t)(bh0 + g) * S_grid + split) * PQ_PART_STRIDE;
             // device-scope stores, complete (performed where every XCD sees them) before the barrier
             publish(gpart + 4 + 2 * lane, o0, o1);
             if (lane == 0)
@@ -422,7 +433,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         // splits' outputs together with the (maximum, weight sum) pairs, so that the merge costs one memory round
         // trip instead of three.  Loads of splits beyond S repeat the last split (unconditional loads from
         // wave-uniform bases); their factor is zero.
-        const float *ps = a.partials + (int64_t)(bh0 + g) * S * PQ_PART_STRIDE;
+        const float *ps = a.partials + (int64_t)(bh0 + g) * S_grid * PQ_PART_STRIDE;
         float2 o[32];
 #pragma unroll
         for (int u = 0; u < 32; ++u)

@@ -173,6 +173,22 @@ def test_decode_outlier_codebooks_gqa():
     check(gpu_decode(w, data), oracle_out(w, data), "outliers")
 
 
+@pytest.mark.parametrize("Hq,Hkv,M", [(4, 4, 64), (8, 2, 64), (4, 4, 32), (8, 2, 32)])
+def test_short_sequences_in_a_long_cache_use_few_of_the_launched_splits(Hq, Hkv, M):
+    """The grid is sized for the capacity (here 16 splits per head); the kernel derives the live splits from each
+    sequence's length (at least 4 blocks of 64 tokens each): 0, 1 and 2 live splits, a split boundary, all 16."""
+    lens = (0, 200, 513, 2048, 70000)
+    w = W.Workload("short_in_long", len(lens), Hq, Hkv, 128, M, max(lens), "f16", recent_cap=40, recent_uniform=True,
+                   seed=321 + Hq + M, ctx_lens=lens)
+    data = W.generate(w)
+    ref = oracle_out(w, data)
+    for splits in (16, 5):
+        got = gpu_decode(w, data, n_splits=splits)
+        check(got, ref, f"{splits} launched splits")
+        for b in range(len(lens)):
+            check(got[b], ref[b], f"{splits} launched splits, length {lens[b]}")
+
+
 @pytest.mark.parametrize("Hq,Hkv,M", [(2, 2, 64), (4, 1, 64), (2, 2, 32)])
 def test_lengths_outside_their_range_are_clamped(Hq, Hkv, M):
     """Device lengths below zero count as 0, lengths above the capacities as the capacities (header contract)."""
