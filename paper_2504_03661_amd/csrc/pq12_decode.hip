@@ -372,7 +372,7 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
     publish(gpart + 4 + 2 * lane, o0, o1);
     if (lane == 0)
         publish(gpart, mx, l);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    publish_wait();
     unsigned int ticket = 0;
     if (lane == 0)
         ticket = __hip_atomic_fetch_add(a.tickets + bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -395,7 +395,7 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_decode_kernel(const pq_decode_
     const float inv = l > 0.f ? 1.f / l : 0.f;
     *(float2 *)(orow + 2 * lane) = make_float2(o0 * inv, o1 * inv);
     if (lane == 0)
-        a.tickets[bh] = 0u;
+        ticket_reset(a.tickets + bh);
 }
 
 
@@ -792,7 +792,7 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_values_kernel(const pq_decode_
         publish(gpart + 4 + 16 * g + 2 * lane, o0, o1);
     if (g == 0 && lane == 0)
         publish(gpart, mx, l);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    publish_wait();
     unsigned int ticket = 0;
     if (lane == 0)
         ticket = __hip_atomic_fetch_add(a.tickets + bh, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -815,7 +815,7 @@ __global__ __launch_bounds__(NW12 * 64) void pq12_values_kernel(const pq_decode_
     const float inv = l > 0.f ? 1.f / l : 0.f;
     *(float2 *)(orow + 2 * lane) = make_float2(o0 * inv, o1 * inv);
     if (lane == 0)
-        a.tickets[bh] = 0u;
+        ticket_reset(a.tickets + bh);
 }
 
 }  // namespace

@@ -450,7 +450,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     publish(gpart + 4 + 2 * lane, o0, o1);
     if (lane == 0)
         publish(gpart, mx, l);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    publish_wait();
 
     // ---------------- the workgroup that takes the last ticket of this (b, hq) merges the
     // splits (flash-decoding style) and leaves the ticket counter at zero for the next call
@@ -491,7 +491,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const float inv = l > 0.f ? 1.f / l : 0.f;
     *(float2 *)(orow + 2 * lane) = make_float2(o0 * inv, o1 * inv);
     if (lane == 0)
-        a.tickets[bh] = 0u;
+        ticket_reset(a.tickets + bh);
 }
 
 template <int M, int DS, typename T, int NW, bool READ_ONCE>

@@ -410,7 +410,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
             publish(gpart + 4 + 2 * lane, o0, o1);
             if (lane == 0)
                 publish(gpart, mx, l);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            publish_wait();
         }
     }
     if (S == 1)
@@ -468,7 +468,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
         *(float2 *)(a.out + (int64_t)(bh0 + g) * PQ_HEAD_DIM + 2 * lane) = make_float2(o0 * inv, o1 * inv);
     }
     if (wave == 0 && lane == 0)
-        a.tickets[bh0] = 0u;
+        ticket_reset(a.tickets + bh0);
 }
 
 }  // namespace

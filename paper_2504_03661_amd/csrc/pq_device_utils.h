@@ -71,20 +71,46 @@ __device__ inline int lane_zero()
     return z;
 }
 
-// A pair of floats stored / loaded at device scope (8-byte aligned): the store is performed at the
-// level of the memory hierarchy all XCDs share instead of staying dirty in the local L2, the load
-// does not take a stale line from the local L2.  Workgroups on different XCDs exchange split
-// partials through these without a whole-L2 write-back or invalidate.
+// ---------------------------------------------------------------------------------------------------
+// Exchange of split partials between the workgroups of one output row.  Every workgroup of the row
+//   1. publishes its partial with relaxed atomic stores at agent scope: on gfx942 / gfx950 the compiler emits
+//      these as write-through stores (sc1) that are performed in the memory all XCDs share, not left dirty in
+//      the XCD's own L2;
+//   2. waits until those stores have completed (s_waitcnt vmcnt(0): the counter falls only when the memory
+//      system has acknowledged the store at the scope it was issued with);
+//   3. takes a ticket: a relaxed atomic add at agent scope on the row's counter — all of a row's tickets are
+//      totally ordered on that one location;
+// and the workgroup that draws the last ticket
+//   4. loads all partials with relaxed atomic loads at agent scope (sc1: not served from a line its own L2
+//      might hold), issued after its ticket has returned, merges them and puts the counter back to zero.
+// Steps 2 and 4 stand where a release fence and an acquire fence would stand.  The code sequences the AMDGPU
+// backend documents for those fences at agent scope are "write back the L2, then s_waitcnt vmcnt(0)" and
+// "invalidate the caches"; the write-back and the invalidate exist for earlier plain stores and later plain
+// loads, which may live in the non-coherent L2 — every store and load of this exchange is itself an
+// agent-scope atomic access and bypasses that cache, so only the wait remains.  (The fences were measured:
+// about 1.8 us per workgroup for the release, 3 us with the acquire, on a 33 us kernel.)  The counter is put
+// back by the one workgroup that has seen every other ticket of the launch; nobody touches it again before
+// the next launch, which the kernel boundary orders after this one: calls on a context must be
+// stream-ordered.
+// ---------------------------------------------------------------------------------------------------
 __device__ inline void publish(float *p, float x, float y)
 {
     const uint64_t bits = (uint64_t)__float_as_uint(x) | ((uint64_t)__float_as_uint(y) << 32);
     __hip_atomic_store((uint64_t *)p, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// all stores this wavefront has issued are complete
+__device__ inline void publish_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ inline float2 fetch(const float *p)
 {
     const uint64_t bits = __hip_atomic_load((const uint64_t *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return make_float2(__uint_as_float((uint32_t)bits), __uint_as_float((uint32_t)(bits >> 32)));
+}
+
+__device__ inline void ticket_reset(unsigned int *ticket)
+{
+    __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __device__ inline uint32_t comp(const uint4 &v, int r)
