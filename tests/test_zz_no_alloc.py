@@ -51,6 +51,44 @@ def test_two_calls_in_a_row_the_second_smaller():
     run_both("na_f32", 1, 2, 2, 64, 700, 5, "f32", 8104)
 
 
+def test_replays_from_a_graph():
+    """The call launches kernels only (codebook re-pack, ticket fill, decode), so a caller can record it into a HIP
+    graph: replays with eager work and synchronisations between them give what the eager call gives."""
+    w = W.Workload("na_graph", 1, 8, 2, 128, 64, 6000, "f16", recent_cap=12, recent_uniform=True, seed=8105)
+    data = W.generate(w)
+    scale = W.attention_scale(w)
+    rng = np.random.default_rng(6)
+    queries = [torch.from_numpy(rng.standard_normal(data["q"].shape).astype(np.float16)).cuda() for _ in range(3)]
+    with PQSession(data, 8, "f16") as s:
+        def call(out):
+            B.pq_attn_decode_noalloc(s.cfg, s.q, s.k_codes[0], s.v_codes[0], s.ctx_len, s.k_codebook, s.v_codebook,
+                                     s.recent_k, s.recent_v, s.recent_len, scale, out)
+        eager = []
+        for q in queries:
+            s.q.copy_(q)
+            o = torch.empty_like(s.out)
+            call(o)
+            eager.append(o)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()                           # default priority
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            call(s.out)                                      # warm-up on the capturing stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            call(s.out)
+        for rep in range(6):
+            i = rep % 3
+            s.q.copy_(queries[i])
+            s.out.fill_(float("nan"))                        # eager work between the replays
+            g.replay()
+            torch.cuda.synchronize()
+            dev = (s.out - eager[i]).abs().max().item()
+            assert dev <= 4e-6, f"replay {rep} differs from the eager call by {dev:.3e}"
+
+
 def test_limits_are_rejected_before_anything_is_launched():
     lib = B.load_library()
     q = torch.zeros(16, device="cuda")
