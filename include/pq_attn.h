@@ -148,7 +148,8 @@ int pq_attn_decode(pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes, cons
  * tensor at most 2 MiB (32 KV heads in fp16, 16 in fp32); batch * n_q_heads <= 1024; with an explicit
  * n_splits, batch * n_q_heads * n_splits <= 1024 ("0 = choose" never exceeds it).
  * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams, two
- * threads, or with a call still in flight) race; stream-order them. */
+ * threads, or with a call still in flight) race; stream-order them.  The first call on a device looks the array's
+ * address up (no allocation, but a runtime query): make that call before any stream capture starts. */
 int pq_attn_decode_noalloc(const pq_attn_config *cfg /* host */, const void *q, const uint8_t *k_codes,
                            const uint8_t *v_codes, const int32_t *ctx_len, const void *k_codebook,
                            const void *v_codebook, const void *recent_k, const void *recent_v,

@@ -4,11 +4,10 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "pq_internal.h"
-
-#include <mutex>
 
 // Scratch of pq_attn_decode_noalloc: one array per GPU the library runs on, held until the process ends.
 //   [0, 2 MiB)           centroid-major image of the K codebooks      (PQ_NOALLOC_CODEBOOK_BYTES)
