@@ -80,6 +80,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.pq_attn_destroy(None) == -1
     assert lib.pq_attn_decode(None, None, None, None, None, None, None, None, None, None, 1.0, None, None) == -1
     assert lib.pq_encode_append(None, None, None, 1, None, None, None, None, None, None) == -1
+    assert lib.pq_attn_decode_noalloc(None, None, None, None, None, None, None, None, None, None, 1.0, None, None) == -1
     assert lib.pq_attn_validate_config(None) == -1
     assert lib.pq_pack_codes(None, 0, None, 1, None, None) == -1
     assert lib.pq_unpack_codes(None, 0, None, 1, None, None) == -1
@@ -94,6 +95,27 @@ def test_null_arguments_are_rejected_without_a_gpu():
     # bad config is reported before any HIP call
     assert lib.pq_attn_create(ctypes.byref(good(batch=0).c_struct()), ctypes.byref(out)) == -2
     assert out.value is None
+
+
+def test_noalloc_entry_point_checks_its_limits_on_the_host():
+    """pq_attn_decode_noalloc validates the configuration and the limits of its static scratch before any HIP call
+    (the pointers only have to be non-NULL for that)."""
+    lib = P.load_library()
+    buf = ctypes.create_string_buffer(64)
+    p = ctypes.cast(buf, ctypes.c_void_p)
+
+    def call(cfg):
+        return lib.pq_attn_decode_noalloc(ctypes.byref(cfg.c_struct()), p, p, p, p, p, p, None, None, None, 1.0, p, None)
+
+    assert call(good(batch=0)) == -2
+    assert call(good(n_q_heads=64, n_kv_heads=64)) == -4                      # 4 MiB of fp16 codebooks
+    assert call(good(dtype=P.PQ_F32)) == -4                                   # 32 heads in fp32: 4 MiB
+    assert call(good(batch=64)) == -4                                         # 2048 (sequence, head) rows
+    assert call(good(batch=16, n_splits=4)) == -4                             # 2048 partial rows
+    assert call(good(n_subspaces=32, n_centroids=4096)) == -3                 # 12-bit codes
+    assert lib.pq_attn_decode_noalloc(ctypes.byref(good().c_struct()), p, p, p, p, p, p, p, None, None, 1.0, p, None) == -1
+    assert lib.pq_attn_decode_noalloc(ctypes.byref(good().c_struct()), p, p, p, p, p, p, None, None, None,
+                                      float("nan"), p, None) == -2
 
 
 def test_status_strings():
