@@ -197,6 +197,28 @@ def test_encode_append_bit_exact_then_decode(n_old, n_new):
         check(out.cpu().numpy(), ref, "after append")
 
 
+def test_append_overflow_saturates_and_flags():
+    """Tokens that would land beyond the capacity are dropped (V units mix old and new tokens: the kept ones must
+    still be right), the length saturates, bit 0 of the error word is set once."""
+    w = W.Workload("ov12", 2, 2, 2, 128, 32, 300, "f16", n_new=100, seed=4712, ctx_lens=(150, 250), n_centroids=4096)
+    data = W.generate(w, ctx_cap=300)
+    want_k = O.encode(data["new_k"], data["k_codebook"])
+    want_v = O.encode(data["new_v"], data["v_codebook"])
+    with PQSession(data, 2, "f16", max_context=300) as s:
+        s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())
+        torch.cuda.synchronize()
+        assert s.ctx_len.cpu().tolist() == [250, 300]
+        assert s.device_error() == 1
+        assert s.device_error() == 0
+        got_k, got_v = s.unpack(PQ_CODES_K, 300), s.unpack(PQ_CODES_V, 300)
+    np.testing.assert_array_equal(got_k[0, :, 150:250], want_k[0])
+    np.testing.assert_array_equal(got_v[0, :, 150:250], want_v[0])
+    np.testing.assert_array_equal(got_k[1, :, 250:300], want_k[1, :, :50])
+    np.testing.assert_array_equal(got_v[1, :, 250:300], want_v[1, :, :50])
+    np.testing.assert_array_equal(got_k[0, :, :150], data["k_codes"][0, :, :150])      # older tokens untouched
+    np.testing.assert_array_equal(got_v[1, :, :250], data["v_codes"][1, :, :250])
+
+
 def test_long_append_runs_in_chunks_through_the_fixed_staging():
     """The staging of a 12-bit context is sized at creation (8 MiB per tensor, at least 64 tokens per head); an
     append of more tokens per head runs as several chunks: 512 (sequence, head) pairs leave 256 tokens per chunk,
