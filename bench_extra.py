@@ -25,7 +25,7 @@ pq12: the 12-bit setting (M = 32, 4096 centroids, 48 bytes per token and tensor;
 against HBM: algorithmic bytes = codes + recent rows + both codebooks once per KV head (2 MiB per head: at 32K
 tokens they are 40 % of the bytes) + q / out.  With few (sequence, head) pairs the decode runs in two passes
 (partial scores per subspace group, then softmax and values): "n_passes" in the output.
-ctx: decode kernel time against context length, 1K .. 128K tokens, for 1 x 32 heads (one query head per KV head) and for
+ctx: decode kernel time against context length, 1K .. 128K tokens (and short sequences in a 128K-capacity cache), for 1 x 32 heads (one query head per KV head) and for
 32 query / 8 KV heads (the grouped-query kernel); split counts as the library chooses them.
 
 step1: one decoding step of a single sequence, 32 heads at 32K tokens: append of one token per head, then decode, for
@@ -260,6 +260,25 @@ def ctx():
                     dec[it[0] % copies]()
                     it[0] += 1
                 rows[str(n)] = {"us": round(_span_ms(step, 400, warmup=1500) * 1e3, 2), "n_splits": s.n_splits}
+        res[label] = rows
+    # a short sequence in a long cache: the grid is sized for the 128K capacity, the live splits follow the length
+    for label, hq, hkv in (("32_heads_in_128k_cache", 32, 32), ("32q_8kv_in_128k_cache", 32, 8)):
+        w = W.Workload("ctx_cap", 1, hq, hkv, 128, 64, 131072, "f16", recent_cap=128, recent_fixed=128, seed=W.BASE_SEED + 22)
+        data = W.generate(w)
+        copies = max(2, min(16, -(-(1 << 30) // (2 * hkv * 131072 * 64))))
+        rows = {}
+        with PQSession(data, hq, "f16", code_copies=copies) as s:
+            dec = [s.prepared_decode(W.attention_scale(w), copy=c) for c in range(copies)]
+            it = [0]
+
+            def step():
+                dec[it[0] % copies]()
+                it[0] += 1
+            for n in (256, 2048, 16384, 131072):
+                s.ctx_len.fill_(n)
+                live = min(s.n_splits, max(1, ((n + 63) // 64) // 4, 128 // 16))
+                rows[str(n)] = {"us": round(_span_ms(step, 400, warmup=1500) * 1e3, 2), "launched_splits": s.n_splits,
+                                "live_splits": live}
         res[label] = rows
     print(json.dumps(res))
 

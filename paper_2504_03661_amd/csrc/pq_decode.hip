@@ -129,10 +129,12 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     // 32-bit unsigned arithmetic: the capacities are limited to 2^24 tokens and S to 64, and a
     // 64-bit division costs more instructions than the whole table build
     const uint32_t nblk = (uint32_t)(N + 63) >> 6;
-    // The grid is sized for the capacity; the LIVE splits follow the length: a split scans at least 4 blocks,
+    // The grid is sized for the capacity; the LIVE splits follow the length: a split scans at least 4 blocks
+    // (or folds in at least 16 recent rows),
     // so a short sequence in a long cache uses the first few splits only and the others leave here, before
     // they build tables (every workgroup of the row computes the same count; the merge expects that many).
-    const int S = (int)(nblk / 4u < 1u ? 1u : (nblk / 4u < (uint32_t)S_grid ? nblk / 4u : (uint32_t)S_grid));
+    const uint32_t want = nblk / 4u > (uint32_t)R / 16u ? nblk / 4u : (uint32_t)R / 16u;  // ... or 16 recent rows
+    const int S = (int)(want < 1u ? 1u : (want < (uint32_t)S_grid ? want : (uint32_t)S_grid));
     if (split >= S)
         return;
     const int blk0 = (int)(nblk * (uint32_t)split / (uint32_t)S);

@@ -144,8 +144,10 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
     R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
     const uint32_t nblk = (uint32_t)(N + 63) >> 6;
-    // live splits follow the length (at least 4 blocks each); the others leave before the images are staged
-    const int S = (int)(nblk / 4u < 1u ? 1u : (nblk / 4u < (uint32_t)S_grid ? nblk / 4u : (uint32_t)S_grid));
+    // live splits follow the length (at least 4 blocks or 16 recent rows each); the others leave before the images
+    // are staged
+    const uint32_t want = nblk / 4u > (uint32_t)R / 16u ? nblk / 4u : (uint32_t)R / 16u;  // ... or 16 recent rows
+    const int S = (int)(want < 1u ? 1u : (want < (uint32_t)S_grid ? want : (uint32_t)S_grid));
     if (split >= S)
         return;
     const int blk0 = (int)(nblk * (uint32_t)split / (uint32_t)S);
