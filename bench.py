@@ -2,7 +2,7 @@
 """Benchmark of PQ decode attention on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--copies C] [--no-cpu-baseline] [--warm]
-                    [--no-others]
+                    [--no-others] [--no-next]
 
 A step is one pass of the hot path over one batch: pq_attn_decode (table build,
 score pass, softmax, value pass, recent rows, split merge — one fused kernel) on
@@ -21,7 +21,9 @@ launches divided by K (so it includes the gap between kernels).
 `cpu_baseline` is the double-precision oracle on the same workload on the host.
 The default run (workload 1) also times the other named workloads — batched, grouped-query 128K, 2-bit +
 encode — with fewer launches each and lists them under `other_workloads` (kernel time, algorithmic bytes,
-fraction of the HBM peak); `value` stays the metric's workload.
+fraction of the HBM peak); `value` stays the metric's workload.  It then runs the measurements of
+bench_extra.py for the operations around the path (bulk encode at prompt shape, encode on a second stream,
+codebook training, 12-bit codes) and lists their results under `next_rows`, each with its own roofline figure.
 """
 import argparse
 import json
@@ -124,7 +126,9 @@ def main():
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="also time the same-buffer (cache-warm) case")
-    ap.add_argument("--no-others", action="store_true", help="skip the other named workloads (only with --config 1 they run)")
+    ap.add_argument("--no-others", action="store_true", help="skip the other named workloads and the bench_extra.py measurements (only with --config 1 they run)")
+    ap.add_argument("--no-next", action="store_true",
+                    help="skip only the bench_extra.py measurements")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -284,6 +288,17 @@ def main():
     if args.config == 1 and not args.no_others:
         others = [time_other_workload(k, steps=n, warmup=wu) for k, n, wu in ((3, 1500, 800), (2, 400, 200), (4, 200, 100))]
 
+    next_rows = None
+    if args.config == 1 and not args.no_next and not args.no_others:
+        import bench_extra
+        next_rows = {}
+        for name, fn in (("prefill_encode", bench_extra.prefill), ("pq12", bench_extra.pq12),
+                         ("kmeans_train", bench_extra.train), ("async_encode", bench_extra.async_encode)):
+            t = time.perf_counter()
+            next_rows[name] = fn()
+            next_rows[name]["wall_s"] = round(time.perf_counter() - t, 1)
+            torch.cuda.empty_cache()
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import pq_oracle
@@ -337,6 +352,7 @@ def main():
                    "code_copies_rotated": copies, "seed": w.seed},
         "roofline": roofline,
         "other_workloads": others,
+        "next_rows": next_rows,
         "cpu_baseline": cpu,
         "paper_context": "MILLION reports 2.09x end-to-end and 2.01x attention speed-up at 32K on one A40 "
                          "(Llama-2-7B, TPOT 63.41 ms vs 132.97 ms); no kernel-level figure is published",

@@ -86,7 +86,7 @@ def prefill():
     ops = vectors * w.n_subspaces * ops_per_subvector
     achieved = ops / (ms * 1e-3)
     scan_ops = vectors * w.n_subspaces * 256 * (2 * w.sub_dim + 3)
-    print(json.dumps({"mode": "prefill_encode", "workload": w.name, "ms": round(ms, 3),
+    return ({"mode": "prefill_encode", "workload": w.name, "ms": round(ms, 3),
                       "vectors_per_s": round(vectors / (ms * 1e-3)), "tokens_per_s": round(n_new / (ms * 1e-3)),
                       "roofline": {"bound": "alu", "unit": "lane-op/s", "achieved": achieved,
                                    "peak": ALU_LANE_OPS_PER_S, "frac": round(achieved / ALU_LANE_OPS_PER_S, 4),
@@ -94,7 +94,7 @@ def prefill():
                       # a SIMD issues a 64-lane vector instruction in 4 cycles and a 4x4x4 matrix instruction in 8
                       "ms_at_the_issue_limit": round(vectors * w.n_subspaces / 64 * (4 * ops_per_subvector + 8 * mfma_per_subvector)
                                                      / (1024 * 2.4e9) * 1e3, 3),
-                      "ms_of_the_fp64_scan_at_alu_peak": round(scan_ops / ALU_LANE_OPS_PER_S * 1e3, 3)}))
+                      "ms_of_the_fp64_scan_at_alu_peak": round(scan_ops / ALU_LANE_OPS_PER_S * 1e3, 3)})
 
 
 def async_encode():
@@ -137,11 +137,11 @@ def async_encode():
         t_dec = _span_ms(decode_only, steps, warmup=50)   # warm-ups pass the clock ramp after an idle period
         t_enc = _span_ms(encode_only, steps, warmup=50)
         t_both = _span_ms(overlapped, steps, warmup=50)
-    print(json.dumps({"mode": "async_encode", "workload": w.name, "decode_ms": round(t_dec, 4),
+    return ({"mode": "async_encode", "workload": w.name, "decode_ms": round(t_dec, 4),
                       "encode_ms": round(t_enc, 4), "serial_ms": round(t_dec + t_enc, 4),
                       "overlapped_ms": round(t_both, 4),
                       "hidden_fraction_of_encode": round((t_dec + t_enc - t_both) / t_enc, 3),
-                      "streams": "two streams of default priority"}))
+                      "streams": "two streams of default priority"})
 
 
 def train():
@@ -174,14 +174,14 @@ def train():
     trained = cb.cpu().numpy()
     B.pq_attn_destroy(ctx)
 
-    print(json.dumps({"mode": "kmeans_train", "workload": f"{Hkv} heads x {n} samples, M={M}, {iters} Lloyd iterations",
+    return ({"mode": "kmeans_train", "workload": f"{Hkv} heads x {n} samples, M={M}, {iters} Lloyd iterations",
                       "ms_per_iteration": round(ms, 3),
                       "sub_vectors_per_s": round(Hkv * M * n / (ms * 1e-3), 1),
                       "alu": {"bound": "alu", "achieved": round(ops / (ms * 1e-3) / 1e12, 2),
                               "peak": round(ALU_LANE_OPS_PER_S / 1e12, 1), "unit": "T vector operations/s",
                               "frac": round(ops / (ms * 1e-3) / ALU_LANE_OPS_PER_S, 4)},
                       "ms_of_the_fp64_scan_at_alu_peak": round(scan_ops / ALU_LANE_OPS_PER_S * 1e3, 3),
-                      "trained_codebook_finite": bool(np.isfinite(trained.astype(np.float32)).all())}))
+                      "trained_codebook_finite": bool(np.isfinite(trained.astype(np.float32)).all())})
 
 
 def pq12():
@@ -237,7 +237,7 @@ def pq12():
                               # 4 cycles of a SIMD per 64-lane vector instruction, 8 per 4x4x4 matrix instruction (4 per group)
                               "ms_at_the_issue_limit": round(pairs / 64 * (4 * (4096 * 4.25 / 4 + 1100) + 8 * 4096) / (1024 * 2.4e9) * 1e3, 3),
                               "ms_of_the_fp64_scan_at_alu_peak": round(pairs * 4096 * 11 / ALU_LANE_OPS_PER_S * 1e3, 3)}
-    print(json.dumps(res))
+    return res
 
 
 def ctx():
@@ -280,7 +280,7 @@ def ctx():
                 rows[str(n)] = {"us": round(_span_ms(step, 400, warmup=1500) * 1e3, 2), "launched_splits": s.n_splits,
                                 "live_splits": live}
         res[label] = rows
-    print(json.dumps(res))
+    return res
 
 
 def step1():
@@ -318,23 +318,13 @@ def step1():
             t_all = _span_ms(whole, 400, warmup=800) * 1e3
         res[label] = {"length_reset_copy": round(t_reset, 2), "append_one_token_per_head": round(t_app - t_reset, 2),
                       "append_and_decode": round(t_all - t_reset, 2)}
-    print(json.dumps(res))
+    return res
 
 
 if __name__ == "__main__":
+    modes = {"prefill": prefill, "async": async_encode, "train": train, "pq12": pq12, "ctx": ctx, "step1": step1}
     mode = sys.argv[1] if len(sys.argv) > 1 else ""
-    if mode == "prefill":
-        prefill()
-    elif mode == "async":
-        async_encode()
-    elif mode == "train":
-        train()
-    elif mode == "pq12":
-        pq12()
-    elif mode == "ctx":
-        ctx()
-    elif mode == "step1":
-        step1()
-    else:
+    if mode not in modes:
         print(__doc__)
         sys.exit(2)
+    print(json.dumps(modes[mode]()))
