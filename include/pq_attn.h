@@ -89,6 +89,12 @@ int pq_attn_n_splits(const pq_attn_ctx *ctx);
  * softmax and values). */
 int pq_attn_n_passes(const pq_attn_ctx *ctx);
 
+/* Query heads one decode workgroup serves: 1 for the kernels that build per-query
+ * tables, 2..4 for the grouped-query kernels (one pass over a KV head's codes for
+ * that many query heads; chosen when Hq / Hkv is a multiple of 2, 3 or 4 and the
+ * context is fp16). */
+int pq_attn_heads_per_workgroup(const pq_attn_ctx *ctx);
+
 /* Registers the codebooks trained offline (Section III-A, "Offline PQ Codebook
  * Training"): C_K, C_V as [Hkv][M][C][ds] in the context dtype, device memory.
  * The kernels launched by this call copy them into context-owned memory (a plain

@@ -79,6 +79,8 @@ def load_library():
     L.pq_attn_n_splits.argtypes = [vp]
     L.pq_attn_n_passes.restype = ctypes.c_int
     L.pq_attn_n_passes.argtypes = [vp]
+    L.pq_attn_heads_per_workgroup.restype = ctypes.c_int
+    L.pq_attn_heads_per_workgroup.argtypes = [vp]
     L.pq_attn_set_codebooks.restype = ctypes.c_int
     L.pq_attn_set_codebooks.argtypes = [vp, vp, vp, vp]
     L.pq_attn_decode.restype = ctypes.c_int
@@ -158,6 +160,10 @@ def pq_attn_n_splits(ctx: int) -> int:
 
 def pq_attn_n_passes(ctx: int) -> int:
     return int(load_library().pq_attn_n_passes(ctx))
+
+
+def pq_attn_heads_per_workgroup(ctx: int) -> int:
+    return int(load_library().pq_attn_heads_per_workgroup(ctx))
 
 
 def pq_attn_set_codebooks(ctx, k_codebook, v_codebook, stream=None) -> None:

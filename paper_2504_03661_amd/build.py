@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpq_attn.so")
-SOURCES = ["pq12_codes.hip", "pq12_decode.hip", "pq_api.hip", "pq_decode.hip", "pq_decode_grouped.hip", "pq_encode.hip", "pq_kmeans.hip", "pq_layout.hip"]
+SOURCES = ["pq12_codes.hip", "pq12_decode.hip", "pq12_decode_grouped.hip", "pq_api.hip", "pq_decode.hip", "pq_decode_grouped.hip", "pq_encode.hip", "pq_kmeans.hip", "pq_layout.hip"]
 HEADERS = [os.path.join(CSRC, "pq_internal.h"), os.path.join(CSRC, "pq_device_utils.h"), os.path.join(CSRC, "pq_nearest_filter.h"), os.path.join(CSRC, "pq_filter_constants.h"),
            os.path.join(ROOT, "include", "pq_attn.h")]
 

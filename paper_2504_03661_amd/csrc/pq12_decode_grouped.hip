@@ -1,0 +1,549 @@
+// Decode attention over a KV cache quantized with 12-bit PQ codes (M = 32 subspaces of 4 dims, 4096
+// centroids: Section IV-A) for GROUPED queries — 2..4 query heads per workgroup read one KV head — one
+// fused kernel.
+//
+// Same result as the per-head 12-bit kernel (Eq. 7 = Eq. 6), different evaluation.  There every query head
+// builds its own score tables and walks the KV head's codes by itself: G times the table refills and G times
+// the LDS gathers, which are what bounds that kernel.  Here a KV head's codes are gathered ONCE for the
+// group, from the CODEBOOKS (not from per-query tables), and the contraction over the query heads goes to
+// the matrix cores.  A subspace of 4 dims is exactly the inner dimension of v_mfma_f32_4x4x4_16B_f16, so a
+// gathered centroid (8 bytes) is an operand as it comes out of LDS:
+//
+//   score passes  8 groups of 4 subspaces: the group's slice of the KEY codebook [4][4096][4] fp16 (128 KiB)
+//                 is copied to LDS.  Lane (quad s, row i) gathers the centroid of token s + 16 i of a
+//                 64-token block: A = the quad's 4 tokens x 4 dims, B = the 4 query heads' slice of this
+//                 subspace (lane j: head j), so D[token][head] lands with lane j holding head j's scores of
+//                 the quad's 4 tokens — which is the A operand layout of the value passes, no transposition.
+//                 One gather and one matrix instruction per (token, subspace) serve all heads.
+//   softmax       all scores of the round exist before the first weight is needed: maximum per head over the
+//                 workgroup (running maximum / rescale only between rounds), weights split into fp16 hi + lo
+//                 (p = hi + lo to 2^-22 relative) in the registers that held the scores.
+//   value passes  8 groups of 4 subspaces: the slice of the VALUE codebook goes to LDS; lane (s, j) gathers
+//                 subspace j of the tokens s + 16 k of a 128-token block (its 12-byte unit), re-packs 4
+//                 tokens x 4 dims into one B operand per dim (8 x v_perm) and accumulates
+//                 D[head][lane's subspace, dim] += weights[head][4 tokens] x B — hi and lo — for all heads.
+//                 The 16 token streams (quads) are summed at the end of each group into an fp32 output
+//                 tile in LDS.
+// The K and V code layouts are those of the per-head kernel (pq_internal.h); a K unit holds 8 subspaces and
+// serves two consecutive score passes from registers, so each code byte still leaves HBM once.  Recent rows,
+// split partials, ticket and merge follow the 8-bit grouped kernel.
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include "pq_internal.h"
+#include "pq_device_utils.h"
+
+namespace {
+
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int GN = 16;                           // wavefronts per workgroup
+constexpr int GH = 4;                            // rows of the 4x4x4 instruction = query heads per workgroup
+constexpr int G12_TAB = 0;                       // 128 KiB: codebook slice [4 subspaces][4096][4] fp16
+constexpr int G12_Q = 131072;                    // fp16 q [4][128] (heads beyond the group: zero rows)
+constexpr int G12_O = G12_Q + GH * 256;          // float [4][128]: the scan's un-normalised output rows
+constexpr int G12_WMAX = G12_O + GH * 512;       // float [16][4]: a round's maxima per wavefront and head
+constexpr int G12_LW = G12_WMAX + GN * GH * 4;   // float [16][4]: weight sums per wavefront and head
+constexpr int G12_FLAG = G12_LW + GN * GH * 4;   // int: "this workgroup drew the last ticket"
+constexpr int G12_BYTES = G12_FLAG + 16;
+// wavefront partials of the recent rows float [16][4][PQ_PART_STRIDE] reuse the table once the scan is over
+constexpr int G12_PART = G12_TAB;
+static_assert(GN * GH * PQ_PART_STRIDE * 4 <= 131072, "partials fit in the table region");
+static_assert(G12_BYTES <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+
+__device__ inline f16x4 f16x4_of(uint32_t lo, uint32_t hi)
+{
+    u32x2 v = {lo, hi};
+    return __builtin_bit_cast(f16x4, v);
+}
+
+__device__ inline void unpack8g(const uint32_t w0, const uint32_t w1, const uint32_t w2, uint32_t (&c)[8])
+{
+    c[0] = w0 & 0xfffu;
+    c[1] = (w0 >> 12) & 0xfffu;
+    c[2] = ((w0 >> 24) | (w1 << 8)) & 0xfffu;
+    c[3] = (w1 >> 4) & 0xfffu;
+    c[4] = (w1 >> 16) & 0xfffu;
+    c[5] = ((w1 >> 28) | (w2 << 4)) & 0xfffu;
+    c[6] = (w2 >> 8) & 0xfffu;
+    c[7] = w2 >> 20;
+}
+
+// sum / maximum over the 16 lanes of the wavefront that share lane % 4 (one head, or one subspace)
+__device__ inline float sum_same_row_in_dpp_row(float x)
+{
+    x += dpp_move<0x124>(x);  // row_ror:4
+    x += dpp_move<0x128>(x);  // row_ror:8
+    return x;
+}
+
+__device__ inline float max_same_row(float x)
+{
+    x = fmaxf(x, dpp_move<0x124>(x));
+    x = fmaxf(x, dpp_move<0x128>(x));
+    x = fmaxf(x, __shfl_xor(x, 16));
+    x = fmaxf(x, __shfl_xor(x, 32));
+    return x;
+}
+
+template <bool NT> __device__ inline uint32_t load_word(const uint32_t *p)
+{
+    return NT ? __builtin_nontemporal_load(p) : *p;
+}
+
+// 128 KiB from memory (L2 after the first workgroup of the XCD) to the table region: 8 x 16 bytes per thread
+__device__ inline void stage_slice(lds_u8 *lbase, const __half *slice, int tid)
+{
+    // the slice address is wave-uniform: kept in scalar registers (base + 32-bit lane offset addressing), so that
+    // no per-lane 64-bit address per piece and slice is computed ahead of the loops and kept alive
+    const uint64_t p = (uint64_t)slice;
+    // (the builtin returns a signed int: widen through uint32_t, or a low word with bit 31 set would sign-extend
+    // into the high word)
+    const uint32_t p_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(p >> 32));
+    const uint32_t p_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+    typedef __attribute__((address_space(1))) const char global_char;  // a global, not a generic, address
+    typedef __attribute__((address_space(1))) const u32x4 global_u32x4;
+    global_char *base = (global_char *)(((uint64_t)p_hi << 32) | (uint64_t)p_lo);
+    const uint32_t off = (uint32_t)tid * 16u;
+    u32x4 t[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+        t[k] = *(global_u32x4 *)(base + k * (GN * 64 * 16) + off);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+        *(lds_u32x4 *)(lbase + G12_TAB + (tid + k * (GN * 64)) * 16) = t[k];
+}
+
+// WAVE_VB: 128-token blocks per wavefront and round (8 score registers per lane each); a workgroup takes
+// 16 WAVE_VB blocks per round.  READ_ONCE: one workgroup per (sequence, KV head, split) reads the codes, so
+// they stream with the non-temporal hint; with more than 4 query heads per KV head several workgroups share
+// the stream through their XCD's L2 and load normally.
+template <int WAVE_VB, bool READ_ONCE>
+__global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_decode_args a)
+{
+    constexpr int ROUND_VB = GN * WAVE_VB;
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[G12_BYTES];
+    lds_u8 *lbase = (lds_u8 *)smem;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int G = a.Gs;  // query heads of this workgroup (2..4)
+
+    const uint32_t grid = gridDim.x;
+    uint32_t logical = blockIdx.x;
+    if ((grid & 7u) == 0)
+        logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
+    const int S = a.S;
+    // neighbours on an XCD: the splits of a (sequence, KV head, sub-group of G query heads), the sub-groups of the
+    // KV head, then the same KV head of the other sequences (they stage the same codebook slices from L2)
+    const int unit = (int)(logical / (uint32_t)S);
+    const int split = (int)(logical - (uint32_t)unit * (uint32_t)S);
+    const int n_sub = a.G / G;
+    const int hb = (int)((uint32_t)unit / (uint32_t)n_sub);  // hkv * B + b
+    const int sub_group = unit - hb * n_sub;
+    const int hkv = (int)((uint32_t)hb / (uint32_t)a.B);
+    const int b = hb - hkv * a.B;
+    const int bkv = b * a.Hkv + hkv;
+    const int bh0 = b * a.Hq + hkv * a.G + sub_group * G;  // first query head of this workgroup
+
+    int N = a.ctx_len[b];
+    int R = (a.recent_k != nullptr && a.recent_len != nullptr) ? a.recent_len[b] : 0;
+    N = N < 0 ? 0 : (N > a.max_context ? a.max_context : N);
+    R = R < 0 ? 0 : (R > a.max_recent ? a.max_recent : R);
+    const uint32_t nvb = (uint32_t)(N + 127) >> 7;  // 128-token blocks of the sequence
+    const int vb0 = (int)(nvb * (uint32_t)split / (uint32_t)S);
+    const int vb1 = (int)(nvb * (uint32_t)(split + 1) / (uint32_t)S);
+    const int r0 = (int)((uint32_t)R * (uint32_t)split / (uint32_t)S);
+    const int r1 = (int)((uint32_t)R * (uint32_t)(split + 1) / (uint32_t)S);
+
+    const uint8_t *k_head = a.k_codes + (int64_t)bkv * a.head_stride;
+    const uint8_t *v_head = a.v_codes + (int64_t)bkv * a.head_stride;
+    const __half *kcb = (const __half *)a.kcb_packed + (int64_t)hkv * PQ12_M * PQ12_CENTROIDS * 4;
+    const __half *vcb = (const __half *)a.vcb_packed + (int64_t)hkv * PQ12_M * PQ12_CENTROIDS * 4;
+
+    // the group's queries (fp16 as they come: the products with fp16 centroids are exact in the fp32
+    // accumulator; the softmax scale is applied to the finished score) and a zeroed output tile
+    if (tid < 64) {
+        u32x4 qraw = {0u, 0u, 0u, 0u};
+        if (tid < 16 * G)
+            qraw = *((const u32x4 *)((const __half *)a.q + (int64_t)bh0 * PQ_HEAD_DIM) + tid);
+        *(lds_u32x4 *)(lbase + G12_Q + tid * 16) = qraw;
+    }
+    lds_f32 *o_lds = (lds_f32 *)(lbase + G12_O);
+    lds_f32 *wmax = (lds_f32 *)(lbase + G12_WMAX);
+    if (tid < GH * 128)
+        o_lds[tid] = 0.f;
+
+    const int quad = lane >> 2;  // the 4x4x4 block of this lane: a stream of tokens (token % 16)
+    const int row = lane & 3;    // query head (as the holder of scores and weights); subspace of the group (value passes)
+    // score passes: this lane gathers token quad + 16 row of a 64-token block
+    const uint32_t *k_units = (const uint32_t *)k_head + (quad + 16 * row) * 3;
+    const uint32_t *v_units = (const uint32_t *)v_head + lane * 3;
+    const uint32_t v_tab = (uint32_t)(G12_TAB + row * (PQ12_CENTROIDS * 8));
+
+    float m_run[GH];           // running maxima, the same in every wavefront of the workgroup
+    float l_lane = 0.f;        // this lane's share of head `row`'s weight sum
+#pragma unroll
+    for (int g = 0; g < GH; ++g)
+        m_run[g] = NEG_BIG;
+
+    for (int sb = vb0; sb < vb1; sb += ROUND_VB) {
+        // wavefront w owns blocks sb + w + 16 jj, jj < n_jj
+        const int left = vb1 - sb - wave;
+        const int n_jj = left <= 0 ? 0 : (left + GN - 1) / GN < WAVE_VB ? (left + GN - 1) / GN : WAVE_VB;
+        const int last_vb = vb1 - 1;  // loads beyond the wavefront's blocks re-read a valid block and are not used
+        f32x4 score[2 * WAVE_VB];     // element r: token quad + 16 r of the 64-token half block, head `row`
+        u32x4 wt[2 * WAVE_VB];        // the same tokens' weights as A operands: fp16 hi (x, y) and lo (z, w)
+#pragma unroll
+        for (int e = 0; e < 2 * WAVE_VB; ++e)
+            score[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        // ---------------- score passes: 4 unit groups of 8 subspaces, two table slices of 4 subspaces each
+#pragma nounroll
+        for (int g = 0; g < 4; ++g) {
+            uint32_t ku[2 * WAVE_VB][3];
+#pragma unroll
+            for (int jj = 0; jj < WAVE_VB; ++jj) {
+                const int want = sb + wave + GN * jj;
+                const int vb = want < last_vb ? want : last_vb;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t *u = k_units + (((int64_t)(2 * vb + h) * 4 + g) * 64) * 3;
+#pragma unroll
+                    for (int e = 0; e < 3; ++e)
+                        ku[2 * jj + h][e] = load_word<READ_ONCE>(u + e);
+                }
+            }
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                __syncthreads();  // the table region is free (and, the first time, the queries are in LDS)
+                stage_slice(lbase, kcb + (int64_t)(8 * g + 4 * hf) * PQ12_CENTROIDS * 4, tid);
+                __syncthreads();
+                f16x4 qb[4];  // B operands: head `row`'s query slice of the 4 resident subspaces
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    qb[j] = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(lbase + G12_Q + row * 256 + (8 * g + 4 * hf + j) * 8));
+#pragma unroll
+                for (int jj = 0; jj < WAVE_VB; ++jj) {
+                    if (jj >= n_jj)
+                        continue;  // wave-uniform; `continue`, not `break`: the loop must unroll (registers are indexed by jj)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        uint32_t c[8];
+                        unpack8g(ku[2 * jj + h][0], ku[2 * jj + h][1], ku[2 * jj + h][2], c);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const u32x2 cv = *(lds_u32x2 *)(lbase + G12_TAB + j * (PQ12_CENTROIDS * 8) + c[4 * hf + j] * 8);
+                            score[2 * jj + h] =
+                                __builtin_amdgcn_mfma_f32_4x4x4f16(f16x4_of(cv.x, cv.y), qb[j], score[2 * jj + h], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+
+        // ---------------- softmax of the round, per head: the scores become fp16 hi / lo weights
+        float mx = NEG_BIG;
+#pragma unroll
+        for (int jj = 0; jj < WAVE_VB; ++jj)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int tok = (sb + wave + GN * jj) * 128 + 64 * h + quad + 16 * r;
+                    const bool valid = jj < n_jj && tok < N;
+                    const float s = valid ? score[2 * jj + h][r] * a.scale_log2e : NEG_BIG;
+                    score[2 * jj + h][r] = s;
+                    mx = fmaxf(mx, s);
+                }
+        mx = max_same_row(mx);
+        if (lane < GH)
+            wmax[wave * GH + lane] = mx;
+        __syncthreads();
+        float alpha[GH];
+#pragma unroll
+        for (int g = 0; g < GH; ++g) {
+            float mw = NEG_BIG;
+#pragma unroll
+            for (int w = 0; w < GN; ++w)
+                mw = fmaxf(mw, wmax[w * GH + g]);
+            const float m_new = fmaxf(m_run[g], mw);
+            alpha[g] = __builtin_amdgcn_exp2f(m_run[g] - m_new);
+            m_run[g] = m_new;
+        }
+        const float m_own = row == 0 ? m_run[0] : row == 1 ? m_run[1] : row == 2 ? m_run[2] : m_run[3];
+        const float a_own = row == 0 ? alpha[0] : row == 1 ? alpha[1] : row == 2 ? alpha[2] : alpha[3];
+        l_lane *= a_own;
+        if (wave < 2 * GH) {  // the output tile of head wave / 2 follows the new maximum (nobody adds to it before the
+                              // next barrier)
+            const int hh = wave >> 1;
+            const float a_h = hh == 0 ? alpha[0] : hh == 1 ? alpha[1] : hh == 2 ? alpha[2] : alpha[3];
+            o_lds[tid] *= a_h;
+        }
+#pragma unroll
+        for (int e = 0; e < 2 * WAVE_VB; ++e) {
+            _Float16 hi[4], lo[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                // an invalid token carries NEG_BIG; against a finite maximum that is weight 0, and a round whose
+                // maximum is NEG_BIG itself has no valid token at all
+                const float p = score[e][r] > 0.5f * NEG_BIG ? __builtin_amdgcn_exp2f(score[e][r] - m_own) : 0.f;
+                l_lane += p;
+                hi[r] = (_Float16)p;
+                lo[r] = (_Float16)(p - (float)hi[r]);
+            }
+            const f16x4 vh = {hi[0], hi[1], hi[2], hi[3]}, vl = {lo[0], lo[1], lo[2], lo[3]};
+            const u32x2 bh = __builtin_bit_cast(u32x2, vh), bl = __builtin_bit_cast(u32x2, vl);
+            wt[e] = u32x4{bh.x, bh.y, bl.x, bl.y};
+        }
+
+        // ---------------- value passes: 8 groups of 4 subspaces
+#pragma nounroll
+        for (int gv = 0; gv < 8; ++gv) {
+            uint32_t vu[WAVE_VB][3];
+#pragma unroll
+            for (int jj = 0; jj < WAVE_VB; ++jj) {
+                const int want = sb + wave + GN * jj;
+                const int vb = want < last_vb ? want : last_vb;
+                const uint32_t *u = v_units + (((int64_t)vb * 8 + gv) * 64) * 3;
+#pragma unroll
+                for (int e = 0; e < 3; ++e)
+                    vu[jj][e] = load_word<READ_ONCE>(u + e);
+            }
+            __syncthreads();  // the table region is free
+            stage_slice(lbase, vcb + (int64_t)(4 * gv) * PQ12_CENTROIDS * 4, tid);
+            __syncthreads();
+            f32x4 acc[4];  // acc[d][g]: head g, dim d of subspace 4 gv + row, this quad's tokens
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int jj = 0; jj < WAVE_VB; ++jj) {
+                if (jj >= n_jj)
+                    continue;
+                uint32_t c[8];
+                unpack8g(vu[jj][0], vu[jj][1], vu[jj][2], c);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    u32x2 cv[4];  // tokens quad + 16 k of the half block, k = 0..3: dims (0, 1) and (2, 3)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        cv[k] = *(lds_u32x2 *)(lbase + v_tab + c[4 * h + k] * 8);
+                    f16x4 B[4];  // per dim: the 4 tokens' values
+                    B[0] = f16x4_of(__builtin_amdgcn_perm(cv[1].x, cv[0].x, 0x05040100u),
+                                    __builtin_amdgcn_perm(cv[3].x, cv[2].x, 0x05040100u));
+                    B[1] = f16x4_of(__builtin_amdgcn_perm(cv[1].x, cv[0].x, 0x07060302u),
+                                    __builtin_amdgcn_perm(cv[3].x, cv[2].x, 0x07060302u));
+                    B[2] = f16x4_of(__builtin_amdgcn_perm(cv[1].y, cv[0].y, 0x05040100u),
+                                    __builtin_amdgcn_perm(cv[3].y, cv[2].y, 0x05040100u));
+                    B[3] = f16x4_of(__builtin_amdgcn_perm(cv[1].y, cv[0].y, 0x07060302u),
+                                    __builtin_amdgcn_perm(cv[3].y, cv[2].y, 0x07060302u));
+                    const f16x4 Ahi = f16x4_of(wt[2 * jj + h].x, wt[2 * jj + h].y);
+                    const f16x4 Alo = f16x4_of(wt[2 * jj + h].z, wt[2 * jj + h].w);
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        acc[d] = __builtin_amdgcn_mfma_f32_4x4x4f16(Ahi, B[d], acc[d], 0, 0, 0);
+                        acc[d] = __builtin_amdgcn_mfma_f32_4x4x4f16(Alo, B[d], acc[d], 0, 0, 0);
+                    }
+                }
+            }
+            // the 16 token streams: 4 per row of 16 lanes by DPP, the 4 rows by LDS adds
+            if (n_jj > 0) {  // wave-uniform
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+#pragma unroll
+                    for (int g = 0; g < GH; ++g) {
+                        const float v = sum_same_row_in_dpp_row(acc[d][g]);
+                        if ((lane & 12) == 0)
+                            __hip_atomic_fetch_add((float *)(o_lds + g * 128 + (4 * gv + row) * 4 + d), v, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
+            }
+        }
+    }
+
+    // ---------------- recent full-precision rows of this split, all heads of the group, per wavefront:
+    // a wavefront's partial starts at the scan's maxima with nothing summed
+    float m_w[GH], l_w[GH];
+    f32x4 accx = {0.f, 0.f, 0.f, 0.f}, accy = {0.f, 0.f, 0.f, 0.f};  // element g: head g, dims 2 lane / 2 lane + 1
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+        m_w[g] = m_run[g];
+        l_w[g] = 0.f;
+    }
+    if (vb0 >= vb1)
+        __syncthreads();  // no round ran: the queries reach LDS here
+    {
+        const int64_t rbase = (int64_t)bkv * a.max_recent;
+        constexpr int RBG = 4;  // rows per trip, their loads issued together
+        for (int r = r0 + wave; r < r1; r += GN * RBG) {
+            uint32_t kw[RBG], vw[RBG];
+#pragma unroll
+            for (int u = 0; u < RBG; ++u) {
+                const int rr = r + u * GN < r1 ? r + u * GN : r;
+                kw[u] = *((const uint32_t *)((const __half *)a.recent_k + (rbase + rr) * PQ_HEAD_DIM) + lane);
+                vw[u] = *((const uint32_t *)((const __half *)a.recent_v + (rbase + rr) * PQ_HEAD_DIM) + lane);
+            }
+#pragma unroll
+            for (int u = 0; u < RBG; ++u) {
+                if (r + u * GN < r1) {  // wave-uniform
+                    const __half2 kh = *(const __half2 *)&kw[u], vh = *(const __half2 *)&vw[u];
+                    const float k0 = __low2float(kh), k1 = __high2float(kh), v0 = __low2float(vh), v1 = __high2float(vh);
+#pragma unroll
+                    for (int g = 0; g < GH; ++g) {
+                        const uint32_t qw = *(lds_u32 *)(lbase + G12_Q + g * 256 + lane * 4);
+                        const __half2 qh = *(const __half2 *)&qw;
+                        const float s = wave_sum(fmaf(__low2float(qh), k0, __high2float(qh) * k1)) * a.scale_log2e;
+                        const float m_new = fmaxf(m_w[g], s);
+                        const float al = __builtin_amdgcn_exp2f(m_w[g] - m_new);
+                        const float p = __builtin_amdgcn_exp2f(s - m_new);
+                        l_w[g] = fmaf(l_w[g], al, p);
+                        accx[g] = fmaf(accx[g], al, p * v0);
+                        accy[g] = fmaf(accy[g], al, p * v1);
+                        m_w[g] = m_new;
+                    }
+                }
+            }
+        }
+    }
+
+    // ---------------- merge inside the workgroup: the scan (maxima m_run, weight sums over all lanes, the
+    // output tile) and the wavefronts' recent-row partials (they overwrite the table: wait for the scan's end)
+    {
+        float l = sum_same_row_in_dpp_row(l_lane);
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (lane < GH)
+            *((lds_f32 *)(lbase + G12_LW) + wave * GH + lane) = l;
+    }
+    __syncthreads();
+    {
+        lds_f32 *part = (lds_f32 *)(lbase + G12_PART) + wave * GH * PQ_PART_STRIDE;
+#pragma unroll
+        for (int g = 0; g < GH; ++g) {
+            if (lane == 0) {
+                part[g * PQ_PART_STRIDE] = m_w[g];
+                part[g * PQ_PART_STRIDE + 1] = l_w[g];
+            }
+            part[g * PQ_PART_STRIDE + 4 + 2 * lane] = accx[g];
+            part[g * PQ_PART_STRIDE + 5 + 2 * lane] = accy[g];
+        }
+    }
+    __syncthreads();
+
+    // Wavefront g (< G) finishes head g, then one ticket per workgroup; the workgroup that draws the last
+    // ticket of the (sequence, KV head, sub-group) merges the splits (as in the 8-bit grouped kernel).
+    typedef __attribute__((address_space(3))) int lds_i32;
+    lds_i32 *last_flag = (lds_i32 *)(lbase + G12_FLAG);
+    const int g = wave;
+    if (g < G) {
+        const lds_f32 *parts = (const lds_f32 *)(lbase + G12_PART);
+        const lds_f32 *lw = (const lds_f32 *)(lbase + G12_LW);
+        const float m_scan = g == 0 ? m_run[0] : g == 1 ? m_run[1] : g == 2 ? m_run[2] : m_run[3];
+        float mx = m_scan;
+#pragma unroll
+        for (int w = 0; w < GN; ++w)
+            mx = fmaxf(mx, parts[(w * GH + g) * PQ_PART_STRIDE]);
+        const float f_scan = __builtin_amdgcn_exp2f(m_scan - mx);
+        float l_scan = 0.f;
+#pragma unroll
+        for (int w = 0; w < GN; ++w)
+            l_scan += lw[w * GH + g];
+        float o0 = o_lds[g * 128 + 2 * lane] * f_scan, o1 = o_lds[g * 128 + 2 * lane + 1] * f_scan, l = l_scan * f_scan;
+#pragma unroll
+        for (int w = 0; w < GN; ++w) {
+            const lds_f32 *pw = parts + (w * GH + g) * PQ_PART_STRIDE;
+            const float f = __builtin_amdgcn_exp2f(pw[0] - mx);
+            o0 = fmaf(pw[4 + 2 * lane], f, o0);
+            o1 = fmaf(pw[5 + 2 * lane], f, o1);
+            l = fmaf(pw[1], f, l);
+        }
+        if (S == 1) {
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            *(float2 *)(a.out + (int64_t)(bh0 + g) * PQ_HEAD_DIM + 2 * lane) = make_float2(o0 * inv, o1 * inv);
+        } else {
+            float *gpart = a.partials + ((int64_t)(bh0 + g) * S + split) * PQ_PART_STRIDE;
+            // device-scope stores, complete (performed where every XCD sees them) before the barrier
+            publish(gpart + 4 + 2 * lane, o0, o1);
+            if (lane == 0)
+                publish(gpart, mx, l);
+            publish_wait();
+        }
+    }
+    if (S == 1)
+        return;
+    __syncthreads();  // all G partials of this workgroup are published
+    if (wave == 0) {
+        unsigned int ticket = 0;
+        if (lane == 0)
+            ticket = __hip_atomic_fetch_add(a.tickets + bh0, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ticket = __builtin_amdgcn_readfirstlane(ticket);
+        if (lane == 0)
+            *last_flag = ticket == (unsigned int)(S - 1);
+    }
+    __syncthreads();
+    if (!*last_flag || g >= G)
+        return;
+    asm volatile("" ::: "memory");  // the loads below stay behind the ticket in the instruction stream
+    {
+        const float *ps = a.partials + (int64_t)(bh0 + g) * S * PQ_PART_STRIDE;
+        const float2 ml = lane < S ? fetch(ps + lane * PQ_PART_STRIDE) : make_float2(NEG_BIG, 0.f);
+        const float mx = wave_max(ml.x);
+        const float f_lane = __builtin_amdgcn_exp2f(ml.x - mx);
+        const float l = wave_sum(ml.y * f_lane);
+        float o0 = 0.f, o1 = 0.f;
+        // four splits at a time, their loads issued together (loads beyond S repeat the last split with factor 0)
+        for (int s0 = 0; s0 < S; s0 += 4) {
+            float2 t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                t[u] = fetch(ps + (s0 + u < S ? s0 + u : S - 1) * PQ_PART_STRIDE + 4 + 2 * lane);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float f = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(f_lane), (s0 + u) & 63));
+                f = s0 + u < S ? f : 0.f;
+                o0 = fmaf(t[u].x, f, o0);
+                o1 = fmaf(t[u].y, f, o1);
+            }
+        }
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        *(float2 *)(a.out + (int64_t)(bh0 + g) * PQ_HEAD_DIM + 2 * lane) = make_float2(o0 * inv, o1 * inv);
+    }
+    if (wave == 0 && lane == 0)
+        ticket_reset(a.tickets + bh0);
+}
+
+template <int WAVE_VB>
+void launch_grouped12(const pq_decode_args &a, int grid, bool once, hipStream_t s)
+{
+    if (once)
+        hipLaunchKernelGGL((pq12_decode_grouped_kernel<WAVE_VB, true>), dim3(grid), dim3(GN * 64), 0, s, a);
+    else
+        hipLaunchKernelGGL((pq12_decode_grouped_kernel<WAVE_VB, false>), dim3(grid), dim3(GN * 64), 0, s, a);
+}
+
+}  // namespace
+
+// 12-bit contexts whose query heads form groups of 2, 3 or 4 per KV head take the kernel above (fp16 only,
+// as all 12-bit contexts; a caller that asks for the two-pass path with n_splits < 0 keeps the per-head kernels).
+bool pq12_config_uses_grouped_kernel(const pq_attn_config *cfg)
+{
+    const int g = cfg->n_kv_heads > 0 ? cfg->n_q_heads / cfg->n_kv_heads : 0;
+    return pq_config_is_12bit(cfg) && cfg->n_splits >= 0 && pq_grouped_heads_per_workgroup(g) > 0;
+}
+
+hipError_t pq12_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
+{
+    const int grid = a.B * a.Hkv * (a.G / a.Gs) * a.S;
+    const bool once = a.G == a.Gs;
+    // blocks of 128 tokens per split at full capacity, per wavefront
+    const int64_t per_wave = (ctx->cap_padded / 128 + (int64_t)a.S * GN - 1) / ((int64_t)a.S * GN);
+    if (per_wave <= 1)
+        launch_grouped12<1>(a, grid, once, s);
+    else if (per_wave <= 2)
+        launch_grouped12<2>(a, grid, once, s);
+    else
+        launch_grouped12<4>(a, grid, once, s);
+    return hipGetLastError();
+}

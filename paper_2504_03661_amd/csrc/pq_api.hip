@@ -116,14 +116,17 @@ int choose_splits(const pq_attn_config *c, int n_cu)
 {
     // the grouped-query kernel runs one workgroup per (sequence, KV head, split)
     const int g = c->n_q_heads / c->n_kv_heads;
-    const int64_t heads =
-        (int64_t)c->batch * (pq_config_uses_grouped_kernel(c) ? c->n_q_heads / pq_grouped_heads_per_workgroup(g) : c->n_q_heads);
+    const bool grouped12 = pq12_config_uses_grouped_kernel(c);
+    const int64_t heads = (int64_t)c->batch * (pq_config_uses_grouped_kernel(c) || grouped12
+                                                   ? c->n_q_heads / pq_grouped_heads_per_workgroup(g)
+                                                   : c->n_q_heads);
     int64_t s = n_cu / heads;
     const int64_t blocks = padded_capacity(c) / 64;
     // 8-bit kernels: at least 4 blocks of 64 tokens per split — short contexts gain more from the parallelism
     // than they lose to idle wavefronts (32 heads x 1K tokens: 11.1 us with one split, 8.2 us with four; 2K: 11.3
-    // -> 8.8; 4K: 10.9 -> 9.6); 12-bit kernel: at least one 4096-token chunk
-    const int64_t per_split = pq_config_is_12bit(c) ? 64 : 4;
+    // -> 8.8; 4K: 10.9 -> 9.6); 12-bit kernel: at least one 4096-token chunk (grouped queries: 2048 tokens, one
+    // 128-token block per wavefront)
+    const int64_t per_split = grouped12 ? 32 : pq_config_is_12bit(c) ? 64 : 4;
     const int64_t max_by_work = blocks / per_split > 0 ? blocks / per_split : 1;
     if (s > max_by_work)
         s = max_by_work;
@@ -194,12 +197,13 @@ int launch_decode(const pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes,
     a.Hq = ctx->cfg.n_q_heads;
     a.Hkv = ctx->cfg.n_kv_heads;
     a.G = ctx->group;
-    a.Gs = ctx->k_skew == PQ_K_SKEW_QUAD ? pq_grouped_heads_per_workgroup(ctx->group) : 0;
+    a.Gs = ctx->k_skew == PQ_K_SKEW_QUAD || ctx->grouped12 ? pq_grouped_heads_per_workgroup(ctx->group) : 0;
     a.S = ctx->n_splits;
     a.max_context = ctx->cfg.max_context;
     a.max_recent = ctx->cfg.max_recent;
     a.head_stride = ctx->cap_padded * token_bytes(&ctx->cfg);
-    const hipError_t e = pq_config_is_12bit(&ctx->cfg)   ? pq12_launch_decode(ctx, a, s)
+    const hipError_t e = ctx->grouped12                  ? pq12_launch_decode_grouped(ctx, a, s)
+                         : pq_config_is_12bit(&ctx->cfg) ? pq12_launch_decode(ctx, a, s)
                          : ctx->k_skew == PQ_K_SKEW_QUAD ? pq_launch_decode_grouped(ctx, a, s)
                                                          : pq_launch_decode(ctx, a, s);
     return e == hipSuccess ? PQ_OK : PQ_ERR_HIP;
@@ -262,6 +266,7 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     ctx->cap_padded = padded_capacity(cfg);
     ctx->elem_bytes = cfg->dtype == PQ_F16 ? 2 : 4;
     ctx->k_skew = pq_config_uses_grouped_kernel(cfg) ? PQ_K_SKEW_QUAD : PQ_K_SKEW_LANE;
+    ctx->grouped12 = pq12_config_uses_grouped_kernel(cfg);
     ctx->n_splits = cfg->n_splits > 0 ? cfg->n_splits : choose_splits(cfg, prop.multiProcessorCount);
     // 12-bit contexts with few (sequence, query head) pairs decode in two passes (split by subspace group, see
     // pq12_decode.hip): chosen when there are 5 or more compute units per (sequence, head) pair, whatever the context
@@ -269,7 +274,7 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     // 64 us at 32K; two sequences at 32K 87 against 84 us, four 182 against 164 us), or on request
     bool two_pass = false;
     const int64_t cus_per_head = prop.multiProcessorCount / ((int64_t)cfg->batch * cfg->n_q_heads);
-    if (pq_config_is_12bit(cfg) && (cfg->n_splits < 0 || (cfg->n_splits == 0 && cus_per_head >= 5))) {
+    if (pq_config_is_12bit(cfg) && !ctx->grouped12 && (cfg->n_splits < 0 || (cfg->n_splits == 0 && cus_per_head >= 5))) {
         two_pass = true;
         const int64_t n_bh8 = (int64_t)cfg->batch * cfg->n_q_heads * 8;
         int64_t ts = cfg->n_splits < 0 ? -cfg->n_splits : prop.multiProcessorCount / n_bh8;
@@ -333,6 +338,13 @@ int pq_attn_destroy(pq_attn_ctx *ctx)
 int pq_attn_n_splits(const pq_attn_ctx *ctx) { return ctx ? ctx->n_splits : PQ_ERR_NULL; }
 
 int pq_attn_n_passes(const pq_attn_ctx *ctx) { return ctx ? (ctx->scores12 ? 2 : 1) : PQ_ERR_NULL; }
+
+int pq_attn_heads_per_workgroup(const pq_attn_ctx *ctx)
+{
+    if (ctx == nullptr)
+        return PQ_ERR_NULL;
+    return ctx->k_skew == PQ_K_SKEW_QUAD || ctx->grouped12 ? pq_grouped_heads_per_workgroup(ctx->group) : 1;
+}
 
 int pq_attn_set_codebooks(pq_attn_ctx *ctx, const void *k_codebook, const void *v_codebook, void *hip_stream)
 {

@@ -111,6 +111,7 @@ struct pq_attn_ctx {
     // 12-bit contexts that decode in two passes: partial scores [B*Hq][4][cap_padded]; n_splits then counts the
     // token ranges of the second pass
     float *scores12;
+    bool grouped12;       // 12-bit context that runs the grouped-query kernel
 };
 
 struct pq_decode_args {
@@ -166,6 +167,9 @@ hipError_t pq_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n_s
 // packing of the staged codes behind the current lengths, and the layout conversions of whole tensors
 bool pq_config_is_12bit(const pq_attn_config *cfg);
 hipError_t pq12_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
+// 12-bit contexts with 2, 3 or 4 query heads per workgroup reading one KV head (pq12_decode_grouped.hip)
+bool pq12_config_uses_grouped_kernel(const pq_attn_config *cfg);
+hipError_t pq12_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
 // a.x holds rows [B][Hkv][x_rows][d]; rows 0 .. a.n_new - 1 of every head are encoded and appended
 // (a.n_new <= ctx->stage_tokens)
 hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_args &a, int64_t x_rows, int32_t *ctx_len,

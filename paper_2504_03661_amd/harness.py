@@ -47,6 +47,7 @@ class PQSession:
         self.ctx = B.pq_attn_create(self.cfg)
         self.n_splits = B.pq_attn_n_splits(self.ctx)
         self.n_passes = B.pq_attn_n_passes(self.ctx)
+        self.heads_per_workgroup = B.pq_attn_heads_per_workgroup(self.ctx)
         self.codes_bytes = B.pq_attn_codes_bytes(self.cfg)
 
         self.q = _dev(data["q"], self.device)

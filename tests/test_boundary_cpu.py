@@ -91,6 +91,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.pq_attn_device_error(None, None) == -1
     assert lib.pq_attn_n_splits(None) == -1
     assert lib.pq_attn_n_passes(None) == -1
+    assert lib.pq_attn_heads_per_workgroup(None) == -1
     out = ctypes.c_void_p()
     # bad config is reported before any HIP call
     assert lib.pq_attn_create(ctypes.byref(good(batch=0).c_struct()), ctypes.byref(out)) == -2

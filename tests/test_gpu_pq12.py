@@ -171,6 +171,78 @@ def test_decode_random_shapes(seed):
     check(got, oracle_out(w, data), f"B={B_} Hkv={Hkv} G={G} lens={lens} rcap={rcap} splits={splits}")
 
 
+GROUPED_CASES = [
+    # name, B, Hq, Hkv, lengths, recent rows, n_splits, capacity beyond the longest sequence
+    ("g4_one_block_per_wave", 1, 4, 1, (1500,), 6, 1, 0),            # 1 split of < 2K tokens: the leanest instantiation
+    ("g4_ragged_splits_3", 2, 8, 2, (5000, 4097), 9, 3, 0),
+    ("g2_splits_2", 2, 4, 2, (9000, 130), 4, 2, 0),
+    ("g3", 1, 6, 2, (7000,), 5, 2, 0),
+    ("g8_two_workgroups_per_kv_head", 1, 8, 1, (6000,), 3, 2, 0),    # groups of 4 share the code stream through L2
+    ("g6_two_groups_of_3", 2, 6, 1, (3000, 2900), 0, 1, 0),
+    ("g4_edges", 6, 4, 1, (0, 1, 127, 128, 129, 0), 8, 2, 0),
+    ("g4_two_blocks_per_wave", 1, 4, 1, (4000,), 5, 1, 0),
+    ("g4_four_blocks_per_wave", 1, 4, 1, (8100,), 5, 1, 0),
+    ("g4_three_rounds", 1, 4, 1, (20000,), 5, 1, 0),                 # a split longer than the 8K tokens a round holds
+    ("g4_short_in_long_cache", 2, 4, 1, (300, 2000), 2, 0, 60000),   # splits chosen for the capacity, most of them empty
+    ("g4_auto_splits", 1, 8, 2, (33000,), 16, 0, 0),
+]
+
+
+@pytest.mark.parametrize("case", GROUPED_CASES, ids=[c[0] for c in GROUPED_CASES])
+def test_decode_grouped_queries(case):
+    """Grouped queries (2, 3 or 4 query heads per workgroup on one KV head's codes): every instantiation, ragged
+    lengths, several rounds and splits, empty sequences, window-only sequences; twice, so that the tickets are
+    seen back at zero."""
+    name, B_, Hq, Hkv, lens, rcap, splits, extra = case
+    w = workload(name, B_, Hq, Hkv, lens, rcap)
+    data = W.generate(w)
+    if name == "g4_edges":
+        data["recent_len"][:] = [0, 0, 3, 0, 7, 5]        # sequence 0: nothing at all; sequence 5: window only
+        fill = np.random.default_rng(7)
+        data["recent_k"][:] = fill.standard_normal(data["recent_k"].shape).astype(np.float16)
+        data["recent_v"][:] = fill.standard_normal(data["recent_v"].shape).astype(np.float16)
+        for b in range(B_):
+            data["recent_k"][b, :, data["recent_len"][b]:] = np.nan
+            data["recent_v"][b, :, data["recent_len"][b]:] = np.nan
+    ref = oracle_out(w, data)
+    cap = None if extra == 0 else max(lens) + extra
+    with PQSession(data, Hq, "f16", n_splits=splits, max_context=cap) as s:
+        g = Hq // Hkv
+        assert s.n_passes == 1 and s.heads_per_workgroup == (4 if g % 4 == 0 else 3 if g % 3 == 0 else 2)
+        for rep in range(2):
+            s.out.fill_(float("nan"))
+            out = s.decode(W.attention_scale(w))
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            check(got, ref, f"{name} call {rep} splits={s.n_splits}")
+    if name == "g4_edges":
+        assert (got[0] == 0).all()
+
+
+def test_group_sizes_without_a_grouped_kernel_keep_the_per_head_kernel():
+    """5 query heads per KV head: no group of 2, 3 or 4 divides it, every query head walks the codes by itself."""
+    w = workload("g5", 1, 5, 1, (5000,), 4)
+    data = W.generate(w)
+    with PQSession(data, 5, "f16", n_splits=2) as s:
+        assert s.heads_per_workgroup == 1
+        out = s.decode(W.attention_scale(w))
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), oracle_out(w, data), "g5")
+
+
+def test_grouped_queries_at_128k():
+    """32 query / 8 KV heads x 128K tokens with 12-bit codes: the grouped-query long-context shape, whole output."""
+    w = W.Workload("pq12_gqa_128k", 1, 32, 8, 128, 32, 131072, "f16", recent_cap=128, recent_fixed=128,
+                   seed=W.BASE_SEED + 14, n_centroids=4096)
+    data = W.generate(w)
+    ref = oracle_out(w, data)
+    with PQSession(data, 32, "f16") as s:
+        assert s.heads_per_workgroup == 4 and s.n_passes == 1
+        out = s.decode(W.attention_scale(w))
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), ref, f"12-bit 32q/8kv x 128K, {s.n_splits} splits")
+
+
 @pytest.mark.parametrize("n_old,n_new", [(0, 70), (100, 64), (130, 300), (255, 1)])
 def test_encode_append_bit_exact_then_decode(n_old, n_new):
     w = W.Workload("enc12", 2, 2, 2, 128, 32, n_old + n_new, "f16", n_new=n_new, seed=4000 + n_old, n_centroids=4096)
