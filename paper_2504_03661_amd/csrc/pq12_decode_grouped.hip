@@ -37,14 +37,19 @@ namespace {
 
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int GN = 16;                           // wavefronts per workgroup
+constexpr int GN = 8;                            // wavefronts per workgroup: 2 per SIMD, 256 registers each (a slice on
+                                                 // its way takes 64 of them, the round's scores, weights and code units
+                                                 // most of the rest; with 16 wavefronts of 128 registers the kernel
+                                                 // spilled, and a reload from scratch waits for every request in flight)
 constexpr int GH = 4;                            // rows of the 4x4x4 instruction = query heads per workgroup
 constexpr int G12_TAB = 0;                       // 128 KiB: codebook slice [4 subspaces][4096][4] fp16
 constexpr int G12_Q = 131072;                    // fp16 q [4][128] (heads beyond the group: zero rows)
 constexpr int G12_O = G12_Q + GH * 256;          // float [4][128]: the scan's un-normalised output rows
 constexpr int G12_WMAX = G12_O + GH * 512;       // float [16][4]: a round's maxima per wavefront and head
 constexpr int G12_LW = G12_WMAX + GN * GH * 4;   // float [16][4]: weight sums per wavefront and head
-constexpr int G12_FLAG = G12_LW + GN * GH * 4;   // int: "this workgroup drew the last ticket"
+constexpr int G12_RED = G12_LW + GN * GH * 4;    // float [8 wavefronts][4 rows of 16 lanes][16 values][4 subspaces]: a value
+                                                 // pass's sums per wavefront and lane row, folded into the tile a phase later
+constexpr int G12_FLAG = G12_RED + GN * 4 * 64 * 4;  // int: "this workgroup drew the last ticket"
 constexpr int G12_BYTES = G12_FLAG + 16;
 // wavefront partials of the recent rows float [16][4][PQ_PART_STRIDE] reuse the table once the scan is over
 constexpr int G12_PART = G12_TAB;
@@ -86,36 +91,57 @@ __device__ inline float max_same_row(float x)
     return x;
 }
 
-template <bool NT> __device__ inline uint32_t load_word(const uint32_t *p)
+// One 12-byte code unit: wave-uniform base (scalar registers) + this lane's 32-bit byte offset
+template <bool NT> __device__ inline void load_unit(uint32_t (&dst)[3], const uint8_t *uniform_base, uint32_t lane_off)
 {
-    return NT ? __builtin_nontemporal_load(p) : *p;
+    typedef __attribute__((address_space(1))) const char global_char;
+    typedef __attribute__((address_space(1))) const uint32_t global_u32;
+    uint64_t base = (uint64_t)uniform_base;
+    asm("" : "+s"(base));  // stays a scalar base: the compiler does not fold it into a per-lane 64-bit address
+    global_u32 *p = (global_u32 *)((global_char *)base + lane_off);
+#pragma unroll
+    for (int e = 0; e < 3; ++e)
+        dst[e] = NT ? __builtin_nontemporal_load(p + e) : p[e];
 }
 
-// 128 KiB from memory (L2 after the first workgroup of the XCD) to the table region: 8 x 16 bytes per thread
-__device__ inline void stage_slice(lds_u8 *lbase, const __half *slice, int tid)
+constexpr int SLICE_VEC = 131072 / (GN * 64 * 16);  // 16-byte pieces of a slice per thread
+
+// A 128 KiB codebook slice travels to the table region in two steps, a phase apart: requested into registers
+// (16 x 16 bytes per thread, from L2 after the first workgroup of the XCD) as soon as the previous slice has been
+// stored, and stored to LDS once every wavefront has left the gathers of the previous phase.
+// PART / PARTS: the pieces PART * SLICE_VEC / PARTS .. of the slice (the requests of a slice are spread over the
+// phase's scan, a few before each block: a wavefront that issues all 16 at once sits in front of the compute
+// unit's address pipeline for most of a microsecond before its first gather)
+template <int PART, int PARTS>
+__device__ inline void slice_request(u32x4 (&t)[SLICE_VEC], const __half *slice, int tid)
 {
-    // the slice address is wave-uniform: kept in scalar registers (base + 32-bit lane offset addressing), so that
-    // no per-lane 64-bit address per piece and slice is computed ahead of the loops and kept alive
-    const uint64_t p = (uint64_t)slice;
-    // (the builtin returns a signed int: widen through uint32_t, or a low word with bit 31 set would sign-extend
+    // the slice address is wave-uniform: kept in scalar registers, one 32-bit lane offset for all pieces (the
+    // builtin returns a signed int: widen through uint32_t, or a low word with bit 31 set would sign-extend
     // into the high word)
+    const uint64_t p = (uint64_t)slice;
     const uint32_t p_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(p >> 32));
     const uint32_t p_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)p);
     typedef __attribute__((address_space(1))) const char global_char;  // a global, not a generic, address
     typedef __attribute__((address_space(1))) const u32x4 global_u32x4;
     global_char *base = (global_char *)(((uint64_t)p_hi << 32) | (uint64_t)p_lo);
     const uint32_t off = (uint32_t)tid * 16u;
-    u32x4 t[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
-        t[k] = *(global_u32x4 *)(base + k * (GN * 64 * 16) + off);
+    for (int k = PART * (SLICE_VEC / PARTS); k < (PART + 1) * (SLICE_VEC / PARTS); ++k) {
+        uint64_t piece = (uint64_t)base + (uint64_t)(k * (GN * 64 * 16));
+        asm("" : "+s"(piece));  // a scalar base per piece + the common lane offset, not eight per-lane 64-bit addresses
+        t[k] = *(global_u32x4 *)((global_char *)piece + off);
+    }
+}
+
+__device__ inline void slice_store(lds_u8 *lbase, const u32x4 (&t)[SLICE_VEC], int tid)
+{
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
+    for (int k = 0; k < SLICE_VEC; ++k)
         *(lds_u32x4 *)(lbase + G12_TAB + (tid + k * (GN * 64)) * 16) = t[k];
 }
 
 // WAVE_VB: 128-token blocks per wavefront and round (8 score registers per lane each); a workgroup takes
-// 16 WAVE_VB blocks per round.  READ_ONCE: one workgroup per (sequence, KV head, split) reads the codes, so
+// 8 WAVE_VB blocks per round.  READ_ONCE: one workgroup per (sequence, KV head, split) reads the codes, so
 // they stream with the non-temporal hint; with more than 4 query heads per KV head several workgroups share
 // the stream through their XCD's L2 and load normally.
 template <int WAVE_VB, bool READ_ONCE>
@@ -178,8 +204,13 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
     const int quad = lane >> 2;  // the 4x4x4 block of this lane: a stream of tokens (token % 16)
     const int row = lane & 3;    // query head (as the holder of scores and weights); subspace of the group (value passes)
     // score passes: this lane gathers token quad + 16 row of a 64-token block
-    const uint32_t *k_units = (const uint32_t *)k_head + (quad + 16 * row) * 3;
-    const uint32_t *v_units = (const uint32_t *)v_head + lane * 3;
+    // K units are requested lane = token (one contiguous 768-byte piece per wavefront and load) and handed to the
+    // lane that gathers the token — lane (quad, row) takes token quad + 16 row — by a lane permutation when the
+    // pass starts; requested in gather order, the 4 lanes of a quad touch 4 separate lines and the loads issue
+    // several times slower
+    const uint32_t k_lane_off = (uint32_t)lane * 12u;
+    const int k_src_lane4 = (quad + 16 * row) * 4;
+    const uint32_t v_lane_off = (uint32_t)lane * 12u;
     const uint32_t v_tab = (uint32_t)(G12_TAB + row * (PQ12_CENTROIDS * 8));
 
     float m_run[GH];           // running maxima, the same in every wavefront of the workgroup
@@ -188,11 +219,61 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
     for (int g = 0; g < GH; ++g)
         m_run[g] = NEG_BIG;
 
+    // A value pass leaves, per wavefront and row of 16 lanes, the sums of its 64 outputs (4 heads x 4 subspaces x 4
+    // dims) in LDS; after the next barrier 4 wavefronts fold the 32 partial sums of each output into the tile.
+    lds_f32 *red = (lds_f32 *)(lbase + G12_RED);
+    auto fold = [&](const int gv) {
+        if (wave < 4) {  // output o = lane: value v = o / 4 (dim d = v / 4, head g = v % 4), subspace j = o % 4
+            float sum = 0.f;
+#pragma unroll
+            for (int p = 0; p < GN; ++p)  // partials (wavefront, lane row) 8 wave .. 8 wave + 7
+                sum += red[(wave * GN + p) * 64 + lane];
+            const int v = lane >> 2, j = lane & 3;
+            __hip_atomic_fetch_add((float *)(o_lds + (v & 3) * 128 + (4 * gv + j) * 4 + (v >> 2)), sum, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    };
+
+    // Everything a phase needs from memory is requested one phase ahead: the next slice right after this one has
+    // been stored, then the code units of the next phase (a K unit serves the two phases of its 8 subspaces).
+    u32x4 sl[SLICE_VEC];
+    uint32_t kn[2 * WAVE_VB][3], vn[WAVE_VB][3];
+    auto k_request = [&](const int sb_, const int g, const int last_vb) {
+#pragma unroll
+        for (int jj = 0; jj < WAVE_VB; ++jj) {
+            const int want = sb_ + wave + GN * jj;
+            const int vb = want < last_vb ? want : last_vb;  // beyond the wavefront's blocks: a valid block, not used
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                load_unit<READ_ONCE>(kn[2 * jj + h], k_head + (((int64_t)(2 * vb + h) * 4 + g) * 64) * 12, k_lane_off);
+        }
+    };
+    auto v_request = [&](const int sb_, const int gv, const int last_vb) {
+#pragma unroll
+        for (int jj = 0; jj < WAVE_VB; ++jj) {
+            const int want = sb_ + wave + GN * jj;
+            const int vb = want < last_vb ? want : last_vb;
+            load_unit<READ_ONCE>(vn[jj], v_head + (((int64_t)vb * 8 + gv) * 64) * 12, v_lane_off);
+        }
+    };
+    // part jj of the next slice's requests, in front of block jj of the scan (pinned there)
+    auto request_part = [&](const int jj, const __half *slice) {
+        if (jj == 0) slice_request<0, WAVE_VB>(sl, slice, tid);
+        if (jj == 1) slice_request<1 % WAVE_VB, WAVE_VB>(sl, slice, tid);
+        if (jj == 2) slice_request<2 % WAVE_VB, WAVE_VB>(sl, slice, tid);
+        if (jj == 3) slice_request<3 % WAVE_VB, WAVE_VB>(sl, slice, tid);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    if (vb0 < vb1) {
+        k_request(vb0, 0, vb1 - 1);
+        slice_request<0, 1>(sl, kcb, tid);
+    }
+
     for (int sb = vb0; sb < vb1; sb += ROUND_VB) {
-        // wavefront w owns blocks sb + w + 16 jj, jj < n_jj
+        // wavefront w owns blocks sb + w + 8 jj, jj < n_jj
         const int left = vb1 - sb - wave;
         const int n_jj = left <= 0 ? 0 : (left + GN - 1) / GN < WAVE_VB ? (left + GN - 1) / GN : WAVE_VB;
-        const int last_vb = vb1 - 1;  // loads beyond the wavefront's blocks re-read a valid block and are not used
+        const int last_vb = vb1 - 1;
         f32x4 score[2 * WAVE_VB];     // element r: token quad + 16 r of the 64-token half block, head `row`
         u32x4 wt[2 * WAVE_VB];        // the same tokens' weights as A operands: fp16 hi (x, y) and lo (z, w)
 #pragma unroll
@@ -204,28 +285,36 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
         for (int g = 0; g < 4; ++g) {
             uint32_t ku[2 * WAVE_VB][3];
 #pragma unroll
-            for (int jj = 0; jj < WAVE_VB; ++jj) {
-                const int want = sb + wave + GN * jj;
-                const int vb = want < last_vb ? want : last_vb;
+            for (int e = 0; e < 2 * WAVE_VB; ++e)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const uint32_t *u = k_units + (((int64_t)(2 * vb + h) * 4 + g) * 64) * 3;
-#pragma unroll
-                    for (int e = 0; e < 3; ++e)
-                        ku[2 * jj + h][e] = load_word<READ_ONCE>(u + e);
-                }
-            }
+                for (int x = 0; x < 3; ++x)
+                    ku[e][x] = (uint32_t)__builtin_amdgcn_ds_bpermute(k_src_lane4, (int)kn[e][x]);
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 __syncthreads();  // the table region is free (and, the first time, the queries are in LDS)
-                stage_slice(lbase, kcb + (int64_t)(8 * g + 4 * hf) * PQ12_CENTROIDS * 4, tid);
+                if (g == 0 && hf == 0 && sb > vb0)
+                    fold(7);  // the previous round's last value pass
+                slice_store(lbase, sl, tid);
                 __syncthreads();
+                // the next phase's requests go out behind the barrier: pushing 128 KiB of requests through the
+                // compute unit's address pipeline takes longer than the stores, and here it overlaps the gathers
+                // (code units before the slice: the next phase waits for the slice, the youngest request, and so
+                // for everything)
+                const __half *next_slice = kcb + (int64_t)(8 * g + 4) * PQ12_CENTROIDS * 4;
+                if (hf == 1) {
+                    if (g < 3)  // wave-uniform
+                        k_request(sb, g + 1, last_vb);
+                    else
+                        v_request(sb, 0, last_vb);
+                    next_slice = g < 3 ? kcb + (int64_t)(8 * g + 8) * PQ12_CENTROIDS * 4 : vcb;
+                }
                 f16x4 qb[4];  // B operands: head `row`'s query slice of the 4 resident subspaces
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     qb[j] = __builtin_bit_cast(f16x4, *(lds_u32x2 *)(lbase + G12_Q + row * 256 + (8 * g + 4 * hf + j) * 8));
 #pragma unroll
                 for (int jj = 0; jj < WAVE_VB; ++jj) {
+                    request_part(jj, next_slice);
                     if (jj >= n_jj)
                         continue;  // wave-uniform; `continue`, not `break`: the loop must unroll (registers are indexed by jj)
 #pragma unroll
@@ -303,23 +392,27 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
         for (int gv = 0; gv < 8; ++gv) {
             uint32_t vu[WAVE_VB][3];
 #pragma unroll
-            for (int jj = 0; jj < WAVE_VB; ++jj) {
-                const int want = sb + wave + GN * jj;
-                const int vb = want < last_vb ? want : last_vb;
-                const uint32_t *u = v_units + (((int64_t)vb * 8 + gv) * 64) * 3;
+            for (int e = 0; e < WAVE_VB; ++e)
 #pragma unroll
-                for (int e = 0; e < 3; ++e)
-                    vu[jj][e] = load_word<READ_ONCE>(u + e);
-            }
+                for (int x = 0; x < 3; ++x)
+                    vu[e][x] = vn[e][x];
             __syncthreads();  // the table region is free
-            stage_slice(lbase, vcb + (int64_t)(4 * gv) * PQ12_CENTROIDS * 4, tid);
+            if (gv > 0)
+                fold(gv - 1);
+            slice_store(lbase, sl, tid);
             __syncthreads();
+            if (gv < 7)  // wave-uniform
+                v_request(sb, gv + 1, last_vb);
+            else  // the next round's first units and slice (after the last round: requested, never used)
+                k_request(sb + ROUND_VB, 0, last_vb);
+            const __half *next_slice = gv < 7 ? vcb + (int64_t)(4 * gv + 4) * PQ12_CENTROIDS * 4 : kcb;
             f32x4 acc[4];  // acc[d][g]: head g, dim d of subspace 4 gv + row, this quad's tokens
 #pragma unroll
             for (int d = 0; d < 4; ++d)
                 acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int jj = 0; jj < WAVE_VB; ++jj) {
+                request_part(jj, next_slice);
                 if (jj >= n_jj)
                     continue;
                 uint32_t c[8];
@@ -348,19 +441,20 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
                     }
                 }
             }
-            // the 16 token streams: 4 per row of 16 lanes by DPP, the 4 rows by LDS adds
-            if (n_jj > 0) {  // wave-uniform
+            // the 16 token streams: the 4 of a row of 16 lanes by DPP, the rows and wavefronts through LDS (see fold)
 #pragma unroll
-                for (int d = 0; d < 4; ++d)
+            for (int d = 0; d < 4; ++d)
 #pragma unroll
-                    for (int g = 0; g < GH; ++g) {
-                        const float v = sum_same_row_in_dpp_row(acc[d][g]);
-                        if ((lane & 12) == 0)
-                            __hip_atomic_fetch_add((float *)(o_lds + g * 128 + (4 * gv + row) * 4 + d), v, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
-                    }
-            }
+                for (int g = 0; g < GH; ++g) {
+                    const float v = sum_same_row_in_dpp_row(acc[d][g]);
+                    if ((lane & 12) == 0)
+                        red[((wave * 4 + (lane >> 4)) * 16 + d * 4 + g) * 4 + row] = v;
+                }
         }
+    }
+    if (vb0 < vb1) {
+        __syncthreads();
+        fold(7);
     }
 
     // ---------------- recent full-precision rows of this split, all heads of the group, per wavefront:
