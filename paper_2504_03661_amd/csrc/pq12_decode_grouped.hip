@@ -208,9 +208,8 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
     // lane that gathers the token — lane (quad, row) takes token quad + 16 row — by a lane permutation when the
     // pass starts; requested in gather order, the 4 lanes of a quad touch 4 separate lines and the loads issue
     // several times slower
-    const uint32_t k_lane_off = (uint32_t)lane * 12u;
+    const uint32_t unit_lane_off = (uint32_t)lane * 12u;
     const int k_src_lane4 = (quad + 16 * row) * 4;
-    const uint32_t v_lane_off = (uint32_t)lane * 12u;
     const uint32_t v_tab = (uint32_t)(G12_TAB + row * (PQ12_CENTROIDS * 8));
 
     float m_run[GH];           // running maxima, the same in every wavefront of the workgroup
@@ -234,26 +233,37 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
         }
     };
 
-    // Everything a phase needs from memory is requested one phase ahead: the next slice right after this one has
-    // been stored, then the code units of the next phase (a K unit serves the two phases of its 8 subspaces).
+    // A round is 8 double phases: 4 groups of 8 key subspaces, then 4 pairs of value groups, each double phase two
+    // phases over one table slice (4 subspaces) each.  Everything comes from memory ahead of its use:
+    //   * the next slice is requested into registers during the scan of the current one, a quarter of its 16
+    //     pieces in front of each block (a wavefront that issues all of them at once sits in front of the
+    //     compute unit's address pipeline for most of a microsecond), and stored once everybody has left the
+    //     current scan;
+    //   * the code units of a double phase — 2 WAVE_VB of them either way: a K unit holds a token's 8 subspaces,
+    //     V units of two groups belong to one double phase — are requested during the FIRST phase of the double
+    //     phase before, and BEHIND that phase's slice requests: they come from HBM, loads return in order, and
+    //     in front of the slice requests they hold the slice (L2 hits) back for a memory round trip.
+    // Every request is unconditional and their number per phase is fixed, so the waits count exactly: the store of
+    // a slice waits for the slice and not for the units requested behind it.
     u32x4 sl[SLICE_VEC];
-    uint32_t kn[2 * WAVE_VB][3], vn[WAVE_VB][3];
-    auto k_request = [&](const int sb_, const int g, const int last_vb) {
+    uint32_t un[2 * WAVE_VB][3];
+    // double phase dp of the round that starts at block sb_: dp 0..3 = key unit group dp, 4..7 = value groups
+    // 2 (dp - 4), + 1; dp = 8 is the next round's dp 0
+    auto units_request = [&](int sb_, int dp, const int last_vb) {
+        if (dp == 8) {  // wave-uniform selects, no branch
+            sb_ += ROUND_VB;
+            dp = 0;
+        }
+        const bool is_k = dp < 4;
 #pragma unroll
         for (int jj = 0; jj < WAVE_VB; ++jj) {
             const int want = sb_ + wave + GN * jj;
             const int vb = want < last_vb ? want : last_vb;  // beyond the wavefront's blocks: a valid block, not used
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-                load_unit<READ_ONCE>(kn[2 * jj + h], k_head + (((int64_t)(2 * vb + h) * 4 + g) * 64) * 12, k_lane_off);
-        }
-    };
-    auto v_request = [&](const int sb_, const int gv, const int last_vb) {
-#pragma unroll
-        for (int jj = 0; jj < WAVE_VB; ++jj) {
-            const int want = sb_ + wave + GN * jj;
-            const int vb = want < last_vb ? want : last_vb;
-            load_unit<READ_ONCE>(vn[jj], v_head + (((int64_t)vb * 8 + gv) * 64) * 12, v_lane_off);
+            for (int x = 0; x < 2; ++x) {
+                const int64_t unit = is_k ? ((int64_t)(2 * vb + x) * 4 + dp) * 64 : ((int64_t)vb * 8 + 2 * (dp - 4) + x) * 64;
+                load_unit<READ_ONCE>(un[2 * jj + x], (is_k ? k_head : v_head) + unit * 12, unit_lane_off);
+            }
         }
     };
     // part jj of the next slice's requests, in front of block jj of the scan (pinned there)
@@ -265,7 +275,7 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
         __builtin_amdgcn_sched_barrier(0);
     };
     if (vb0 < vb1) {
-        k_request(vb0, 0, vb1 - 1);
+        units_request(vb0, 0, vb1 - 1);
         slice_request<0, 1>(sl, kcb, tid);
     }
 
@@ -283,12 +293,13 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
         // ---------------- score passes: 4 unit groups of 8 subspaces, two table slices of 4 subspaces each
 #pragma nounroll
         for (int g = 0; g < 4; ++g) {
+            // the units were requested lane = token; lane (quad, row) gathers token quad + 16 row
             uint32_t ku[2 * WAVE_VB][3];
 #pragma unroll
             for (int e = 0; e < 2 * WAVE_VB; ++e)
 #pragma unroll
                 for (int x = 0; x < 3; ++x)
-                    ku[e][x] = (uint32_t)__builtin_amdgcn_ds_bpermute(k_src_lane4, (int)kn[e][x]);
+                    ku[e][x] = (uint32_t)__builtin_amdgcn_ds_bpermute(k_src_lane4, (int)un[e][x]);
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 __syncthreads();  // the table region is free (and, the first time, the queries are in LDS)
@@ -296,18 +307,9 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
                     fold(7);  // the previous round's last value pass
                 slice_store(lbase, sl, tid);
                 __syncthreads();
-                // the next phase's requests go out behind the barrier: pushing 128 KiB of requests through the
-                // compute unit's address pipeline takes longer than the stores, and here it overlaps the gathers
-                // (code units before the slice: the next phase waits for the slice, the youngest request, and so
-                // for everything)
-                const __half *next_slice = kcb + (int64_t)(8 * g + 4) * PQ12_CENTROIDS * 4;
-                if (hf == 1) {
-                    if (g < 3)  // wave-uniform
-                        k_request(sb, g + 1, last_vb);
-                    else
-                        v_request(sb, 0, last_vb);
-                    next_slice = g < 3 ? kcb + (int64_t)(8 * g + 8) * PQ12_CENTROIDS * 4 : vcb;
-                }
+                const __half *next_slice = hf == 0   ? kcb + (int64_t)(8 * g + 4) * PQ12_CENTROIDS * 4
+                                           : g < 3 ? kcb + (int64_t)(8 * g + 8) * PQ12_CENTROIDS * 4
+                                                   : vcb;
                 f16x4 qb[4];  // B operands: head `row`'s query slice of the 4 resident subspaces
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -328,6 +330,10 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
                                 __builtin_amdgcn_mfma_f32_4x4x4f16(f16x4_of(cv.x, cv.y), qb[j], score[2 * jj + h], 0, 0, 0);
                         }
                     }
+                }
+                if (hf == 0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    units_request(sb, g + 1, last_vb);
                 }
             }
         }
@@ -364,8 +370,7 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
         const float m_own = row == 0 ? m_run[0] : row == 1 ? m_run[1] : row == 2 ? m_run[2] : m_run[3];
         const float a_own = row == 0 ? alpha[0] : row == 1 ? alpha[1] : row == 2 ? alpha[2] : alpha[3];
         l_lane *= a_own;
-        if (wave < 2 * GH) {  // the output tile of head wave / 2 follows the new maximum (nobody adds to it before the
-                              // next barrier)
+        {  // the output tile of head wave / 2 follows the new maximum (nobody adds to it before the next barrier)
             const int hh = wave >> 1;
             const float a_h = hh == 0 ? alpha[0] : hh == 1 ? alpha[1] : hh == 2 ? alpha[2] : alpha[3];
             o_lds[tid] *= a_h;
@@ -387,69 +392,74 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
             wt[e] = u32x4{bh.x, bh.y, bl.x, bl.y};
         }
 
-        // ---------------- value passes: 8 groups of 4 subspaces
+        // ---------------- value passes: 4 pairs of groups of 4 subspaces
 #pragma nounroll
-        for (int gv = 0; gv < 8; ++gv) {
-            uint32_t vu[WAVE_VB][3];
+        for (int u = 0; u < 4; ++u) {
+            uint32_t vu[2 * WAVE_VB][3];
 #pragma unroll
-            for (int e = 0; e < WAVE_VB; ++e)
+            for (int e = 0; e < 2 * WAVE_VB; ++e)
 #pragma unroll
                 for (int x = 0; x < 3; ++x)
-                    vu[e][x] = vn[e][x];
-            __syncthreads();  // the table region is free
-            if (gv > 0)
-                fold(gv - 1);
-            slice_store(lbase, sl, tid);
-            __syncthreads();
-            if (gv < 7)  // wave-uniform
-                v_request(sb, gv + 1, last_vb);
-            else  // the next round's first units and slice (after the last round: requested, never used)
-                k_request(sb + ROUND_VB, 0, last_vb);
-            const __half *next_slice = gv < 7 ? vcb + (int64_t)(4 * gv + 4) * PQ12_CENTROIDS * 4 : kcb;
-            f32x4 acc[4];  // acc[d][g]: head g, dim d of subspace 4 gv + row, this quad's tokens
+                    vu[e][x] = un[e][x];
 #pragma unroll
-            for (int d = 0; d < 4; ++d)
-                acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int x2 = 0; x2 < 2; ++x2) {
+                const int gv = 2 * u + x2;
+                __syncthreads();  // the table region is free
+                if (gv > 0)
+                    fold(gv - 1);
+                slice_store(lbase, sl, tid);
+                __syncthreads();
+                // after the last group: the next round's first slice (after the last round: requested, never used)
+                const __half *next_slice = gv < 7 ? vcb + (int64_t)(4 * gv + 4) * PQ12_CENTROIDS * 4 : kcb;
+                f32x4 acc[4];  // acc[d][g]: head g, dim d of subspace 4 gv + row, this quad's tokens
 #pragma unroll
-            for (int jj = 0; jj < WAVE_VB; ++jj) {
-                request_part(jj, next_slice);
-                if (jj >= n_jj)
-                    continue;
-                uint32_t c[8];
-                unpack8g(vu[jj][0], vu[jj][1], vu[jj][2], c);
+                for (int d = 0; d < 4; ++d)
+                    acc[d] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    u32x2 cv[4];  // tokens quad + 16 k of the half block, k = 0..3: dims (0, 1) and (2, 3)
+                for (int jj = 0; jj < WAVE_VB; ++jj) {
+                    request_part(jj, next_slice);
+                    if (jj >= n_jj)
+                        continue;
+                    uint32_t c[8];
+                    unpack8g(vu[2 * jj + x2][0], vu[2 * jj + x2][1], vu[2 * jj + x2][2], c);
 #pragma unroll
-                    for (int k = 0; k < 4; ++k)
-                        cv[k] = *(lds_u32x2 *)(lbase + v_tab + c[4 * h + k] * 8);
-                    f16x4 B[4];  // per dim: the 4 tokens' values
-                    B[0] = f16x4_of(__builtin_amdgcn_perm(cv[1].x, cv[0].x, 0x05040100u),
-                                    __builtin_amdgcn_perm(cv[3].x, cv[2].x, 0x05040100u));
-                    B[1] = f16x4_of(__builtin_amdgcn_perm(cv[1].x, cv[0].x, 0x07060302u),
-                                    __builtin_amdgcn_perm(cv[3].x, cv[2].x, 0x07060302u));
-                    B[2] = f16x4_of(__builtin_amdgcn_perm(cv[1].y, cv[0].y, 0x05040100u),
-                                    __builtin_amdgcn_perm(cv[3].y, cv[2].y, 0x05040100u));
-                    B[3] = f16x4_of(__builtin_amdgcn_perm(cv[1].y, cv[0].y, 0x07060302u),
-                                    __builtin_amdgcn_perm(cv[3].y, cv[2].y, 0x07060302u));
-                    const f16x4 Ahi = f16x4_of(wt[2 * jj + h].x, wt[2 * jj + h].y);
-                    const f16x4 Alo = f16x4_of(wt[2 * jj + h].z, wt[2 * jj + h].w);
+                    for (int h = 0; h < 2; ++h) {
+                        u32x2 cv[4];  // tokens quad + 16 k of the half block, k = 0..3: dims (0, 1) and (2, 3)
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        acc[d] = __builtin_amdgcn_mfma_f32_4x4x4f16(Ahi, B[d], acc[d], 0, 0, 0);
-                        acc[d] = __builtin_amdgcn_mfma_f32_4x4x4f16(Alo, B[d], acc[d], 0, 0, 0);
+                        for (int k = 0; k < 4; ++k)
+                            cv[k] = *(lds_u32x2 *)(lbase + v_tab + c[4 * h + k] * 8);
+                        f16x4 B[4];  // per dim: the 4 tokens' values
+                        B[0] = f16x4_of(__builtin_amdgcn_perm(cv[1].x, cv[0].x, 0x05040100u),
+                                        __builtin_amdgcn_perm(cv[3].x, cv[2].x, 0x05040100u));
+                        B[1] = f16x4_of(__builtin_amdgcn_perm(cv[1].x, cv[0].x, 0x07060302u),
+                                        __builtin_amdgcn_perm(cv[3].x, cv[2].x, 0x07060302u));
+                        B[2] = f16x4_of(__builtin_amdgcn_perm(cv[1].y, cv[0].y, 0x05040100u),
+                                        __builtin_amdgcn_perm(cv[3].y, cv[2].y, 0x05040100u));
+                        B[3] = f16x4_of(__builtin_amdgcn_perm(cv[1].y, cv[0].y, 0x07060302u),
+                                        __builtin_amdgcn_perm(cv[3].y, cv[2].y, 0x07060302u));
+                        const f16x4 Ahi = f16x4_of(wt[2 * jj + h].x, wt[2 * jj + h].y);
+                        const f16x4 Alo = f16x4_of(wt[2 * jj + h].z, wt[2 * jj + h].w);
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            acc[d] = __builtin_amdgcn_mfma_f32_4x4x4f16(Ahi, B[d], acc[d], 0, 0, 0);
+                            acc[d] = __builtin_amdgcn_mfma_f32_4x4x4f16(Alo, B[d], acc[d], 0, 0, 0);
+                        }
                     }
                 }
-            }
-            // the 16 token streams: the 4 of a row of 16 lanes by DPP, the rows and wavefronts through LDS (see fold)
-#pragma unroll
-            for (int d = 0; d < 4; ++d)
-#pragma unroll
-                for (int g = 0; g < GH; ++g) {
-                    const float v = sum_same_row_in_dpp_row(acc[d][g]);
-                    if ((lane & 12) == 0)
-                        red[((wave * 4 + (lane >> 4)) * 16 + d * 4 + g) * 4 + row] = v;
+                if (x2 == 0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    units_request(sb, 4 + u + 1, last_vb);
                 }
+                // the 16 token streams: the 4 of a row of 16 lanes by DPP, the rows and wavefronts through LDS (see fold)
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+#pragma unroll
+                    for (int g = 0; g < GH; ++g) {
+                        const float v = sum_same_row_in_dpp_row(acc[d][g]);
+                        if ((lane & 12) == 0)
+                            red[((wave * 4 + (lane >> 4)) * 16 + d * 4 + g) * 4 + row] = v;
+                    }
+            }
         }
     }
     if (vb0 < vb1) {
