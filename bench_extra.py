@@ -4,7 +4,8 @@
     python bench_extra.py prefill   # bulk encode of a 32K-token prompt, all heads, K and V
     python bench_extra.py async     # encode on a second stream while decode runs
     python bench_extra.py train     # offline codebook training (k-means), 64K samples x 32 heads
-    python bench_extra.py pq12      # 12-bit codes: decode at 1 x 32 heads x 32K and 8 x 32 x 32K, 64-token append
+    python bench_extra.py pq12 [shape]  # 12-bit codes: decode at 1 x 32 heads x 32K, 8 x 32 x 32K, 32 query / 8 KV heads x
+                                    # 128K and 8 x 32q/8kv x 32K (or the one shape named), 64-token append
     python bench_extra.py ctx       # decode time against context length (1K .. 128K), 32 heads and 32 query / 8 KV heads
     python bench_extra.py step1     # one decoding step of one sequence: one-token append + decode, 8-bit and 12-bit
 
@@ -184,18 +185,23 @@ def train():
                       "trained_codebook_finite": bool(np.isfinite(trained.astype(np.float32)).all())})
 
 
-def pq12():
+def pq12(only=None):
     import numpy as np
     import torch
     from paper_2504_03661_amd.harness import PQSession
     from synth import workloads as W
 
     res = {"mode": "pq12"}
-    for name, Bn in (("1x32x32k", 1), ("8x32x32k", 8)):
-        w = W.Workload("pq12_" + name, Bn, 32, 32, 128, 32, 32768, "f16", recent_cap=128, recent_fixed=128,
+    # one query head per KV head (the metric's layer shape, one and eight sequences), then grouped queries: 32 query /
+    # 8 KV heads at 128K tokens and eight sequences at 32K (the grouped-query kernel)
+    for name, Bn, hkv, n in (("1x32x32k", 1, 32, 32768), ("8x32x32k", 8, 32, 32768),
+                             ("1x32q8kv_128k", 1, 8, 131072), ("8x32q8kv_32k", 8, 8, 32768)):
+        if only is not None and name != only:
+            continue
+        w = W.Workload("pq12_" + name, Bn, 32, hkv, 128, 32, n, "f16", recent_cap=128, recent_fixed=128,
                        seed=W.BASE_SEED + 12, n_centroids=4096)
         data = W.generate(w)
-        one_copy = 2 * Bn * 32 * 32768 * 48
+        one_copy = 2 * Bn * hkv * n * 48
         copies = max(2, min(8, -(-(1 << 30) // one_copy)))
         with PQSession(data, 32, "f16", code_copies=copies) as s:
             dec = [s.prepared_decode(W.attention_scale(w), copy=c) for c in range(copies)]
@@ -206,13 +212,16 @@ def pq12():
                 it[0] += 1
             # warm-up past the clock ramp that follows an idle period (the first 10-20 ms run slower)
             ms = _span_ms(step, 400, warmup=max(100, int(30e-3 / (70e-6 * Bn))))
-            n_splits, n_passes = s.n_splits, s.n_passes
-        codes = Bn * 32 * 32768 * 96
-        total = codes + Bn * 32 * 128 * 128 * 2 * 2 + 32 * 2 * 32 * 4096 * 4 * 2 + Bn * 32 * 128 * 6
-        res[name] = {"decode_ms": round(ms, 4), "n_passes": n_passes, "n_splits": n_splits, "ctx_tokens_per_s": round(Bn * (32768 + 128) / (ms * 1e-3), 1),
+            n_splits, n_passes, hpw = s.n_splits, s.n_passes, s.heads_per_workgroup
+        codes = Bn * hkv * n * 96
+        total = codes + Bn * hkv * 128 * 128 * 2 * 2 + hkv * 2 * 32 * 4096 * 4 * 2 + Bn * 32 * 128 * 6
+        res[name] = {"decode_ms": round(ms, 4), "n_passes": n_passes, "n_splits": n_splits, "heads_per_workgroup": hpw,
+                     "ctx_tokens_per_s": round(Bn * (n + 128) / (ms * 1e-3), 1),
                      "roofline": {"bound": "hbm", "achieved": round(total / (ms * 1e-3) / 1e9, 1), "peak": 8000.0,
                                   "unit": "GB/s", "frac": round(total / (ms * 1e-3) / 1e9 / 8000.0, 4),
                                   "algorithmic_bytes": total, "code_bytes": codes}}
+    if only is not None:
+        return res
     # append of 64 tokens per head, 16 sequences x 32 heads (the shape of the 8-bit encode workload)
     w = W.Workload("pq12_append", 16, 32, 32, 128, 32, 4096, "f16", n_new=64, seed=W.BASE_SEED + 13, n_centroids=4096)
     data = W.generate(w)
@@ -327,4 +336,4 @@ if __name__ == "__main__":
     if mode not in modes:
         print(__doc__)
         sys.exit(2)
-    print(json.dumps(modes[mode]()))
+    print(json.dumps(modes[mode](*sys.argv[2:3]) if mode == "pq12" else modes[mode]()))

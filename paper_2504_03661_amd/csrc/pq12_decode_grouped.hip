@@ -629,12 +629,23 @@ void launch_grouped12(const pq_decode_args &a, int grid, bool once, hipStream_t 
 
 }  // namespace
 
-// 12-bit contexts whose query heads form groups of 2, 3 or 4 per KV head take the kernel above (fp16 only,
-// as all 12-bit contexts; a caller that asks for the two-pass path with n_splits < 0 keeps the per-head kernels).
-bool pq12_config_uses_grouped_kernel(const pq_attn_config *cfg)
+// 12-bit contexts whose query heads form groups of 2, 3 or 4 per KV head take the kernel above (fp16 only, as all
+// 12-bit contexts) — unless the work is small.  A workgroup of this kernel streams all 16 codebook slices (2 MiB)
+// through its LDS per round, about 45 us whatever the length, while the per-head kernels' two-pass path (chosen
+// when there are 5 or more compute units per (sequence, query head)) keeps one slice per workgroup: measured with
+// 32 query / 8 KV heads, one sequence: 8K tokens 46 against 20 us, 32K 46 against 37 us, 64K 47 against 59 us,
+// 128K 60 against 97 us; 16 query / 8 KV heads x 64K 48 against 40 us.  So the grouped kernel serves the shapes
+// that would not decode in two passes (4 sequences x 32K: 59 against 121 us; 64 query / 8 KV heads x 32K: 48 against
+// 71 us) and those with 1.5 M (query head, token) pairs of capacity or more.  A caller that asks for the two-pass
+// path (n_splits < 0) keeps the per-head kernels.
+bool pq12_config_uses_grouped_kernel(const pq_attn_config *cfg, int n_cu)
 {
     const int g = cfg->n_kv_heads > 0 ? cfg->n_q_heads / cfg->n_kv_heads : 0;
-    return pq_config_is_12bit(cfg) && cfg->n_splits >= 0 && pq_grouped_heads_per_workgroup(g) > 0;
+    if (!pq_config_is_12bit(cfg) || cfg->n_splits < 0 || pq_grouped_heads_per_workgroup(g) == 0)
+        return false;
+    const int64_t heads = (int64_t)cfg->batch * cfg->n_q_heads;
+    const bool two_pass_otherwise = cfg->n_splits == 0 && n_cu / heads >= 5;
+    return !two_pass_otherwise || heads * cfg->max_context >= 1536 * 1024;
 }
 
 hipError_t pq12_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)

@@ -116,7 +116,7 @@ int choose_splits(const pq_attn_config *c, int n_cu)
 {
     // the grouped-query kernel runs one workgroup per (sequence, KV head, split)
     const int g = c->n_q_heads / c->n_kv_heads;
-    const bool grouped12 = pq12_config_uses_grouped_kernel(c);
+    const bool grouped12 = pq12_config_uses_grouped_kernel(c, n_cu);
     const int64_t heads = (int64_t)c->batch * (pq_config_uses_grouped_kernel(c) || grouped12
                                                    ? c->n_q_heads / pq_grouped_heads_per_workgroup(g)
                                                    : c->n_q_heads);
@@ -266,7 +266,7 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     ctx->cap_padded = padded_capacity(cfg);
     ctx->elem_bytes = cfg->dtype == PQ_F16 ? 2 : 4;
     ctx->k_skew = pq_config_uses_grouped_kernel(cfg) ? PQ_K_SKEW_QUAD : PQ_K_SKEW_LANE;
-    ctx->grouped12 = pq12_config_uses_grouped_kernel(cfg);
+    ctx->grouped12 = pq12_config_uses_grouped_kernel(cfg, prop.multiProcessorCount);
     ctx->n_splits = cfg->n_splits > 0 ? cfg->n_splits : choose_splits(cfg, prop.multiProcessorCount);
     // 12-bit contexts with few (sequence, query head) pairs decode in two passes (split by subspace group, see
     // pq12_decode.hip): chosen when there are 5 or more compute units per (sequence, head) pair, whatever the context

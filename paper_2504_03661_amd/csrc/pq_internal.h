@@ -168,7 +168,7 @@ hipError_t pq_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n_s
 bool pq_config_is_12bit(const pq_attn_config *cfg);
 hipError_t pq12_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
 // 12-bit contexts with 2, 3 or 4 query heads per workgroup reading one KV head (pq12_decode_grouped.hip)
-bool pq12_config_uses_grouped_kernel(const pq_attn_config *cfg);
+bool pq12_config_uses_grouped_kernel(const pq_attn_config *cfg, int n_cu);
 hipError_t pq12_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
 // a.x holds rows [B][Hkv][x_rows][d]; rows 0 .. a.n_new - 1 of every head are encoded and appended
 // (a.n_new <= ctx->stage_tokens)

@@ -19,6 +19,7 @@ CASES = [
     ("two_bit_grouped", 1, 8, 2, 32, 12000, 9, 256, 3),
     ("pq12_fused", 1, 2, 2, 32, 9000, 8, 4096, 2),
     ("pq12_two_pass", 1, 2, 2, 32, 9000, 8, 4096, -2),
+    ("pq12_grouped", 1, 8, 2, 32, 9000, 8, 4096, 2),
 ]
 
 

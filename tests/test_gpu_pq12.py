@@ -183,8 +183,8 @@ GROUPED_CASES = [
     ("g4_two_blocks_per_wave", 1, 4, 1, (4000,), 5, 1, 0),
     ("g4_four_blocks_per_wave", 1, 4, 1, (8100,), 5, 1, 0),
     ("g4_three_rounds", 1, 4, 1, (20000,), 5, 1, 0),                 # a split longer than the 8K tokens a round holds
-    ("g4_short_in_long_cache", 2, 4, 1, (300, 2000), 2, 0, 60000),   # splits chosen for the capacity, most of them empty
-    ("g4_auto_splits", 1, 8, 2, (33000,), 16, 0, 0),
+    ("g4_short_in_long_cache", 2, 4, 1, (300, 2000), 2, 8, 60000),   # 8 splits of a 62K-token capacity, most of them empty
+    ("g4_auto_splits", 8, 8, 2, (3000, 2500, 1, 4096, 3100, 0, 2047, 2049), 16, 0, 0),  # 64 (sequence, head) pairs
 ]
 
 
@@ -217,6 +217,18 @@ def test_decode_grouped_queries(case):
             check(got, ref, f"{name} call {rep} splits={s.n_splits}")
     if name == "g4_edges":
         assert (got[0] == 0).all()
+
+
+def test_small_grouped_query_shapes_keep_the_two_pass_per_head_path():
+    """Few (sequence, head) pairs and a short capacity: a workgroup of the grouped kernel would stream all 16
+    codebook slices for a handful of tokens; the per-head two-pass path keeps one slice per workgroup."""
+    w = workload("g4_small", 1, 8, 2, (9000,), 4)
+    data = W.generate(w)
+    with PQSession(data, 8, "f16") as s:
+        assert s.heads_per_workgroup == 1 and s.n_passes == 2
+        out = s.decode(W.attention_scale(w))
+        torch.cuda.synchronize()
+        check(out.cpu().numpy(), oracle_out(w, data), "g4_small")
 
 
 def test_group_sizes_without_a_grouped_kernel_keep_the_per_head_kernel():
