@@ -1,7 +1,7 @@
 """The split exchange of the decode kernels is ordered at the instruction level (no fences): its argument rests on
 the compiler emitting the agent-scope atomic stores and loads of the partials as write-through / cache-bypassing
-instructions (`sc1`) and the ticket as a device atomic.  This test cross-compiles the two 8-bit decode kernels to
-gfx950 assembly (no GPU needed) and checks exactly that, so a toolchain that changed the mapping would be noticed."""
+instructions (`sc1`) and the ticket as a device atomic.  This test cross-compiles the decode kernels that merge
+splits in the launch (8-bit per-head and grouped, 12-bit fused, two-pass and grouped) to gfx950 assembly (no GPU needed) and checks exactly that, so a toolchain that changed the mapping would be noticed."""
 import os
 import re
 import subprocess
@@ -31,7 +31,9 @@ def kernels(text):
     return out
 
 
-@pytest.mark.parametrize("source,needle", [("pq_decode.hip", "pq_decode_kernel"), ("pq_decode_grouped.hip", "pq_decode_grouped_kernel")])
+@pytest.mark.parametrize("source,needle", [("pq_decode.hip", "pq_decode_kernel"), ("pq_decode_grouped.hip", "pq_decode_grouped_kernel"),
+                                           ("pq12_decode.hip", "pq12_decode_kernel"), ("pq12_decode.hip", "pq12_values_kernel"),
+                                           ("pq12_decode_grouped.hip", "pq12_decode_grouped_kernel")])
 def test_partials_travel_with_sc1_and_the_ticket_is_a_device_atomic(source, needle, tmp_path):
     ks = {k: v for k, v in kernels(assembly(source, tmp_path)).items() if needle in k}
     assert ks, "no decode kernel found in the assembly"
