@@ -178,7 +178,8 @@ int pq_attn_decode_noalloc(const pq_attn_config *cfg /* host */, const void *q, 
  * two are given different length arrays and the decode does not attend over the positions being
  * written (asynchronous quantization, Section III-B); the caller publishes the new lengths afterwards.
  *
- * With 12-bit codes the call stages the codes in context-owned memory sized at pq_attn_create; a long
+ * With 12-bit codes the call stages the codes in context-owned memory sized at pq_attn_create (except for
+ * 8 or fewer new tokens per KV head over all sequences, which go straight into the code tensors); a long
  * append runs as several chunks through it (more launches, no allocation, no synchronisation).  Two appends
  * on one context must not overlap.
  *

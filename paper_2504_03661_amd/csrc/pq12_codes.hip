@@ -105,9 +105,16 @@ __global__ __launch_bounds__(E12_WAVES * 64) void pq12_encode_kernel(const __hal
 // of the 4096 computed values per token.  Pass 2: one bit per block of 16 centroids that holds a value
 // within tau of it (256 bits per token; the sign of the value once best + tau is folded into the C operand).
 // One or two marked blocks: their 16 or 32 centroids are evaluated in
-// the defining fp64 arithmetic, ascending, lowest index first.  More, or a codebook whose |c|^2 / 2 leaves the
-// fp16 range: the sub-chunk runs the full fp64 scan.  About 1.1 vector instructions per (sub-vector, centroid)
+// the defining fp64 arithmetic, ascending, lowest index first; more: the lane walks all of its marked blocks the
+// same way.  A codebook whose |c|^2 / 2 leaves the fp16 range, or no marked block at all (non-finite values): the
+// sub-chunk runs the full fp64 scan.  About 1.1 vector instructions per (sub-vector, centroid)
 // instead of 11.
+// SPLIT (a head has at most 64 NQ tokens in the call — a decoding step of a batch): with one sub-chunk per
+// workgroup seven of its eight wavefronts would idle while one walks all 4096 centroids alone, each step waiting
+// out the latency of two dependent matrix instructions (17 tokens per head: 454 us).  Here all eight take the SAME
+// tokens and an eighth of the centroids each — 128 of the 1024 groups in pass 1, one of the eight 32-block mask
+// words in pass 2 — and exchange the per-token minimum and the mask words through LDS; the words are the ones the
+// unsplit walk computes, so the refinement (wavefront 0) and the codes are the same.
 // ---------------------------------------------------------------------------------------------------
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4e __attribute__((ext_vector_type(4)));
@@ -115,7 +122,7 @@ typedef uint32_t u32x2e __attribute__((ext_vector_type(2)));
 
 constexpr int F12_WAVES = 8;  // wavefronts that share one set of A rows
 
-template <int NQ>
+template <int NQ, bool SPLIT>
 __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void pq12_encode_fast_kernel(const __half *x0, const __half *x1,
                                                                          const __half *cb0, const __half *cb1,
                                                                          uint16_t *out0, uint16_t *out1, int B, int Hkv,
@@ -124,6 +131,7 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
 #pragma clang fp contract(off)
     __shared__ __attribute__((aligned(16))) unsigned char arow[PQ12_CENTROIDS * 16];
     __shared__ float red[2 * F12_WAVES + 1];
+    __shared__ uint32_t xchg[SPLIT ? F12_WAVES * NQ * 64 : 1];  // SPLIT: per wavefront, sub-chunk and token
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -132,7 +140,8 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     const int i = blockIdx.y;      // subspace
     const int n_tok = B * n_new;   // tokens of one KV head over all sequences
     const int hkv = blockIdx.x / groups_per_head;
-    const int chunk = (blockIdx.x - hkv * groups_per_head) * F12_WAVES + wave;  // of 64 NQ tokens
+    // of 64 NQ tokens; SPLIT: the workgroup's eight wavefronts share one
+    const int chunk = SPLIT ? blockIdx.x - hkv * groups_per_head : (blockIdx.x - hkv * groups_per_head) * F12_WAVES + wave;
     const __half *x = which ? x1 : x0;
     const __half *cb = (which ? cb1 : cb0) + ((int64_t)hkv * PQ12_M + i) * PQ12_CENTROIDS * 4;
     uint16_t *out = which ? out1 : out0;
@@ -225,14 +234,28 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
     for (int q = 0; q < NQ; ++q)
         best[q] = 0x7f800000;
+    constexpr int M_PER_WAVE = SPLIT ? PQ12_CENTROIDS / 4 / F12_WAVES : PQ12_CENTROIDS / 4;
+    const int m0 = SPLIT ? wave * M_PER_WAVE : 0;
 #pragma unroll 2
-    for (int m = 0; m < PQ12_CENTROIDS / 4; ++m) {
+    for (int m = m0; m < m0 + M_PER_WAVE; ++m) {
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const f32x4e d = values(m, q);
             best[q] = min(min(best[q], __float_as_int(d[0])), __float_as_int(d[1]));
             best[q] = min(min(best[q], __float_as_int(d[2])), __float_as_int(d[3]));
         }
+    }
+    if (SPLIT) {  // the minimum over the eight wavefronts' shares
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+            xchg[(wave * NQ + q) * 64 + lane] = (uint32_t)best[q];
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+            for (int w = 0; w < F12_WAVES; ++w)
+                best[q] = min(best[q], (int)xchg[(w * NQ + q) * 64 + lane]);
+        __syncthreads();  // the words are written again below
     }
     // ---- pass 2: one bit per block of 16 centroids within tau of the minimum.  With off - (best + tau) in the C
     // operand a computed value is negative exactly where it is a candidate: the OR of a block's 16 results carries
@@ -247,6 +270,8 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
     }
 #pragma unroll
     for (int wd = 0; wd < 8; ++wd) {
+        if (SPLIT && wd != wave)  // wave-uniform: this wavefront's word only
+            continue;
         uint32_t bits[NQ];
 #pragma unroll
         for (int q = 0; q < NQ; ++q)
@@ -272,6 +297,21 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
 #pragma unroll
         for (int q = 0; q < NQ; ++q)
             cand[q][wd] = bits[q];
+        if (SPLIT) {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+                xchg[(wave * NQ + q) * 64 + lane] = bits[q];
+        }
+    }
+    if (SPLIT) {
+        __syncthreads();
+        if (wave != 0)
+            return;  // wavefront 0 refines and stores for the workgroup
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+            for (int wd = 0; wd < 8; ++wd)
+                cand[q][wd] = xchg[(wd * NQ + q) * 64 + lane];
     }
 
     // ---- refine / full scan, store
@@ -321,7 +361,34 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
             for (int k = 0; k < 16; ++k)
                 exact(16 * last + k, code, bd);
         }
-        const bool unsure = live[q] && (bad[q] || cnt < 1 || cnt > 2);
+        // more than two marked blocks (a cluster of near-ties, a token far outside the codebook's range): this
+        // lane walks all of its marked blocks, ascending — the nearest centroid and every tie lie in them
+        const bool many = live[q] && !bad[q] && cnt > 2;
+        if (__builtin_amdgcn_ballot_w64(many) != 0) {  // wave-uniform
+            int code_m = 0;
+            double bd_m = __builtin_huge_val();
+#pragma unroll
+            for (int wd = 0; wd < 8; ++wd) {
+                uint32_t wbits = many ? cand[q][wd] : 0u;
+                while (__builtin_amdgcn_ballot_w64(wbits != 0u) != 0) {  // block 32 wd + k sits in bit 31 - k
+                    const int k32 = wbits ? __builtin_clz(wbits) : 0;
+                    double bd_t = bd_m;
+                    int code_t = code_m;
+                    for (int k = 0; k < 16; ++k)
+                        exact(16 * (32 * wd + k32) + k, code_t, bd_t);
+                    if (wbits != 0u) {
+                        bd_m = bd_t;
+                        code_m = code_t;
+                    }
+                    wbits &= ~(0x80000000u >> k32);
+                }
+            }
+            if (many) {
+                code = code_m;
+                bd = bd_m;
+            }
+        }
+        const bool unsure = live[q] && (bad[q] || cnt < 1);
         if (__builtin_amdgcn_ballot_w64(unsure) != 0) {  // wave-uniform: the defining scan for this sub-chunk
             code = 0;
             bd = __builtin_huge_val();
@@ -339,15 +406,22 @@ __global__ __launch_bounds__(F12_WAVES * 64) __attribute__((amdgpu_waves_per_eu(
 // of a workgroup hold 4 centroids each in registers, evaluate the defining fp64 distances of the token at hand
 // (ascending index per thread, strict "<") and the workgroup takes the lexicographic minimum of (distance,
 // index): the lowest index among equal distances, as in the scan.  The floor is reading the codebooks once
-// (64 MiB for K and V of 32 heads).
+// (64 MiB for K and V of 32 heads).  The code goes straight into the device layout — no staging, no packing
+// kernels: a 12-bit field of a unit that other workgroups (K: the token's other subspaces) or nobody else in
+// this call (V) writes, so it is cleared and set with two device-scope atomics per 32-bit word it touches;
+// fields are disjoint, so the order of the workgroups does not matter.  Tokens beyond the capacity are not
+// written (the length update flags them).
 // ---------------------------------------------------------------------------------------------------
-constexpr int FEW12_TOKENS = 16;
+constexpr int FEW12_TOKENS = 16;  // capacity of the kernel
+constexpr int FEW12_USED = 8;     // what the launcher gives it
 constexpr int FEW12_WAVES = 16;
 
 __global__ __launch_bounds__(FEW12_WAVES * 64) void pq12_encode_few_kernel(const __half *x0, const __half *x1,
                                                                           const __half *cb0, const __half *cb1,
-                                                                          uint16_t *out0, uint16_t *out1, int B, int Hkv,
-                                                                          int n_new, int64_t x_head_stride)
+                                                                          uint8_t *codes0, uint8_t *codes1,
+                                                                          const int32_t *ctx_len, int B, int Hkv, int n_new,
+                                                                          int64_t x_head_stride, int max_context,
+                                                                          int64_t head_stride)
 {
 #pragma clang fp contract(off)
     static_assert(FEW12_TOKENS <= 64, "lane u fetches token u");
@@ -363,7 +437,7 @@ __global__ __launch_bounds__(FEW12_WAVES * 64) void pq12_encode_few_kernel(const
     const int n_tok = B * n_new;  // <= FEW12_TOKENS
     const __half *x = which ? x1 : x0;
     const __half *cb = (which ? cb1 : cb0) + ((int64_t)hkv * PQ12_M + i) * PQ12_CENTROIDS * 4;
-    uint16_t *out = which ? out1 : out0;
+    uint8_t *codes = which ? codes1 : codes0;
 
     double c[4][4];
 #pragma unroll
@@ -421,7 +495,24 @@ __global__ __launch_bounds__(FEW12_WAVES * 64) void pq12_encode_few_kernel(const
         if (lane == 0) {
             const int b = wave / n_new;
             const int t = wave - b * n_new;
-            out[(((int64_t)b * Hkv + hkv) * n_new + t) * PQ12_M + i] = (uint16_t)cc;
+            int p0 = ctx_len[b];
+            p0 = p0 < 0 ? 0 : p0;
+            const int64_t pos = (int64_t)p0 + t;
+            if (pos < max_context) {
+                int slot;
+                const int64_t unit = which ? pq12_v_unit(pos, i, &slot) : pq12_k_unit(pos, i, &slot);
+                unsigned int *w = (unsigned int *)(codes + ((int64_t)b * Hkv + hkv) * head_stride + unit);  // 3 words
+                const int bit = 12 * slot;  // the field: bits bit .. bit + 11 of the 96
+                const uint64_t field = (uint64_t)((uint32_t)cc & 0xfffu) << (bit & 31);
+                const uint64_t mask = (uint64_t)0xfffu << (bit & 31);
+                unsigned int *w0 = w + (bit >> 5);
+                __hip_atomic_fetch_and(w0, ~(unsigned int)mask, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_or(w0, (unsigned int)field, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((mask >> 32) != 0) {  // the field runs into the next word
+                    __hip_atomic_fetch_and(w0 + 1, ~(unsigned int)(mask >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_fetch_or(w0 + 1, (unsigned int)(field >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
         }
     }
 }
@@ -554,21 +645,40 @@ hipError_t pq12_launch_encode_append(const pq_attn_ctx *ctx, const pq_encode_arg
                                      unsigned int *dev_err, hipStream_t s)
 {
     const int64_t n_tok = (int64_t)a.B * a.n_new;  // tokens of a head over all sequences
-    if (n_tok <= FEW12_TOKENS) {
+    // measured, 32 heads, one new token per sequence: 1 sequence 17 us, 8 sequences 62 us with the kernel below
+    // (6.6 us per token: fp64 arithmetic); 17 .. 64 sequences 74 .. 82 us with the split filter kernel
+    if (n_tok <= FEW12_USED) {
+        // a decoding step: encode and write the device layouts in one kernel, then the lengths
         hipLaunchKernelGGL(pq12_encode_few_kernel, dim3((unsigned)a.Hkv, PQ12_M, 2), dim3(FEW12_WAVES * 64), 0, s,
                            (const __half *)a.x[0], (const __half *)a.x[1], (const __half *)a.codebook[0],
-                           (const __half *)a.codebook[1], ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, x_rows);
+                           (const __half *)a.codebook[1], a.codes[0], a.codes[1], a.ctx_len, a.B, a.Hkv, a.n_new, x_rows,
+                           a.max_context, ctx->cap_padded * PQ12_TOKEN_BYTES);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return e;
+        return pq_launch_bump_len(ctx_len, a.B, a.n_new, a.max_context, dev_err, s);
+    } else if (n_tok <= 128) {
+        // a decoding step of a batch: one sub-chunk per head, its centroids split over the workgroup's wavefronts
+        const dim3 grid((unsigned)a.Hkv, PQ12_M, 2);
+        if (n_tok > 64)
+            hipLaunchKernelGGL((pq12_encode_fast_kernel<2, true>), grid, dim3(F12_WAVES * 64), 0, s, (const __half *)a.x[0],
+                               (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
+                               ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, 1, x_rows);
+        else
+            hipLaunchKernelGGL((pq12_encode_fast_kernel<1, true>), grid, dim3(F12_WAVES * 64), 0, s, (const __half *)a.x[0],
+                               (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
+                               ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, 1, x_rows);
     } else if (n_tok < ((int64_t)1 << 30)) {
         // matrix-core filter: 8 wavefronts per workgroup, each takes 64 NQ tokens of the head
         const int nq = n_tok > 64 * F12_WAVES ? 2 : 1;
         const int groups_per_head = (int)((n_tok + 64 * nq * F12_WAVES - 1) / (64 * nq * F12_WAVES));
         const dim3 grid((unsigned)(a.Hkv * groups_per_head), PQ12_M, 2);
         if (nq == 2)
-            hipLaunchKernelGGL(pq12_encode_fast_kernel<2>, grid, dim3(F12_WAVES * 64), 0, s, (const __half *)a.x[0],
+            hipLaunchKernelGGL((pq12_encode_fast_kernel<2, false>), grid, dim3(F12_WAVES * 64), 0, s, (const __half *)a.x[0],
                                (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
                                ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, x_rows);
         else
-            hipLaunchKernelGGL(pq12_encode_fast_kernel<1>, grid, dim3(F12_WAVES * 64), 0, s, (const __half *)a.x[0],
+            hipLaunchKernelGGL((pq12_encode_fast_kernel<1, false>), grid, dim3(F12_WAVES * 64), 0, s, (const __half *)a.x[0],
                                (const __half *)a.x[1], (const __half *)a.codebook[0], (const __half *)a.codebook[1],
                                ctx->stage[0], ctx->stage[1], a.B, a.Hkv, a.n_new, groups_per_head, x_rows);
     } else {
@@ -649,7 +759,7 @@ hipError_t pq12_launch_kmeans(const pq_attn_ctx *ctx, const void *samples, int n
             const __half *x = (const __half *)samples + (int64_t)c0 * PQ_HEAD_DIM;
             // assignment = the encode's matrix-core filter (one sequence, grid.z = 1: only the first pointers are used)
             const int groups_per_head = (nc + 128 * F12_WAVES - 1) / (128 * F12_WAVES);
-            hipLaunchKernelGGL(pq12_encode_fast_kernel<2>, dim3((unsigned)(Hkv * groups_per_head), PQ12_M, 1),
+            hipLaunchKernelGGL((pq12_encode_fast_kernel<2, false>), dim3((unsigned)(Hkv * groups_per_head), PQ12_M, 1),
                                dim3(F12_WAVES * 64), 0, s, x, x, (const __half *)codebook, (const __half *)codebook, codes,
                                codes, 1, Hkv, nc, groups_per_head, (int64_t)n_samples);
             const int64_t total = (int64_t)Hkv * nc * PQ12_M;

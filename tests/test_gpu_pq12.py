@@ -326,7 +326,8 @@ def test_long_append_runs_in_chunks_through_the_fixed_staging():
     np.testing.assert_array_equal(got_v[:, :, :n_old], data["v_codes"][:, :, :n_old])
 
 
-@pytest.mark.parametrize("B_,n_new", [(1, 3), (2, 100), (3, 333), (1, 512), (1, 513), (2, 512), (1, 1025), (16, 1), (2, 8), (1, 17)])
+@pytest.mark.parametrize("B_,n_new", [(1, 3), (2, 100), (3, 333), (1, 512), (1, 513), (2, 512), (1, 1025), (16, 1), (2, 8), (1, 17),
+                                        (5, 1), (1, 64), (1, 65), (2, 64), (8, 5), (1, 129), (40, 1), (128, 1)])
 def test_encode_filter_paths_are_bit_exact(B_, n_new):
     """The 12-bit encode is a matrix-core filter with the fp64 expression as the decision: every way through it gives
     the oracle's codes — ties inside one block of 16 centroids, across two blocks, across many (full scan), a
