@@ -113,9 +113,10 @@ __global__ __launch_bounds__(ENC_WAVES * 64) void pq_encode_kernel(const pq_enco
 //   refine  one or two candidate groups (nearly always): the true minimiser is among their centroids — the
 //           distances of those 4 (8 if some token of the wavefront has two groups) are evaluated in the
 //           defining fp64 arithmetic (see the top of this file),
-//           ascending, and the smallest, lowest index first, is the code.  Otherwise (three or more groups
-//           within tau: duplicated centroids, near-ties; subnormal or out-of-range inputs) the 64-token chunk
-//           runs the full fp64 scan.
+//           ascending, and the smallest, lowest index first, is the code.  Three or more groups within tau
+//           (duplicated centroids, near-ties): the lane walks all of its marked groups the same way.  A
+//           codebook or token outside the range the bound covers (no marked group, non-finite values): the
+//           64-token chunk runs the full fp64 scan.
 // Either way the code is decided by the fp64 expression, so it is bit-exact by construction; the filter only
 // has to be SAFE: every centroid outside the candidate groups must have a strictly larger true distance.  With
 // |computed - true| <= e for every centroid and c^ the minimiser of the computed values, a centroid c outside

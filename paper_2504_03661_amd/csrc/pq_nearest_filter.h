@@ -185,7 +185,34 @@ __device__ inline void pq_filter_codes(const unsigned char *arow, const double *
             for (int k = 0; k < 4; ++k)  // ... then the last one (the same group again where there is only one)
                 take(4 * last[q] + k);
         }
-        const bool unsure = live[q] && (bad[q] || cnt[q] < 1 || cnt[q] > 2);
+        // more than two candidate groups (a cluster of near-ties, a token far outside the codebook's range): the
+        // lane walks all of its marked groups, ascending — the nearest centroid and every tie lie in them
+        const bool many = live[q] && !bad[q] && cnt[q] > 2;
+        if (__builtin_amdgcn_ballot_w64(many) != 0) {  // wave-uniform
+            const int code_12 = code;
+            const double bd_12 = bd;
+            code = 0;
+            bd = __builtin_huge_val();
+            uint64_t left = many ? ((uint64_t)cand_lo[q] << 32) | cand_hi[q] : 0;  // group g sits in bit 63 - g
+            while (__builtin_amdgcn_ballot_w64(left != 0) != 0) {
+                const int g = left ? __builtin_clzll(left) : 0;
+                const int code_before = code;
+                const double bd_before = bd;
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    take(4 * g + k);
+                if (left == 0) {  // this lane had nothing left: keep what it had
+                    code = code_before;
+                    bd = bd_before;
+                }
+                left &= ~(0x8000000000000000ull >> g);
+            }
+            if (!many) {
+                code = code_12;
+                bd = bd_12;
+            }
+        }
+        const bool unsure = live[q] && (bad[q] || cnt[q] < 1);
         if (__builtin_amdgcn_ballot_w64(unsure) != 0) {  // wave-uniform: the defining scan for this sub-chunk
             code = 0;
             bd = __builtin_huge_val();
