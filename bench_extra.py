@@ -8,6 +8,8 @@
                                     # 128K and 8 x 32q/8kv x 32K (or the one shape named), 64-token append
     python bench_extra.py ctx       # decode time against context length (1K .. 128K), 32 heads and 32 query / 8 KV heads
     python bench_extra.py step1     # one decoding step of one sequence: one-token append + decode, 8-bit and 12-bit
+    python bench_extra.py batch     # many short sequences: 8 x 32K .. 256 x 1K tokens (32 heads, 128 recent rows), decode and
+                                    # the one-token-per-sequence append
 
 prefill: the nearest-centroid encode at prompt shape (Section III-A, "Online Prefill with KV Cache
 Quantization"): vectors per second against the vector-ALU roofline (256 CUs x 64 lanes x 2.4 GHz = 39.3 T
@@ -31,6 +33,9 @@ ctx: decode kernel time against context length, 1K .. 128K tokens (and short seq
 
 step1: one decoding step of a single sequence, 32 heads at 32K tokens: append of one token per head, then decode, for
 8-bit codes (M = 64) and 12-bit codes (M = 32, 4096 centroids).
+batch: the same number of cached tokens as 8 sequences x 32K, cut into more and shorter sequences (a serving batch):
+decode time against the bytes the method must move (codes, the recent rows — a large share at 1K tokens — codebooks,
+q / out), and the append of one new token per sequence.
 Each mode prints one JSON line.
 """
 import json
@@ -330,8 +335,45 @@ def step1():
     return res
 
 
+def batch():
+    import torch
+    from paper_2504_03661_amd.harness import PQSession
+    from synth import workloads as W
+
+    res = {"mode": "batched_short_sequences", "heads": 32, "recent_rows": 128}
+    for Bn, n in ((8, 32768), (32, 8192), (64, 4096), (128, 2048), (256, 1024)):
+        w = W.Workload("batch", Bn, 32, 32, 128, 64, n, "f16", recent_cap=128, recent_fixed=128, n_new=1,
+                       seed=W.BASE_SEED + 31)
+        data = W.generate(w)
+        with PQSession(data, 32, "f16", code_copies=2) as s:
+            dec = [s.prepared_decode(W.attention_scale(w), copy=c) for c in range(2)]
+            nk, nv = torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda()
+            base = s.ctx_len.clone()
+            app = [s.prepared_append(nk, nv, copy=c) for c in range(2)]
+            it = [0]
+
+            def step():
+                dec[it[0] % 2]()
+                it[0] += 1
+
+            def reset_only():
+                s.ctx_len.copy_(base)
+
+            def append_step():
+                s.ctx_len.copy_(base)
+                app[it[0] % 2]()
+                it[0] += 1
+            ms = _span_ms(step, 100, warmup=100)
+            t_app = (_span_ms(append_step, 100, warmup=50) - _span_ms(reset_only, 100, warmup=50)) * 1e3
+        total = Bn * 32 * (n - 1) * 128 + Bn * 32 * 128 * 128 * 2 * 2 + 32 * 2 * 64 * 256 * 2 * 2 + Bn * 32 * 128 * 6
+        res[f"{Bn}x{n // 1024}k"] = {"decode_us": round(ms * 1e3, 1), "append_one_token_per_sequence_us": round(t_app, 1),
+                                     "algorithmic_bytes": total,
+                                     "frac_of_hbm_peak": round(total / (ms * 1e-3) / 1e9 / 8000.0, 4)}
+    return res
+
+
 if __name__ == "__main__":
-    modes = {"prefill": prefill, "async": async_encode, "train": train, "pq12": pq12, "ctx": ctx, "step1": step1}
+    modes = {"batch": batch, "prefill": prefill, "async": async_encode, "train": train, "pq12": pq12, "ctx": ctx, "step1": step1}
     mode = sys.argv[1] if len(sys.argv) > 1 else ""
     if mode not in modes:
         print(__doc__)

@@ -31,6 +31,8 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "pq_internal.h"
 #include "pq_device_utils.h"
 
@@ -367,38 +369,55 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         const int64_t rbase = ((int64_t)b * a.Hkv + hkv) * a.max_recent;
         // RB rows per trip: their loads go out together, so a wavefront with many rows (one split per head,
         // a few hundred recent rows) pays one memory round trip per RB rows instead of one per row.  Rows
-        // beyond the range re-read the trip's first row and are skipped.
-        constexpr int RB = 4;
-        for (int r = r0 + wave; r < r1; r += NW * RB) {
-            float kv[RB][DS], vv[RB][DS];
+        // beyond the range re-read the trip's first row and are skipped.  16 per trip when the wavefront has more
+        // than 4 rows — with short sequences in a large batch the window is a large share of the work and its round
+        // trips are not hidden by anything (256 x 32 heads x 1K tokens, 128 rows: 434 -> 363 us; 128 x 2K: 274 -> 253
+        // us) — and 4 otherwise (the 14 dead loads of a 16-row trip cost 0.4 us on 1 x 32 heads x 32K, where a
+        // wavefront has 2 rows).
+        // (the rows wait in their registers as loaded — fp16 pairs — and are converted when used)
+        constexpr int RW = DS * (int)sizeof(T) / 4;  // 32-bit words of a lane's DS elements
+        auto rows = [&](auto rb_tag) {
+            constexpr int RB = decltype(rb_tag)::value;
+            for (int r = r0 + wave; r < r1; r += NW * RB) {
+                uint32_t kw[RB][RW], vw[RB][RW];
 #pragma unroll
-            for (int u = 0; u < RB; ++u) {
-                const int rr = r + u * NW < r1 ? r + u * NW : r;
+                for (int u = 0; u < RB; ++u) {
+                    const int rr = r + u * NW < r1 ? r + u * NW : r;
+                    const uint32_t *kp = (const uint32_t *)((const T *)a.recent_k + (rbase + rr) * PQ_HEAD_DIM + sub * DS);
+                    const uint32_t *vp = (const uint32_t *)((const T *)a.recent_v + (rbase + rr) * PQ_HEAD_DIM + sub * DS);
 #pragma unroll
-                for (int j = 0; j < DS; ++j) {
-                    kv[u][j] = owner ? elem<T>::ld(a.recent_k, (rbase + rr) * PQ_HEAD_DIM + sub * DS + j) : 0.f;
-                    vv[u][j] = owner ? elem<T>::ld(a.recent_v, (rbase + rr) * PQ_HEAD_DIM + sub * DS + j) : 0.f;
+                    for (int x = 0; x < RW; ++x) {
+                        kw[u][x] = owner ? kp[x] : 0u;
+                        vw[u][x] = owner ? vp[x] : 0u;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < RB; ++u) {
+                    if (r + u * NW < r1) {  // wave-uniform
+                        float dot = 0.f;
+#pragma unroll
+                        for (int j = 0; j < DS; ++j)
+                            dot = fmaf(qs[j], elem<T>::ld(&kw[u][0], j), dot);
+                        const float s = wave_sum(dot);
+                        const float m_new = fmaxf(m_run, s);
+                        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                        const float p = __builtin_amdgcn_exp2f(s - m_new);
+                        l_lane = fmaf(l_lane, alpha, lane == 0 ? p : 0.f);
+#pragma unroll
+                        for (int j = 0; j < DS; ++j)
+                            acc[j] = fmaf(acc[j], alpha, p * elem<T>::ld(&vw[u][0], j));
+                        m_run = m_new;
+                    }
                 }
             }
-#pragma unroll
-            for (int u = 0; u < RB; ++u) {
-                if (r + u * NW < r1) {  // wave-uniform
-                    float dot = 0.f;
-#pragma unroll
-                    for (int j = 0; j < DS; ++j)
-                        dot = fmaf(qs[j], kv[u][j], dot);
-                    const float s = wave_sum(dot);
-                    const float m_new = fmaxf(m_run, s);
-                    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-                    const float p = __builtin_amdgcn_exp2f(s - m_new);
-                    l_lane = fmaf(l_lane, alpha, lane == 0 ? p : 0.f);
-#pragma unroll
-                    for (int j = 0; j < DS; ++j)
-                        acc[j] = fmaf(acc[j], alpha, p * vv[u][j]);
-                    m_run = m_new;
-                }
-            }
-        }
+        };
+        // the larger trip: 16 rows for fp16 in the 8-wavefront kernel (32 registers), 8 in the 16-wavefront kernels
+        // (128 registers per lane); fp32 contexts keep 4
+        constexpr int RB_BIG = sizeof(T) == 2 ? (NW == 8 ? 16 : 8) : 4;
+        if (RB_BIG > 4 && r1 - r0 > 4 * NW)  // workgroup-uniform
+            rows(std::integral_constant<int, RB_BIG>{});
+        else
+            rows(std::integral_constant<int, 4>{});
     }
 
     // ---------------- merge the wavefronts of this workgroup
