@@ -9,8 +9,8 @@
 // the matrix cores.  A subspace of 4 dims is exactly the inner dimension of v_mfma_f32_4x4x4_16B_f16, so a
 // gathered centroid (8 bytes) is an operand as it comes out of LDS:
 //
-//   score passes  8 groups of 4 subspaces: the group's slice of the KEY codebook [4][4096][4] fp16 (128 KiB)
-//                 is copied to LDS.  Lane (quad s, row i) gathers the centroid of token s + 16 i of a
+//   score passes  8 slices of 4 subspaces: a slice of the KEY codebook [4][4096][4] fp16 (128 KiB) is
+//                 copied to LDS.  Lane (quad s, row i) gathers the centroid of token s + 16 i of a
 //                 64-token block: A = the quad's 4 tokens x 4 dims, B = the 4 query heads' slice of this
 //                 subspace (lane j: head j), so D[token][head] lands with lane j holding head j's scores of
 //                 the quad's 4 tokens — which is the A operand layout of the value passes, no transposition.
@@ -22,11 +22,12 @@
 //                 subspace j of the tokens s + 16 k of a 128-token block (its 12-byte unit), re-packs 4
 //                 tokens x 4 dims into one B operand per dim (8 x v_perm) and accumulates
 //                 D[head][lane's subspace, dim] += weights[head][4 tokens] x B — hi and lo — for all heads.
-//                 The 16 token streams (quads) are summed at the end of each group into an fp32 output
-//                 tile in LDS.
+//                 The 16 token streams (quads) are summed at the end of each slice — DPP inside rows of 16
+//                 lanes, a small LDS buffer across rows and wavefronts — into an fp32 output tile in LDS.
 // The K and V code layouts are those of the per-head kernel (pq_internal.h); a K unit holds 8 subspaces and
 // serves two consecutive score passes from registers, so each code byte still leaves HBM once.  Recent rows,
-// split partials, ticket and merge follow the 8-bit grouped kernel.
+// split partials, ticket and merge follow the 8-bit grouped kernel.  What binds the kernel is not HBM but the
+// 16 slices (2 MiB) every workgroup pulls out of L2 per round of tokens (see the round loop for the schedule).
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -45,13 +46,13 @@ constexpr int GH = 4;                            // rows of the 4x4x4 instructio
 constexpr int G12_TAB = 0;                       // 128 KiB: codebook slice [4 subspaces][4096][4] fp16
 constexpr int G12_Q = 131072;                    // fp16 q [4][128] (heads beyond the group: zero rows)
 constexpr int G12_O = G12_Q + GH * 256;          // float [4][128]: the scan's un-normalised output rows
-constexpr int G12_WMAX = G12_O + GH * 512;       // float [16][4]: a round's maxima per wavefront and head
-constexpr int G12_LW = G12_WMAX + GN * GH * 4;   // float [16][4]: weight sums per wavefront and head
+constexpr int G12_WMAX = G12_O + GH * 512;       // float [8][4]: a round's maxima per wavefront and head
+constexpr int G12_LW = G12_WMAX + GN * GH * 4;   // float [8][4]: weight sums per wavefront and head
 constexpr int G12_RED = G12_LW + GN * GH * 4;    // float [8 wavefronts][4 rows of 16 lanes][16 values][4 subspaces]: a value
                                                  // pass's sums per wavefront and lane row, folded into the tile a phase later
 constexpr int G12_FLAG = G12_RED + GN * 4 * 64 * 4;  // int: "this workgroup drew the last ticket"
 constexpr int G12_BYTES = G12_FLAG + 16;
-// wavefront partials of the recent rows float [16][4][PQ_PART_STRIDE] reuse the table once the scan is over
+// wavefront partials of the recent rows float [8][4][PQ_PART_STRIDE] reuse the table once the scan is over
 constexpr int G12_PART = G12_TAB;
 static_assert(GN * GH * PQ_PART_STRIDE * 4 <= 131072, "partials fit in the table region");
 static_assert(G12_BYTES <= 160 * 1024, "LDS budget of a gfx950 compute unit");
