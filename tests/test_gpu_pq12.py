@@ -375,6 +375,43 @@ def test_encode_filter_paths_are_bit_exact(B_, n_new):
     assert (exp_k[..., 0] == 0).all() and (exp_k[..., 1] == 7).all() and (exp_k[..., 2] == 3).all()
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_append_at_random_positions_keeps_the_cache_and_flags_overflow(seed):
+    """Seeded random decoding steps and short appends — 1 .. 40 new tokens for 1 .. 8 sequences at different lengths,
+    some beyond the capacity, 12-bit and 8-bit codes (every append path: codes written straight into the device
+    layouts, the split filter kernel, staging + packing): the tokens already cached keep their codes, the new ones get
+    the oracle's, what does not fit is dropped, the lengths saturate and the overflow flag says so."""
+    rng = np.random.default_rng(4000 + seed)
+    cent = int(rng.choice([4096, 4096, 256]))
+    M = 32 if cent == 4096 else int(rng.choice([64, 32]))
+    B_ = int(rng.integers(1, 9))
+    Hkv = int(rng.integers(1, 4))
+    n_new = int(rng.choice([1, 1, 1, 2, 3, 5, 9, 16, 17, 40]))
+    cap = int(rng.choice([300, 400, 1000]))
+    lens = tuple(int(x) for x in rng.integers(0, cap, size=B_))
+    w = W.Workload(f"fa{seed}", B_, Hkv, Hkv, 128, M, cap, "f16", n_new=n_new, seed=4000 + seed, ctx_lens=lens,
+                   n_centroids=cent)
+    data = W.generate(w)
+    exp_k = O.encode(data["new_k"], data["k_codebook"])
+    exp_v = O.encode(data["new_v"], data["v_codebook"])
+    with PQSession(data, Hkv, "f16", max_context=cap) as s:
+        s.ctx_len.copy_(torch.tensor(lens, dtype=torch.int32))
+        s.append(torch.from_numpy(data["new_k"]).cuda(), torch.from_numpy(data["new_v"]).cuda())
+        torch.cuda.synchronize()
+        got_k, got_v = s.unpack(PQ_CODES_K, cap), s.unpack(PQ_CODES_V, cap)
+        new_len = s.ctx_len.cpu().numpy()
+        flags = s.device_error()
+    for b in range(B_):
+        L = lens[b]
+        fit = max(0, min(n_new, cap - L))
+        for got, old, new in ((got_k, data["k_codes"], exp_k), (got_v, data["v_codes"], exp_v)):
+            np.testing.assert_array_equal(got[b, :, :L], old[b, :, :L])
+            np.testing.assert_array_equal(got[b, :, L:L + fit], new[b, :, :fit])
+            np.testing.assert_array_equal(got[b, :, L + fit:], old[b, :, L + fit:cap])
+        assert new_len[b] == min(L + n_new, cap)
+    assert bool(flags & 1) == any(L + n_new > cap for L in lens)
+
+
 def test_llama2_7b_layer_shape_at_32k():
     """The metric's shape with 12-bit codes: 1 x 32 heads x 32K tokens, 128 recent rows."""
     w = W.Workload("pq12_llama2_7b_32k", 1, 32, 32, 128, 32, 32768, "f16", recent_cap=128, recent_fixed=128,
