@@ -91,8 +91,9 @@ int pq_attn_n_passes(const pq_attn_ctx *ctx);
 
 /* Query heads one decode workgroup serves: 1 for the kernels that build per-query
  * tables, 2..4 for the grouped-query kernels (one pass over a KV head's codes for
- * that many query heads; chosen when Hq / Hkv is a multiple of 2, 3 or 4 and the
- * context is fp16 — for 4096-centroid contexts only where the shape is large
+ * that many query heads: a KV head's Hq / Hkv >= 2 query heads are cut into
+ * ceil(Hq / Hkv / 4) sub-groups of 2..4 heads, sizes as equal as possible, and the
+ * largest is returned; chosen when the context is fp16 — for 4096-centroid contexts only where the shape is large
  * enough to pay for it: fewer than 5 compute units per (sequence, query head), or
  * a capacity of 1.5 M (query head, token) pairs, and n_splits >= 0). */
 int pq_attn_heads_per_workgroup(const pq_attn_ctx *ctx);

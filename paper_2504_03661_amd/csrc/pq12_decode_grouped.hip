@@ -155,7 +155,6 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int G = a.Gs;  // query heads of this workgroup (2..4)
 
     const uint32_t grid = gridDim.x;
     uint32_t logical = blockIdx.x;
@@ -166,13 +165,18 @@ __global__ __launch_bounds__(GN * 64) void pq12_decode_grouped_kernel(const pq_d
     // KV head, then the same KV head of the other sequences (they stage the same codebook slices from L2)
     const int unit = (int)(logical / (uint32_t)S);
     const int split = (int)(logical - (uint32_t)unit * (uint32_t)S);
-    const int n_sub = a.G / G;
+    const int n_sub = a.n_sub;
     const int hb = (int)((uint32_t)unit / (uint32_t)n_sub);  // hkv * B + b
     const int sub_group = unit - hb * n_sub;
     const int hkv = (int)((uint32_t)hb / (uint32_t)a.B);
     const int b = hb - hkv * a.B;
     const int bkv = b * a.Hkv + hkv;
-    const int bh0 = b * a.Hq + hkv * a.G + sub_group * G;  // first query head of this workgroup
+    // the KV head's a.G query heads in n_sub sub-groups whose sizes differ by at most one: this workgroup's heads
+    // are g_first .. g_first + G - 1, G = 2..4
+    const int g_base = a.G / n_sub, g_rem = a.G - g_base * n_sub;
+    const int G = g_base + (sub_group < g_rem ? 1 : 0);
+    const int g_first = sub_group * g_base + (sub_group < g_rem ? sub_group : g_rem);
+    const int bh0 = b * a.Hq + hkv * a.G + g_first;  // first query head of this workgroup
 
     int N = a.ctx_len[b];
     int R = (a.recent_k != nullptr && a.recent_len != nullptr) ? a.recent_len[b] : 0;
@@ -630,7 +634,7 @@ void launch_grouped12(const pq_decode_args &a, int grid, bool once, hipStream_t 
 
 }  // namespace
 
-// 12-bit contexts whose query heads form groups of 2, 3 or 4 per KV head take the kernel above (fp16 only, as all
+// 12-bit contexts with 2 or more query heads per KV head take the kernel above (fp16 only, as all
 // 12-bit contexts) — unless the work is small.  A workgroup of this kernel streams all 16 codebook slices (2 MiB)
 // through its LDS per round, about 45 us whatever the length, while the per-head kernels' two-pass path (chosen
 // when there are 5 or more compute units per (sequence, query head)) keeps one slice per workgroup: measured with
@@ -651,8 +655,8 @@ bool pq12_config_uses_grouped_kernel(const pq_attn_config *cfg, int n_cu)
 
 hipError_t pq12_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
 {
-    const int grid = a.B * a.Hkv * (a.G / a.Gs) * a.S;
-    const bool once = a.G == a.Gs;
+    const int grid = a.B * a.Hkv * a.n_sub * a.S;
+    const bool once = a.n_sub == 1;
     // blocks of 128 tokens per split at full capacity, per wavefront
     const int64_t per_wave = (ctx->cap_padded / 128 + (int64_t)a.S * GN - 1) / ((int64_t)a.S * GN);
     if (per_wave <= 1)

@@ -118,7 +118,7 @@ int choose_splits(const pq_attn_config *c, int n_cu)
     const int g = c->n_q_heads / c->n_kv_heads;
     const bool grouped12 = pq12_config_uses_grouped_kernel(c, n_cu);
     const int64_t heads = (int64_t)c->batch * (pq_config_uses_grouped_kernel(c) || grouped12
-                                                   ? c->n_q_heads / pq_grouped_heads_per_workgroup(g)
+                                                   ? c->n_kv_heads * pq_grouped_sub_groups(g)
                                                    : c->n_q_heads);
     int64_t s = n_cu / heads;
     const int64_t blocks = padded_capacity(c) / 64;
@@ -198,6 +198,7 @@ int launch_decode(const pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes,
     a.Hkv = ctx->cfg.n_kv_heads;
     a.G = ctx->group;
     a.Gs = ctx->k_skew == PQ_K_SKEW_QUAD || ctx->grouped12 ? pq_grouped_heads_per_workgroup(ctx->group) : 0;
+    a.n_sub = ctx->k_skew == PQ_K_SKEW_QUAD || ctx->grouped12 ? pq_grouped_sub_groups(ctx->group) : 0;
     a.S = ctx->n_splits;
     a.max_context = ctx->cfg.max_context;
     a.max_recent = ctx->cfg.max_recent;

@@ -93,7 +93,6 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int G = a.Gs;  // query heads of this workgroup (2..4)
 
     const uint32_t grid = gridDim.x;
     uint32_t logical = blockIdx.x;
@@ -103,14 +102,19 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     // workgroups of one KV head are neighbours: (sequence, KV head, sub-group of G query heads, split)
     const int unit = (int)(logical / (uint32_t)S_grid);
     const int split = (int)(logical - (uint32_t)unit * (uint32_t)S_grid);
-    const int n_sub = a.G / G;                     // sub-groups per KV head
+    const int n_sub = a.n_sub;                     // sub-groups per KV head
     // ... then the same KV head of the other sequences (same codebook images: once per XCD from memory)
     const int hb = (int)((uint32_t)unit / (uint32_t)n_sub);  // hkv * B + b
     const int sub_group = unit - hb * n_sub;
     const int hkv = (int)((uint32_t)hb / (uint32_t)a.B);
     const int b = hb - hkv * a.B;
     const int bkv = b * a.Hkv + hkv;
-    const int bh0 = b * a.Hq + hkv * a.G + sub_group * G;  // first query head of this workgroup
+    // the KV head's a.G query heads in n_sub sub-groups whose sizes differ by at most one (the first a.G % n_sub take
+    // one more): this workgroup's heads are g_first .. g_first + G - 1, G = 2..4
+    const int g_base = a.G / n_sub, g_rem = a.G - g_base * n_sub;
+    const int G = g_base + (sub_group < g_rem ? 1 : 0);
+    const int g_first = sub_group * g_base + (sub_group < g_rem ? sub_group : g_rem);
+    const int bh0 = b * a.Hq + hkv * a.G + g_first;  // first query head of this workgroup
     // The lengths are requested first and taken out of their registers only after the table loads
     // below have been issued.  The loads go through lane_zero(), which the compiler cannot see
     // through: a load from a wave-uniform address is otherwise made scalar on the spot, with a full
@@ -475,16 +479,15 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
 
 }  // namespace
 
-// Query heads per workgroup for a group of g query heads per KV head: the largest of 4, 3, 2 that divides
-// g (the matrix instruction has 4 rows); 0 if none does or g = 1.
+// A KV head's g query heads are cut into ceil(g / 4) sub-groups (the matrix instruction has 4 rows), one workgroup
+// each, sizes as equal as possible: 2..4 heads for every g >= 2 (5 = 3 + 2, 7 = 4 + 3, 10 = 4 + 3 + 3).
+int pq_grouped_sub_groups(int g) { return g < 2 ? 0 : (g + GMAX - 1) / GMAX; }
+
+// the largest sub-group; 0 for g = 1 (no grouped kernel)
 int pq_grouped_heads_per_workgroup(int g)
 {
-    if (g < 2)
-        return 0;
-    for (int gs = GMAX; gs >= 2; --gs)
-        if (g % gs == 0)
-            return gs;
-    return 0;
+    const int n = pq_grouped_sub_groups(g);
+    return n == 0 ? 0 : (g + n - 1) / n;
 }
 
 bool pq_config_uses_grouped_kernel(const pq_attn_config *cfg)
@@ -497,8 +500,8 @@ bool pq_config_uses_grouped_kernel(const pq_attn_config *cfg)
 
 hipError_t pq_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s)
 {
-    const int grid = a.B * a.Hkv * (a.G / a.Gs) * a.S;
-    const bool once = a.G == a.Gs;
+    const int grid = a.B * a.Hkv * a.n_sub * a.S;
+    const bool once = a.n_sub == 1;
     if (ctx->cfg.n_subspaces == 64) {
         if (once) hipLaunchKernelGGL((pq_decode_grouped_kernel<true, 64>), dim3(grid), dim3(GNW * 64), 0, s, a);
         else hipLaunchKernelGGL((pq_decode_grouped_kernel<false, 64>), dim3(grid), dim3(GNW * 64), 0, s, a);

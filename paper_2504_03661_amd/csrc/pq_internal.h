@@ -126,7 +126,9 @@ struct pq_decode_args {
     unsigned int *tickets;
     float scale_log2e;
     int B, Hq, Hkv, G, S;  // G = Hq / Hkv
-    int Gs;                // grouped-query kernel: query heads per workgroup (divides G)
+    int Gs;                // grouped-query kernels: the largest number of query heads a workgroup takes (2..4)
+    int n_sub;             // ... and the sub-groups a KV head's G query heads are cut into: ceil(G / 4) groups whose
+                           // sizes differ by at most one (7 = 4 + 3, 5 = 3 + 2, 10 = 4 + 3 + 3)
     int max_context, max_recent;
     int64_t head_stride;  // bytes of one (sequence, KV head) in a code tensor
 };
@@ -144,9 +146,11 @@ struct pq_encode_args {
 // launchers (each returns hipGetLastError() after its launches)
 hipError_t pq_launch_decode(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
 hipError_t pq_launch_decode_grouped(const pq_attn_ctx *ctx, const pq_decode_args &a, hipStream_t s);
-// true when the grouped-query kernel serves this configuration (fp16, M = 64 or 32, 8-bit codes, Hq / Hkv a multiple of
-// 2, 3 or 4); the kernel takes pq_grouped_heads_per_workgroup(Hq / Hkv) query heads per workgroup
+// true when the grouped-query kernel serves this configuration (fp16, M = 64 or 32, 8-bit codes, Hq / Hkv >= 2).  A KV
+// head's g query heads are cut into pq_grouped_sub_groups(g) = ceil(g / 4) sub-groups of 2..4 heads whose sizes differ by
+// at most one, one workgroup each; pq_grouped_heads_per_workgroup(g) is the largest of them (0 for g < 2)
 bool pq_config_uses_grouped_kernel(const pq_attn_config *cfg);
+int pq_grouped_sub_groups(int g);
 int pq_grouped_heads_per_workgroup(int g);
 hipError_t pq_launch_encode(const pq_attn_ctx *ctx, const pq_encode_args &a, int32_t *ctx_len, unsigned int *dev_err,
                             hipStream_t s);

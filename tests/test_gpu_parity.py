@@ -98,7 +98,9 @@ CASES = [
     ("gqa8_m64_f16_two_subgroups", 1, 8, 1, 64, "f16", (1500,), 7, 2),
     ("gqa6_m64_f16_two_subgroups_of_3", 2, 12, 2, 64, "f16", (2100, 777), 9, 3),
     ("gqa16_m64_f16_four_subgroups", 1, 16, 1, 64, "f16", (3000,), 5, 0),
-    ("gqa5_m64_f16_per_head", 1, 5, 1, 64, "f16", (1300,), 6, 2),
+    ("gqa5_m64_f16_subgroups_3_2", 1, 5, 1, 64, "f16", (1300,), 6, 2),
+    ("gqa7_m64_f16_subgroups_4_3", 2, 14, 2, 64, "f16", (2500, 300), 9, 3),
+    ("gqa10_m64_f16_subgroups_4_3_3", 1, 10, 1, 64, "f16", (1900,), 4, 0),
     ("gqa4_m64_f32_per_head", 1, 4, 1, 64, "f32", (700,), 7, 2),
     ("gqa_edges", 6, 8, 2, 64, "f16", (0, 1, 63, 64, 65, 0), 8, 4),
     ("mha_m32_f16", 2, 4, 4, 32, "f16", (777, 4096), 20, 0),
@@ -106,7 +108,8 @@ CASES = [
     ("gqa4_m32_f16_s1", 2, 8, 2, 32, "f16", (2100, 129), 5, 1),
     ("gqa3_m32_f16", 1, 6, 2, 32, "f16", (4097,), 7, 5),
     ("gqa8_m32_f16_two_subgroups", 1, 8, 1, 32, "f16", (1500,), 7, 2),
-    ("gqa5_m32_f16_per_head", 1, 5, 1, 32, "f16", (1300,), 6, 2),
+    ("gqa5_m32_f16_subgroups_3_2", 1, 5, 1, 32, "f16", (1300,), 6, 2),
+    ("gqa7_m32_f16_subgroups_4_3", 1, 7, 1, 32, "f16", (2600,), 5, 2),
     ("gqa_m32_edges", 6, 8, 2, 32, "f16", (0, 1, 63, 64, 65, 0), 8, 4),
     ("gqa_m32_f16_s5", 2, 8, 4, 32, "f16", (1500, 63), 9, 5),
     ("mha_m64_f32", 2, 2, 2, 64, "f32", (900, 65), 12, 2),
@@ -140,11 +143,12 @@ def test_decode_small(case):
 @pytest.mark.parametrize("seed", range(24))
 def test_decode_random_shapes(seed):
     """Seeded random shapes across every kernel variant: batch, group size (per-head, grouped with 2 / 3 / 4 heads
-    per workgroup, fall-back sizes), M, dtype, ragged lengths including empty sequences, window sizes, splits."""
+    per workgroup, equal and unequal sub-groups), M, dtype, ragged lengths including empty sequences, window sizes,
+    splits."""
     rng = np.random.default_rng(9000 + seed)
     B_ = int(rng.integers(1, 5))
     Hkv = int(rng.integers(1, 4))
-    G = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 8]))
+    G = int(rng.choice([1, 1, 2, 3, 4, 5, 6, 7, 8]))
     M = int(rng.choice([64, 64, 32]))
     dtype = "f32" if seed % 6 == 5 else "f16"
     lens = tuple(int(x) for x in rng.choice([0, 1, 63, 64, 65, 500, 2047, 4096, 6001], size=B_))

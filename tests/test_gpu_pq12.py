@@ -179,6 +179,8 @@ GROUPED_CASES = [
     ("g3", 1, 6, 2, (7000,), 5, 2, 0),
     ("g8_two_workgroups_per_kv_head", 1, 8, 1, (6000,), 3, 2, 0),    # groups of 4 share the code stream through L2
     ("g6_two_groups_of_3", 2, 6, 1, (3000, 2900), 0, 1, 0),
+    ("g5_groups_of_3_and_2", 1, 5, 1, (5000,), 4, 2, 0),
+    ("g7_groups_of_4_and_3", 2, 14, 2, (2500, 4100), 6, 3, 0),
     ("g4_edges", 6, 4, 1, (0, 1, 127, 128, 129, 0), 8, 2, 0),
     ("g4_two_blocks_per_wave", 1, 4, 1, (4000,), 5, 1, 0),
     ("g4_four_blocks_per_wave", 1, 4, 1, (8100,), 5, 1, 0),
@@ -208,7 +210,8 @@ def test_decode_grouped_queries(case):
     cap = None if extra == 0 else max(lens) + extra
     with PQSession(data, Hq, "f16", n_splits=splits, max_context=cap) as s:
         g = Hq // Hkv
-        assert s.n_passes == 1 and s.heads_per_workgroup == (4 if g % 4 == 0 else 3 if g % 3 == 0 else 2)
+        n_sub = (g + 3) // 4                                 # sub-groups of 2..4 heads, sizes as equal as possible
+        assert s.n_passes == 1 and s.heads_per_workgroup == (g + n_sub - 1) // n_sub
         for rep in range(2):
             s.out.fill_(float("nan"))
             out = s.decode(W.attention_scale(w))
@@ -231,15 +234,15 @@ def test_small_grouped_query_shapes_keep_the_two_pass_per_head_path():
         check(out.cpu().numpy(), oracle_out(w, data), "g4_small")
 
 
-def test_group_sizes_without_a_grouped_kernel_keep_the_per_head_kernel():
-    """5 query heads per KV head: no group of 2, 3 or 4 divides it, every query head walks the codes by itself."""
-    w = workload("g5", 1, 5, 1, (5000,), 4)
+def test_per_head_kernels_serve_grouped_queries_on_request():
+    """n_splits < 0 asks for the two-pass path, which is per query head whatever the group size."""
+    w = workload("g5_two_pass", 1, 5, 1, (5000,), 4)
     data = W.generate(w)
-    with PQSession(data, 5, "f16", n_splits=2) as s:
-        assert s.heads_per_workgroup == 1
+    with PQSession(data, 5, "f16", n_splits=-2) as s:
+        assert s.heads_per_workgroup == 1 and s.n_passes == 2
         out = s.decode(W.attention_scale(w))
         torch.cuda.synchronize()
-        check(out.cpu().numpy(), oracle_out(w, data), "g5")
+        check(out.cpu().numpy(), oracle_out(w, data), "g5 two-pass")
 
 
 def test_grouped_queries_at_128k():
