@@ -369,6 +369,21 @@ def batch():
         res[f"{Bn}x{n // 1024}k"] = {"decode_us": round(ms * 1e3, 1), "append_one_token_per_sequence_us": round(t_app, 1),
                                      "algorithmic_bytes": total,
                                      "frac_of_hbm_peak": round(total / (ms * 1e-3) / 1e9 / 8000.0, 4)}
+    # ragged batches in a 128K-capacity cache: with 256 (sequence, head) pairs the library chooses one split, and a
+    # long sequence is then scanned by one workgroup per head while the compute units of the short ones idle; a
+    # caller who expects ragged batches asks for splits (the live splits follow each sequence's length)
+    for label, lens in (("one_128k_seven_1k", (131072,) + (1024,) * 7), ("64k_halving_to_512", tuple(65536 >> k for k in range(8))),
+                        ("eight_32k", (32768,) * 8)):
+        row = {}
+        for n_splits in (0, 8):
+            w = W.Workload("ragged", 8, 32, 32, 128, 64, 131072, "f16", recent_cap=128, recent_fixed=128,
+                           seed=W.BASE_SEED + 51, ctx_lens=lens)
+            data = W.generate(w)
+            with PQSession(data, 32, "f16", n_splits=n_splits) as s:
+                dec = s.prepared_decode(W.attention_scale(w))
+                row[f"n_splits_{n_splits}"] = {"splits": s.n_splits, "decode_us": round(_span_ms(dec, 50, warmup=50) * 1e3, 1)}
+            del data
+        res["ragged_" + label] = row
     return res
 
 
