@@ -202,6 +202,7 @@ int launch_decode(const pq_attn_ctx *ctx, const void *q, const uint8_t *k_codes,
     a.S = ctx->n_splits;
     a.max_context = ctx->cfg.max_context;
     a.max_recent = ctx->cfg.max_recent;
+    a.n_cu = ctx->n_cu;
     a.head_stride = ctx->cap_padded * token_bytes(&ctx->cfg);
     const hipError_t e = ctx->grouped12                  ? pq12_launch_decode_grouped(ctx, a, s)
                          : pq_config_is_12bit(&ctx->cfg) ? pq12_launch_decode(ctx, a, s)
@@ -267,6 +268,7 @@ int pq_attn_create(const pq_attn_config *cfg, pq_attn_ctx **out)
     ctx->cap_padded = padded_capacity(cfg);
     ctx->elem_bytes = cfg->dtype == PQ_F16 ? 2 : 4;
     ctx->k_skew = pq_config_uses_grouped_kernel(cfg) ? PQ_K_SKEW_QUAD : PQ_K_SKEW_LANE;
+    ctx->n_cu = prop.multiProcessorCount;
     ctx->grouped12 = pq12_config_uses_grouped_kernel(cfg, prop.multiProcessorCount);
     ctx->n_splits = cfg->n_splits > 0 ? cfg->n_splits : choose_splits(cfg, prop.multiProcessorCount);
     // 12-bit contexts with few (sequence, query head) pairs decode in two passes (split by subspace group, see
@@ -421,6 +423,7 @@ int pq_attn_decode_noalloc(const pq_attn_config *cfg, const void *q, const uint8
     ctx.cap_padded = padded_capacity(cfg);
     ctx.elem_bytes = elem;
     ctx.k_skew = pq_config_uses_grouped_kernel(cfg) ? PQ_K_SKEW_QUAD : PQ_K_SKEW_LANE;
+    ctx.n_cu = dev.n_cu;
     int64_t splits = cfg->n_splits > 0 ? cfg->n_splits : choose_splits(cfg, dev.n_cu);
     if (rows * splits > PQ_NOALLOC_MAX_ROWS)
         splits = PQ_NOALLOC_MAX_ROWS / rows;

@@ -64,15 +64,12 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     // dealt round-robin to the 8 XCDs; un-deal them so that all splits of a head (and
     // all query heads of a KV group) sit on one XCD and share its L2 for the
     // codebooks and, with grouped queries, the code stream itself.
-    const uint32_t grid = gridDim.x;
-    uint32_t logical = blockIdx.x;
-    if ((grid & 7u) == 0)
-        logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
     const int S_grid = a.S;  // splits the grid was launched with (partials are laid out with this stride)
     // neighbours: the splits of a (sequence, query head), the query heads of its KV group, then the same
     // KV head of the other sequences (they load the same codebooks: once per XCD instead of once per sequence)
-    const uint32_t unit = logical / (uint32_t)S_grid;
-    const int split = (int)(logical - unit * (uint32_t)S_grid);
+    uint32_t unit, split_u;
+    unit_and_split(blockIdx.x, gridDim.x, (uint32_t)S_grid, unit, split_u);
+    const int split = (int)split_u;
     const uint32_t bkv = unit / (uint32_t)a.G;          // hkv * B + b
     const int gq = (int)(unit - bkv * (uint32_t)a.G);
     const int hkv = (int)(bkv / (uint32_t)a.B);
@@ -88,6 +85,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const bool has_recent = a.recent_k != nullptr && a.recent_len != nullptr;
     const int n_vec = a.ctx_len[b + zero];
     const int r_vec = (has_recent ? a.recent_len : a.ctx_len)[b + zero];
+    const int w_lane = a.B > 1 ? batch_work_lane(a, has_recent, lane) : 0;
 
     // ---- prologue: LUT[c][x] for x = 0..63 (for M = 32 columns x and x+32 hold the same
     // subspace), and the value codebook image.  Order matters at this time scale:
@@ -135,7 +133,11 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     // (or folds in at least 16 recent rows),
     // so a short sequence in a long cache uses the first few splits only and the others leave here, before
     // they build tables (every workgroup of the row computes the same count; the merge expects that many).
-    const uint32_t want = nblk / 4u > (uint32_t)R / 16u ? nblk / 4u : (uint32_t)R / 16u;  // ... or 16 recent rows
+    uint32_t want = nblk / 4u > (uint32_t)R / 16u ? nblk / 4u : (uint32_t)R / 16u;  // ... or 16 recent rows
+    if (a.B > 1) {  // ... and in a batch no more than the sequence's share of the compute units
+        const uint32_t cap = live_split_cap(a, a.Hq, N + R, w_lane);
+        want = want < cap ? want : cap;
+    }
     const int S = (int)(want < 1u ? 1u : (want < (uint32_t)S_grid ? want : (uint32_t)S_grid));
     if (split >= S)
         return;

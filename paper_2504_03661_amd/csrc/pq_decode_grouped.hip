@@ -94,14 +94,11 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    const uint32_t grid = gridDim.x;
-    uint32_t logical = blockIdx.x;
-    if ((grid & 7u) == 0)
-        logical = (blockIdx.x & 7u) * (grid >> 3) + (blockIdx.x >> 3);
     const int S_grid = a.S;  // splits the grid was launched with (partials are laid out with this stride)
     // workgroups of one KV head are neighbours: (sequence, KV head, sub-group of G query heads, split)
-    const int unit = (int)(logical / (uint32_t)S_grid);
-    const int split = (int)(logical - (uint32_t)unit * (uint32_t)S_grid);
+    uint32_t unit_u, split_u;
+    unit_and_split(blockIdx.x, gridDim.x, (uint32_t)S_grid, unit_u, split_u);
+    const int unit = (int)unit_u, split = (int)split_u;
     const int n_sub = a.n_sub;                     // sub-groups per KV head
     // ... then the same KV head of the other sequences (same codebook images: once per XCD from memory)
     const int hb = (int)((uint32_t)unit / (uint32_t)n_sub);  // hkv * B + b
@@ -123,6 +120,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const bool has_recent = a.recent_k != nullptr && a.recent_len != nullptr;
     const int n_vec = a.ctx_len[b + zero];
     const int r_vec = (has_recent ? a.recent_len : a.ctx_len)[b + zero];
+    const int w_lane = a.B > 1 ? batch_work_lane(a, has_recent, lane) : 0;
 
     // ---- prologue: both codebook images and the group's queries; table loads first, bare
     // barrier, then the first code block (see the per-head kernel for why)
@@ -150,7 +148,11 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const uint32_t nblk = (uint32_t)(N + 63) >> 6;
     // live splits follow the length (at least 4 blocks or 16 recent rows each); the others leave before the images
     // are staged
-    const uint32_t want = nblk / 4u > (uint32_t)R / 16u ? nblk / 4u : (uint32_t)R / 16u;  // ... or 16 recent rows
+    uint32_t want = nblk / 4u > (uint32_t)R / 16u ? nblk / 4u : (uint32_t)R / 16u;  // ... or 16 recent rows
+    if (a.B > 1) {  // ... and in a batch no more than the sequence's share of the compute units
+        const uint32_t cap = live_split_cap(a, a.Hkv * a.n_sub, N + R, w_lane);
+        want = want < cap ? want : cap;
+    }
     const int S = (int)(want < 1u ? 1u : (want < (uint32_t)S_grid ? want : (uint32_t)S_grid));
     if (split >= S)
         return;

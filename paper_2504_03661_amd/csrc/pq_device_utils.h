@@ -138,6 +138,66 @@ __device__ inline int lds_grab(uint32_t lds_addr)
     return __builtin_amdgcn_readfirstlane((int)r);
 }
 
+
+// Which (unit, split) a workgroup owns; unit = a (sequence, head or head group).  Workgroups are dealt round-robin
+// to the 8 XCDs; they are un-dealt so that all splits of a unit — and neighbouring units: the heads of a KV group,
+// the same KV head of other sequences — sit on one XCD and share its L2.  Where every XCD gets whole units, its
+// workgroups are numbered SPLIT-major: the first splits of all its units come first.  With unit-major numbering the
+// live workgroups of an oversubscribed grid whose surplus splits leave at once (8 launched splits, 1 live) sit 8
+// apart, and the dispatcher, which deals consecutive workgroups to the shader engines in turn, put them all on one
+// engine's compute units: 8 x 32 heads x 32K with 8 launched splits took 483 us instead of 165.
+__device__ inline void unit_and_split(uint32_t bid, uint32_t grid, uint32_t S, uint32_t &unit, uint32_t &split)
+{
+    const uint32_t n_units = grid / S;
+    if ((n_units & 7u) == 0) {
+        const uint32_t per_xcd = n_units >> 3, xcd = bid & 7u, local = bid >> 3;
+        split = local / per_xcd;
+        uint32_t j = local - split * per_xcd;
+        // ... and where the XCD's unit count is a power of two, the units are visited in a scrambled order (low 3
+        // bits XOR the next 3): the long sequences of a ragged batch sit at a fixed stride in the unit numbering
+        // (unit = head x batch + sequence), which met the same engine every time
+        if (per_xcd >= 16u && (per_xcd & (per_xcd - 1u)) == 0u)
+            j ^= (j >> 3) & 7u;
+        unit = xcd * per_xcd + j;
+    } else {
+        const uint32_t logical = (grid & 7u) == 0 ? (bid & 7u) * (grid >> 3) + (bid >> 3) : bid;
+        unit = logical / S;
+        split = logical - unit * S;
+    }
+}
+
+// Sum over the batch of (cached tokens + recent rows), each clamped like the sequence's own lengths: lane l adds
+// sequences l, l + 64, ...; the loads go out with the workgroup's own lengths.  Only batches need it (the live
+// split count of a sequence follows its share of the batch's work).
+template <typename A> __device__ inline int batch_work_lane(const A &a, bool has_recent, int lane)
+{
+    int w = 0;
+    for (int b2 = lane; b2 < a.B; b2 += 64) {
+        int n2 = a.ctx_len[b2];
+        n2 = n2 < 0 ? 0 : (n2 > a.max_context ? a.max_context : n2);
+        int r2 = has_recent ? a.recent_len[b2] : 0;
+        r2 = r2 < 0 ? 0 : (r2 > a.max_recent ? a.max_recent : r2);
+        w += n2 + r2;
+    }
+    return w;
+}
+
+// The live splits of a sequence in a batch: no more than its share of the compute units — n_cu x (its work) /
+// (workgroups per split x the batch's work) — so that in an oversubscribed grid (explicit n_splits on a large
+// batch: a cache that must serve ragged batches) the splits go to the long sequences and a batch of equal lengths
+// runs one split per sequence, as if none had been asked for.  Every workgroup of the row computes the same number
+// from the same lengths.
+template <typename A> __device__ inline uint32_t live_split_cap(const A &a, int units, int own_work, int w_lane)
+{
+    int total = w_lane;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+        total += __shfl_xor(total, o);
+    total = __builtin_amdgcn_readfirstlane(total);
+    const float share = (float)a.n_cu * (float)own_work / ((float)units * (float)(total > 0 ? total : 1));
+    return share >= 1.f ? (uint32_t)share : 1u;
+}
+
 // 16 code bytes of one lane.  Codes that are read once per launch are loaded with the
 // non-temporal hint: the stream then does not displace the tables and each other's lines in L2
 // and the memory-side cache, and HBM delivers markedly more (measured on the 8 x 32 heads x 32K

@@ -112,6 +112,7 @@ struct pq_attn_ctx {
     // token ranges of the second pass
     float *scores12;
     bool grouped12;       // 12-bit context that runs the grouped-query kernel
+    int n_cu;             // compute units of the device
 };
 
 struct pq_decode_args {
@@ -130,6 +131,7 @@ struct pq_decode_args {
     int n_sub;             // ... and the sub-groups a KV head's G query heads are cut into: ceil(G / 4) groups whose
                            // sizes differ by at most one (7 = 4 + 3, 5 = 3 + 2, 10 = 4 + 3 + 3)
     int max_context, max_recent;
+    int n_cu;              // compute units of the device (the live split count of a batch's sequences follows it)
     int64_t head_stride;  // bytes of one (sequence, KV head) in a code tensor
 };
 

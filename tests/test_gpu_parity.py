@@ -165,6 +165,23 @@ def test_decode_random_shapes(seed):
             assert (got[b] == 0).all()
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(32, 32), (32, 8)], ids=["per_head", "grouped"])
+def test_ragged_batch_in_an_oversubscribed_grid(Hq, Hkv):
+    """16 sequences with 8 launched splits each — more workgroups than compute units: the live splits of a sequence
+    follow its share of the batch's tokens (the long sequence takes several, the short ones one each, the surplus
+    workgroups leave), whatever the numbering of the workgroups; twice, for the tickets."""
+    lens = (20000, 300, 64, 0, 1500, 299, 4096, 65, 300, 300, 1, 777, 2048, 300, 63, 5000)
+    w = W.Workload("ragged16", 16, Hq, Hkv, 128, 64, 20000, "f16", recent_cap=40, recent_uniform=True, seed=77, ctx_lens=lens)
+    data = W.generate(w)
+    ref = oracle_out(w, data)
+    with PQSession(data, Hq, "f16", n_splits=8) as s:
+        for rep in range(2):
+            s.out.fill_(float("nan"))
+            out = s.decode(W.attention_scale(w))
+            torch.cuda.synchronize()
+            check(out.cpu().numpy(), ref, f"ragged16 {Hq}/{Hkv} call {rep}")
+
+
 def test_decode_no_recent_tensors_and_codebooks_passed_per_call():
     w = W.Workload("nr", 2, 4, 4, 128, 64, 1500, "f16", seed=31, ctx_lens=(1500, 700))
     data = W.generate(w)
