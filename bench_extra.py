@@ -371,7 +371,8 @@ def batch():
                                      "frac_of_hbm_peak": round(total / (ms * 1e-3) / 1e9 / 8000.0, 4)}
     # ragged batches in a 128K-capacity cache: with 256 (sequence, head) pairs the library chooses one split, and a
     # long sequence is then scanned by one workgroup per head while the compute units of the short ones idle; a
-    # caller who expects ragged batches asks for splits (the live splits follow each sequence's length)
+    # caller who expects ragged batches asks for splits (the live splits follow each sequence's length and its share
+    # of the batch's tokens, the surplus workgroups leave at once)
     for label, lens in (("one_128k_seven_1k", (131072,) + (1024,) * 7), ("64k_halving_to_512", tuple(65536 >> k for k in range(8))),
                         ("eight_32k", (32768,) * 8)):
         row = {}
