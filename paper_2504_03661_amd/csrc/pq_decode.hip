@@ -24,6 +24,8 @@
 //   value pass  lane = subspace (= output dims).  Lane i gathers centroid row
 //               code from column i of the value codebook image: again 64 distinct
 //               columns per gather; the fp16 pair is consumed by v_fma_mix.
+// fp32 contexts: table and (fp32, 128 KiB) value codebook image take turns in LDS, the
+// scan runs in chunks of two phases (see the scan loop).
 // The recent full-precision rows are spread over the splits and folded into the
 // same running softmax.  Partials of the wavefronts are merged in LDS, the
 // workgroup's partial goes to global scratch, and the workgroup that takes the
@@ -44,6 +46,13 @@ constexpr int PBUF_OFF = 131072;     // float [NW][64]
 constexpr int PART_OFF = 131072 + 4096;  // float [NW][PQ_PART_STRIDE]
 constexpr int CTR_OFF = PART_OFF + 16 * PQ_PART_STRIDE * 4;  // uint32: next unowned block of the split
 constexpr int SMEM_BYTES = CTR_OFF + 16;
+// fp32 contexts: the value codebook image is 128 KiB (256 rows of 512 bytes) and cannot sit next to the table, so
+// a workgroup scans in chunks of F32_CHUNK blocks and two phases (see the scan below); the scores of a chunk wait
+// in LDS between the phases
+constexpr int F32_CHUNK = 64;        // blocks (of 64 tokens) per chunk
+constexpr int SBUF_OFF = SMEM_BYTES; // float [F32_CHUNK][64]
+constexpr int SMEM_BYTES_F32 = SBUF_OFF + F32_CHUNK * 256;
+static_assert(SMEM_BYTES_F32 <= 160 * 1024, "LDS budget of a gfx950 compute unit");
 template <int M, int DS, typename T, int NW, bool READ_ONCE>
 __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args a)
 {
@@ -53,7 +62,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
 
     // The only LDS object of the kernel, so it sits at LDS address 0 and the
     // byte-assembled gather addresses below are used as they are.
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[F16 ? SMEM_BYTES : SMEM_BYTES_F32];
     lds_u8 *lbase = (lds_u8 *)smem;
 
     const int tid = threadIdx.x;
@@ -104,6 +113,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const int e0 = ((4 * g) & (M - 1)) * DS;           // first element of those columns in a row
     const char *kcb = (const char *)a.kcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM * sizeof(T);
     u32x4 kraw[PASSES][NV];
+    u32x4 qraw[NV];  // the query elements of columns 4g .. 4g+3 (converted after the barrier)
 #pragma unroll
     for (int k = 0; k < PASSES; ++k)
 #pragma unroll
@@ -116,7 +126,6 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         for (int v = 0; v < VPT; ++v)
             vraw[v] = src[tid + v * (NW * 64)];
     }
-    u32x4 qraw[NV];  // the query elements of columns 4g .. 4g+3 (converted after the barrier)
 #pragma unroll
     for (int v = 0; v < NV; ++v)
         qraw[v] = *(const u32x4 *)((const char *)a.q + (((int64_t)b * a.Hq + hq) * PQ_HEAD_DIM + e0) * sizeof(T) + v * 16);
@@ -164,7 +173,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     // READ_ONCE: one query head per KV head, so every code byte is read by exactly one workgroup,
     // once, and is loaded with the non-temporal hint (see load_codes).  With grouped queries the G
     // workgroups of a group share the code stream through their XCD's L2 and load normally.
-    constexpr int NBUF = M == 64 ? 1 : 2;
+    constexpr int NBUF = (M == 64 && F16) ? 1 : 2;  // fp32 contexts: two buffers, K codes in one phase, V codes in the other
     uint4 kbuf[NBUF][M / 16], vbuf[NBUF][M / 16];
     auto load_k = [&](uint4 (&dst)[M / 16], int blk_id, bool live) {
         const u32x4 *kp = (const u32x4 *)(k_head + (int64_t)blk_id * (64 * M)) + (live ? lane : 0);
@@ -188,7 +197,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     *(lds_u32 *)(lbase + CTR_OFF) = (uint32_t)(blk0 + NW);  // same value from every thread: no branch
     const uint32_t ctr_addr = (uint32_t)(uintptr_t)(lbase + CTR_OFF);
     load_k(kbuf[0], blk < blk1 ? blk : 0, blk < blk1);
-    if (NBUF == 2)
+    if (F16 && NBUF == 2)
         load_v(vbuf[0], blk < blk1 ? blk : 0, blk < blk1);
 
     // ---- this lane's query sub-vector, pre-multiplied by scale * log2(e)
@@ -242,7 +251,6 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     for (int j = 0; j < DS; ++j)
         acc[j] = 0.f;
 
-    const float *vcb_f32 = (const float *)a.vcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM;
     lds_u8 *pline = lbase + PBUF_OFF + wave * 256;
 
     auto process = [&](const uint4 (&kb)[M / 16], const uint4 (&vb)[M / 16], const int blk, auto &&after_score) {
@@ -323,13 +331,6 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
                             acc[DS - 2] = fmaf(pk[k], __low2float(h1), acc[DS - 2]);
                             acc[DS - 1] = fmaf(pk[k], __high2float(h1), acc[DS - 1]);
                         }
-                    } else {
-                        // fp32 codebooks do not fit in LDS next to the table: gather from memory
-                        const uint32_t code = (w >> (8 * k)) & 255u;
-                        const float *cv = vcb_f32 + ((int64_t)code * M + sub) * DS;
-#pragma unroll
-                        for (int j = 0; j < DS; ++j)
-                            acc[j] = fmaf(pk[k], cv[j], acc[j]);
                     }
                 }
             }
@@ -337,7 +338,158 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
         __builtin_amdgcn_wave_barrier();
     };
 
-    if constexpr (NBUF == 1) {
+    if constexpr (!F16) {
+        // fp32 contexts.  The table (64 KiB) and the fp32 value codebook image (128 KiB) do not fit LDS together, so
+        // the split is scanned in chunks of F32_CHUNK blocks, each in two phases with the whole workgroup in step:
+        //   phase 1  the table is resident; every wavefront scores its blocks of the chunk (block c0 + wave, then
+        //            every NW-th) and leaves the raw scores in LDS;
+        //   swap     the image of the value codebook replaces the table (read once more from L2);
+        //   phase 2  the same blocks again: running softmax on the stored scores, then the value pass, whose
+        //            gathers (8 or 16 bytes per lane, row = code, column = subspace) are conflict-free;
+        //   before the next chunk the table is rebuilt from the key codebook.
+        // A chunk moves 4096 tokens' codes (512 KiB at M = 64) for 256 KiB of codebook re-reads out of L2.
+        constexpr int KV = M / 16;
+        constexpr int IMG_VEC = 8192 / (NW * 64);  // 16-byte vectors of the image per thread
+        const u32x4 *vimg = (const u32x4 *)((const float *)a.vcb_packed + (int64_t)hkv * 256 * PQ_HEAD_DIM);
+        const uint32_t vcol32 = (uint32_t)(sub * DS * 4);
+        // the table again, for the chunks after the first (the prologue's steps in one go)
+        auto rebuild_table = [&]() {
+#pragma unroll
+            for (int k = 0; k < PASSES; ++k)
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
+                    kraw[k][v] = *(const u32x4 *)(kcb + ((row0 + k * ROWS_PER_PASS) * PQ_HEAD_DIM + e0) * sizeof(T) + v * 16);
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+                qraw[v] = *(const u32x4 *)((const char *)a.q + (((int64_t)b * a.Hq + hq) * PQ_HEAD_DIM + e0) * sizeof(T) + v * 16);
+            float qv[4 * DS];
+#pragma unroll
+            for (int e = 0; e < 4 * DS; ++e)
+                qv[e] = elem<T>::ld(&qraw[0], e) * a.scale_log2e;
+#pragma unroll
+            for (int k = 0; k < PASSES; ++k) {
+                f32x4 ent;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    float e = 0.f;
+#pragma unroll
+                    for (int j = 0; j < DS; ++j)
+                        e = fmaf(qv[u * DS + j], elem<T>::ld(&kraw[k][0], u * DS + j), e);
+                    ent[u] = e;
+                }
+                *(lds_f32x4 *)(lbase + LUT_OFF + (row0 + k * ROWS_PER_PASS) * 256 + g * 16) = ent;
+            }
+        };
+        auto score_block = [&](const uint4 (&kb)[KV], const int blk_id, const int c0) {
+            float s4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int r = 0; r < M / 4; ++r) {
+                const uint32_t w = comp(kb[r >> 2], r & 3);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t sel = 0x0c0c0000u | ((4 + k) << 8) | k;
+                    s4[k] += *(lds_f32 *)(lbase + __builtin_amdgcn_perm(w, idx[r], sel));
+                }
+            }
+            const bool valid = blk_id * 64 + lane < N;
+            *(lds_f32 *)(lbase + SBUF_OFF + ((blk_id - c0) * 64 + lane) * 4) =
+                valid ? (s4[0] + s4[1]) + (s4[2] + s4[3]) : NEG_BIG;
+        };
+        auto value_block = [&](const uint4 (&vb)[KV], const int blk_id, const int c0) {
+            const float s = *(lds_f32 *)(lbase + SBUF_OFF + ((blk_id - c0) * 64 + lane) * 4);
+            const bool valid = blk_id * 64 + lane < N;
+            const float m_new = fmaxf(m_run, wave_max(s));
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            const float p = valid ? __builtin_amdgcn_exp2f(s - m_new) : 0.f;
+            l_lane = fmaf(l_lane, alpha, p);
+#pragma unroll
+            for (int j = 0; j < DS; ++j)
+                acc[j] *= alpha;
+            m_run = m_new;
+            *(lds_f32 *)(pline + lane * 4) = p;
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int n = 0; n < KV; ++n) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t w = comp(vb[n], r);
+                    const int tok0 = (M == 64) ? (16 * n + 4 * r) : (32 * n + 16 * half_id + 4 * r);
+                    const f32x4 p4 = *(lds_f32x4 *)(pline + tok0 * 4);
+                    const float pk[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const uint32_t addr = (((w >> (8 * k)) & 255u) << 9) | vcol32;  // image row = 512 bytes
+                        if constexpr (DS == 2) {
+                            const lds_f32 *cv = (const lds_f32 *)(lbase + addr);
+                            const float c0v = cv[0], c1v = cv[1];
+                            acc[0] = fmaf(pk[k], c0v, acc[0]);
+                            acc[1] = fmaf(pk[k], c1v, acc[1]);
+                        } else {
+                            const f32x4 cv = *(lds_f32x4 *)(lbase + addr);
+                            acc[0] = fmaf(pk[k], cv.x, acc[0]);
+                            acc[1] = fmaf(pk[k], cv.y, acc[1]);
+                            acc[DS - 2] = fmaf(pk[k], cv.z, acc[DS - 2]);
+                            acc[DS - 1] = fmaf(pk[k], cv.w, acc[DS - 1]);
+                        }
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        };
+        for (int c0 = blk0; c0 < blk1; c0 += F32_CHUNK) {
+            const int c1 = c0 + F32_CHUNK < blk1 ? c0 + F32_CHUNK : blk1;
+            int cur = c0 + wave;
+            if (c0 != blk0) {  // (the first chunk's table and first K codes come from the prologue)
+                __syncthreads();  // the value pass of the previous chunk is over: the image may go
+                load_k(kbuf[0], cur < c1 ? cur : c0, cur < c1);
+                rebuild_table();
+                __syncthreads();
+            }
+            // ---- phase 1: scores (two blocks per trip so that the buffers swap roles without copies)
+            bool more = cur < c1;
+            while (more) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if (more) {
+                        const int nb = cur + NW;
+                        load_k(kbuf[j ^ 1], nb < c1 ? nb : cur, nb < c1);
+                        score_block(kbuf[j], cur, c0);
+                        cur = nb;
+                        more = nb < c1;
+                    }
+                }
+            }
+            // ---- swap: the value codebook image over the table
+            cur = c0 + wave;
+            load_v(vbuf[0], cur < c1 ? cur : c0, cur < c1);
+            __syncthreads();  // nobody reads the table any more
+#pragma unroll
+            for (int h = 0; h < IMG_VEC; h += 8) {
+                u32x4 t[8];
+#pragma unroll
+                for (int v = 0; v < 8; ++v)
+                    t[v] = vimg[tid + (h + v) * (NW * 64)];
+#pragma unroll
+                for (int v = 0; v < 8; ++v)
+                    *(lds_u32x4 *)(lbase + (tid + (h + v) * (NW * 64)) * 16) = t[v];
+            }
+            __syncthreads();
+            // ---- phase 2: softmax and value pass over the same blocks
+            more = cur < c1;
+            while (more) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if (more) {
+                        const int nb = cur + NW;
+                        load_v(vbuf[j ^ 1], nb < c1 ? nb : cur, nb < c1);
+                        value_block(vbuf[j], cur, c0);
+                        cur = nb;
+                        more = nb < c1;
+                    }
+                }
+            }
+        }
+    } else if constexpr (NBUF == 1) {
         while (blk < blk1) {
             const int nb = lds_grab(ctr_addr);
             const int next_blk = nb < blk1 ? nb : blk;

@@ -165,6 +165,24 @@ def test_decode_random_shapes(seed):
             assert (got[b] == 0).all()
 
 
+@pytest.mark.parametrize("M,Hq,Hkv,splits", [(64, 2, 2, 1), (64, 4, 2, 3), (32, 2, 2, 2), (32, 6, 2, 1)])
+def test_fp32_contexts_scan_in_chunks(M, Hq, Hkv, splits):
+    """fp32 contexts keep the table and the value codebook image in LDS in turn: a split longer than one chunk
+    (4096 tokens) walks several chunks, each in two phases; lengths around the chunk and block borders, one and
+    several splits, one and several query heads per KV head."""
+    lens = (9000, 4096, 4097, 20001, 0, 8192)
+    w = W.Workload("f32chunks", len(lens), Hq, Hkv, 128, M, max(lens), "f32", recent_cap=9, recent_uniform=True,
+                   seed=4100 + M + Hq, ctx_lens=lens)
+    data = W.generate(w)
+    ref = oracle_out(w, data)
+    with PQSession(data, Hq, "f32", n_splits=splits) as s:
+        for rep in range(2):
+            s.out.fill_(float("nan"))
+            out = s.decode(W.attention_scale(w))
+            torch.cuda.synchronize()
+            check(out.cpu().numpy(), ref, f"fp32 chunks M={M} {Hq}/{Hkv} S={splits} call {rep}")
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(32, 32), (32, 8)], ids=["per_head", "grouped"])
 def test_ragged_batch_in_an_oversubscribed_grid(Hq, Hkv):
     """16 sequences with 8 launched splits each — more workgroups than compute units: the live splits of a sequence
