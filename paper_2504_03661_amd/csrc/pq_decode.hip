@@ -94,7 +94,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const bool has_recent = a.recent_k != nullptr && a.recent_len != nullptr;
     const int n_vec = a.ctx_len[b + zero];
     const int r_vec = (has_recent ? a.recent_len : a.ctx_len)[b + zero];
-    const int w_lane = a.B > 1 ? batch_work_lane(a, has_recent, lane) : 0;
+    const float w_lane = a.B > 1 ? batch_work_lane(a, has_recent, lane) : 0.f;
 
     // ---- prologue: LUT[c][x] for x = 0..63 (for M = 32 columns x and x+32 hold the same
     // subspace), and the value codebook image.  Order matters at this time scale:

@@ -120,7 +120,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const bool has_recent = a.recent_k != nullptr && a.recent_len != nullptr;
     const int n_vec = a.ctx_len[b + zero];
     const int r_vec = (has_recent ? a.recent_len : a.ctx_len)[b + zero];
-    const int w_lane = a.B > 1 ? batch_work_lane(a, has_recent, lane) : 0;
+    const float w_lane = a.B > 1 ? batch_work_lane(a, has_recent, lane) : 0.f;
 
     // ---- prologue: both codebook images and the group's queries; table loads first, bare
     // barrier, then the first code block (see the per-head kernel for why)

@@ -169,15 +169,16 @@ __device__ inline void unit_and_split(uint32_t bid, uint32_t grid, uint32_t S, u
 // Sum over the batch of (cached tokens + recent rows), each clamped like the sequence's own lengths: lane l adds
 // sequences l, l + 64, ...; the loads go out with the workgroup's own lengths.  Only batches need it (the live
 // split count of a sequence follows its share of the batch's work).
-template <typename A> __device__ inline int batch_work_lane(const A &a, bool has_recent, int lane)
+// (a float: 64 sequences of 2^24 tokens already exceed an int, and every workgroup adds in the same order)
+template <typename A> __device__ inline float batch_work_lane(const A &a, bool has_recent, int lane)
 {
-    int w = 0;
+    float w = 0.f;
     for (int b2 = lane; b2 < a.B; b2 += 64) {
         int n2 = a.ctx_len[b2];
         n2 = n2 < 0 ? 0 : (n2 > a.max_context ? a.max_context : n2);
         int r2 = has_recent ? a.recent_len[b2] : 0;
         r2 = r2 < 0 ? 0 : (r2 > a.max_recent ? a.max_recent : r2);
-        w += n2 + r2;
+        w += (float)(n2 + r2);
     }
     return w;
 }
@@ -187,15 +188,15 @@ template <typename A> __device__ inline int batch_work_lane(const A &a, bool has
 // batch: a cache that must serve ragged batches) the splits go to the long sequences and a batch of equal lengths
 // runs one split per sequence, as if none had been asked for.  Every workgroup of the row computes the same number
 // from the same lengths.
-template <typename A> __device__ inline uint32_t live_split_cap(const A &a, int units, int own_work, int w_lane)
+template <typename A> __device__ inline uint32_t live_split_cap(const A &a, int units, int own_work, float w_lane)
 {
-    int total = w_lane;
+    float total = w_lane;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1)
         total += __shfl_xor(total, o);
-    total = __builtin_amdgcn_readfirstlane(total);
-    const float share = (float)a.n_cu * (float)own_work / ((float)units * (float)(total > 0 ? total : 1));
-    return share >= 1.f ? (uint32_t)share : 1u;
+    total = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(total)));
+    const float share = (float)a.n_cu * (float)own_work / ((float)units * (total > 0.f ? total : 1.f));
+    return share >= 1.f ? (share < 64.f ? (uint32_t)share : 64u) : 1u;
 }
 
 // 16 code bytes of one lane.  Codes that are read once per launch are loaded with the
