@@ -94,7 +94,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     const bool has_recent = a.recent_k != nullptr && a.recent_len != nullptr;
     const int n_vec = a.ctx_len[b + zero];
     const int r_vec = (has_recent ? a.recent_len : a.ctx_len)[b + zero];
-    const float w_lane = a.B > 1 ? batch_work_lane(a, has_recent, lane) : 0.f;
+    const float w_lane = (a.B > 1 && a.S > 1) ? batch_work_lane(a, has_recent, lane) : 0.f;  // one launched split: nothing to cap
 
     // ---- prologue: LUT[c][x] for x = 0..63 (for M = 32 columns x and x+32 hold the same
     // subspace), and the value codebook image.  Order matters at this time scale:
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(NW * 64) void pq_decode_kernel(const pq_decode_args
     // so a short sequence in a long cache uses the first few splits only and the others leave here, before
     // they build tables (every workgroup of the row computes the same count; the merge expects that many).
     uint32_t want = nblk / 4u > (uint32_t)R / 16u ? nblk / 4u : (uint32_t)R / 16u;  // ... or 16 recent rows
-    if (a.B > 1) {  // ... and in a batch no more than the sequence's share of the compute units
+    if (a.B > 1 && a.S > 1) {  // ... and in a batch no more than the sequence's share of the compute units
         const uint32_t cap = live_split_cap(a, a.Hq, N + R, w_lane);
         want = want < cap ? want : cap;
     }

@@ -120,7 +120,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     const bool has_recent = a.recent_k != nullptr && a.recent_len != nullptr;
     const int n_vec = a.ctx_len[b + zero];
     const int r_vec = (has_recent ? a.recent_len : a.ctx_len)[b + zero];
-    const float w_lane = a.B > 1 ? batch_work_lane(a, has_recent, lane) : 0.f;
+    const float w_lane = (a.B > 1 && a.S > 1) ? batch_work_lane(a, has_recent, lane) : 0.f;  // one launched split: nothing to cap
 
     // ---- prologue: both codebook images and the group's queries; table loads first, bare
     // barrier, then the first code block (see the per-head kernel for why)
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(GNW * 64) void pq_decode_grouped_kernel(const pq_de
     // live splits follow the length (at least 4 blocks or 16 recent rows each); the others leave before the images
     // are staged
     uint32_t want = nblk / 4u > (uint32_t)R / 16u ? nblk / 4u : (uint32_t)R / 16u;  // ... or 16 recent rows
-    if (a.B > 1) {  // ... and in a batch no more than the sequence's share of the compute units
+    if (a.B > 1 && a.S > 1) {  // ... and in a batch no more than the sequence's share of the compute units
         const uint32_t cap = live_split_cap(a, a.Hkv * a.n_sub, N + R, w_lane);
         want = want < cap ? want : cap;
     }
